@@ -1,0 +1,177 @@
+/*
+ * rtn.h -- C ABI of the MI355X (gfx950) library for weight-only round-to-nearest (RTN)
+ * quantised linear layers: the load-time quantise-and-pack pass and the fused
+ * dequantise-GEMM used in token generation, plus the selective-precision dispatch.
+ *
+ * Paper: "Is (Selective) Round-To-Nearest Quantization All You Need?" (arXiv 2505.15909).
+ * Each entry point cites the passage that defines the operation it performs.
+ *
+ * General conventions
+ *   - Every pointer named dev_* is DEVICE memory (HIP global memory of the current device);
+ *     everything else is host memory.  The caller owns every buffer.  Unless an entry says
+ *     otherwise the library allocates nothing, frees nothing and never synchronises: all
+ *     work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream) and is complete when that stream reaches the point after the call.
+ *   - All device pointers must be 16-byte aligned.
+ *   - Every call validates its arguments on the host before launching anything and
+ *     returns an rtn_status; nothing aborts and nothing throws.  A HIP launch failure is
+ *     reported as RTN_ERR_HIP.
+ *   - Inputs must be finite fp16 values (NaN / Inf give unspecified results).
+ *   - Shapes: W is [N, K] (N output channels, K input channels, row-major), activations
+ *     A are [M, K] row-major, outputs C are [M, N] row-major, all IEEE binary16.
+ *     N % 16 == 0.  K % 512 == 0 for 4-bit, K % 256 == 0 for 8-bit (one k-chunk of the
+ *     GEMM kernels).  group_size g: g == K (or g <= 0) means one scale per output channel;
+ *     otherwise g must be 128, 256, 512 or a multiple of 512 dividing K for 4-bit and 64,
+ *     128, 256 or a multiple of 256 dividing K for 8-bit.
+ *   - Scales are fp16 [N, K/g] row-major (group j of row n covers columns j*g .. j*g+g-1):
+ *     the sub-channel grouping of Section 2.2.
+ *
+ * Packed weight layout (layout version 1; Section 5: weights are reshuffled once at load
+ * into the layout the kernel expects -- this one is designed for gfx950, not Marlin's):
+ *   The code matrix is cut into tiles of 16 rows x TK columns, TK = 128 (4-bit) or
+ *   64 (8-bit); a tile is 1024 bytes; tiles are stored row-tile-major [N/16][K/TK].
+ *   Inside a tile the 16-byte chunk number l (0..63; one per wavefront lane, so a
+ *   wavefront reads a tile with one fully coalesced 16-byte-per-lane load) belongs to row
+ *   l % 16 and column-quarter kq = l / 16.
+ *     4-bit: the chunk is four little-endian 32-bit words t = 0..3; word t holds the 8
+ *            codes of columns 32 t + 8 kq + e (e = 0..7), each stored as q + 8 in nibble
+ *            number {0,4,1,5,2,6,3,7}[e] (nibble p = bits 4p..4p+3), the order in which a
+ *            two-at-a-time mask-and-or unpack produces them.
+ *     8-bit: chunk byte 8 t + e (t = 0..1, e = 0..7) holds column 32 t + 8 kq + e as q + 128.
+ *   Each (lane, word) therefore carries the 8 consecutive-k values one lane feeds to one
+ *   16x16x32 fp16 MFMA.
+ */
+#ifndef RTN_H_
+#define RTN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RTN_OK = 0,
+    RTN_ERR_NULL = 1,      /* a required pointer is NULL */
+    RTN_ERR_BITS = 2,      /* bits is not 4 or 8 */
+    RTN_ERR_GROUP = 3,     /* group_size not supported for this K / bits */
+    RTN_ERR_SHAPE = 4,     /* M, N or K not supported (see conventions) */
+    RTN_ERR_ALIGN = 5,     /* a device pointer is not 16-byte aligned */
+    RTN_ERR_WORKSPACE = 6, /* workspace smaller than rtn_workspace_nbytes() */
+    RTN_ERR_CONFIG = 7,    /* explicit kernel configuration invalid for this problem */
+    RTN_ERR_HIP = 8        /* the HIP runtime reported an error at launch */
+} rtn_status;
+
+/* Scale rule flags of rtn_quantize.  Eq. 2 of Section 2.2 defines S = 2 max|r| / (2^b - 1)
+ * = max|r| / (2^(b-1) - 0.5); the default of this library is S = max|r| / (2^(b-1) - 1),
+ * under which the group maximum maps exactly onto +-(2^(b-1) - 1) and no code is clamped. */
+enum { RTN_SCALE_QMAX = 0, RTN_SCALE_EQ2 = 1 };
+
+/* Horizontal selection policies of Section 4.1. */
+enum { RTN_POLICY_FIRST = 0, RTN_POLICY_LAST = 1, RTN_POLICY_MIDDLE = 2 };
+
+const char* rtn_status_str(rtn_status s);
+int rtn_layout_version(void);
+
+/* Sizes in bytes of the buffers the caller must provide; 0 if the arguments are invalid.
+ * qweight: N*K*bits/8.  scales: N*(K/g)*2.  workspace (rtn_linear, rtn_layer_forward):
+ * fp32 split-K partial sums; an upper bound over every configuration the library may
+ * choose for this problem; never more than a few MiB. */
+size_t rtn_qweight_nbytes(int64_t N, int64_t K, int bits);
+size_t rtn_scales_nbytes(int64_t N, int64_t K, int group_size);
+size_t rtn_workspace_nbytes(int64_t M, int64_t N, int64_t K, int bits, int group_size);
+
+/* Load-time RTN quantise-and-pack (Section 2.2, Eq. 1 and Eq. 2, applied per group of g
+ * consecutive input columns of every output row; Section 5: done once per weight tensor
+ * while loading).  For every group: amax = max|w|; S = fp16(amax / D) with D per `flags`;
+ * q = clamp(round_half_even(w / S), -2^(b-1), 2^(b-1)-1), with S the stored fp16 value;
+ * a group whose S is zero gets all-zero codes.  Results are bit-exact and deterministic.
+ *   dev_W        in   fp16 [N, K]
+ *   dev_qweight  out  rtn_qweight_nbytes() bytes, packed layout above
+ *   dev_scales   out  fp16 [N, K/g]
+ */
+rtn_status rtn_quantize(const void* dev_W, int64_t N, int64_t K, int bits, int group_size, int flags,
+                        void* dev_qweight, void* dev_scales, void* stream);
+
+/* Fused dequantise-GEMM of the weight-only quantised linear layer (Sections 2.3 and 5:
+ * 16-bit activations times 4- or 8-bit weights, W4A16 / W8A16, for the small batches of
+ * token generation):  C[m, n] = fp16( sum_k A[m, k] * q[n, k] * S[n, k / g] ), products and
+ * sums in fp32 (codes enter the matrix cores exactly; the scale multiplies fp32 group
+ * partial sums).  Any M >= 1; the path (wavefront-level skinny kernel with split-K for
+ * small M, wider MFMA tiles for larger M) is chosen from M, N, K.  Deterministic: the same
+ * inputs give the same output bits (split-K partials are summed in a fixed order).
+ *   dev_A          in   fp16 [M, K]
+ *   dev_qweight    in   packed codes from rtn_quantize
+ *   dev_scales     in   fp16 [N, K/g]
+ *   dev_C          out  fp16 [M, N]
+ *   dev_workspace  scratch, >= rtn_workspace_nbytes(M, N, K, bits, g); contents undefined
+ *                  before and after; calls that overlap in time need distinct workspaces
+ */
+rtn_status rtn_linear(const void* dev_A, int64_t M, const void* dev_qweight, const void* dev_scales,
+                      int64_t N, int64_t K, int bits, int group_size, void* dev_C,
+                      void* dev_workspace, size_t workspace_nbytes, void* stream);
+
+/* Explicit kernel configuration for rtn_linear_ex (tuning sweeps and tests of every path).
+ * A zeroed struct means "choose automatically", field by field. */
+typedef struct {
+    int path;      /* 0 auto, 1 MFMA skinny kernel, 2 vector-ALU dot-product kernel (M <= 4) */
+    int r_tiles;   /* 16-row weight tiles per wavefront: 1, 2 or 4 */
+    int waves_n;   /* wavefronts of a workgroup along N (share the staged activations) */
+    int waves_k;   /* wavefronts of a workgroup along K (in-workgroup split-K) */
+    int split_k;   /* workgroups along K (global split-K, reduced through the workspace) */
+} rtn_linear_cfg;
+
+rtn_status rtn_linear_ex(const void* dev_A, int64_t M, const void* dev_qweight, const void* dev_scales,
+                         int64_t N, int64_t K, int bits, int group_size, void* dev_C,
+                         void* dev_workspace, size_t workspace_nbytes, void* stream,
+                         const rtn_linear_cfg* cfg);
+
+/* Reports the configuration rtn_linear would use (host only, launches nothing). */
+rtn_status rtn_linear_query(int64_t M, int64_t N, int64_t K, int bits, int group_size, rtn_linear_cfg* out);
+
+/* Test / debug hook: packed codes -> int8 [N, K] row-major (the inverse of the layout). */
+rtn_status rtn_unpack(const void* dev_qweight, int64_t N, int64_t K, int bits, void* dev_codes_i8, void* stream);
+
+/* Dequantise to 16 bit: W'[n, k] = fp16(q[n, k] * S[n, k / g]) -- the first half of the
+ * large-input path of Section 5 (dequantise, then a dense 16-bit GEMM). */
+rtn_status rtn_dequantize(const void* dev_qweight, const void* dev_scales, int64_t N, int64_t K, int bits,
+                          int group_size, void* dev_W_fp16, void* stream);
+
+/* One linear module of a Transformer layer with its own precision (Section 4: each of the
+ * four linear modules of a layer may be kept at 8 bit while the rest is at 4 bit). */
+typedef struct {
+    const void* dev_A;        /* fp16 [M, K] */
+    int64_t M;
+    const void* dev_qweight;
+    const void* dev_scales;
+    int64_t N, K;
+    int bits;                 /* 4 or 8 */
+    int group_size;
+    void* dev_C;              /* fp16 [M, N] */
+} rtn_module;
+
+/* Selective-precision dispatch (Section 4.3, Section 5: RTN-~5 / RTN-~6 models mix 4- and
+ * 8-bit modules): runs the n_mods modules in order on `stream`, each with the kernel
+ * instantiation of its own (bits, group_size).  The workspace must cover the largest
+ * rtn_workspace_nbytes() of the modules; it is reused, which is safe because the launches
+ * are ordered on one stream.  Stops at, and returns, the first error. */
+rtn_status rtn_layer_forward(const rtn_module* mods, int n_mods, void* dev_workspace,
+                             size_t workspace_nbytes, void* stream);
+
+/* Hybrid selection rule of Section 4.3: bits of module `module_id` (1 = QKV projection,
+ * 2 = attention output projection, 3 and 4 = feed-forward, numbering of Section 4.2) of
+ * 0-based `layer` when X layers chosen by `policy` (first / last / middle, Section 4.1)
+ * keep the modules in `module_mask` (bit i-1 set = module i) at 8 bit and everything else
+ * is 4 bit.  Returns 4 or 8, or -1 on invalid arguments.  Host only. */
+int rtn_plan_bits(int layer, int n_layers, int module_id, int policy, int X, unsigned module_mask);
+
+/* Average bits per weight of such a plan (Section 4.3: "effectively quantized into 5 bit");
+ * module_params[i] = weights of module i+1 in one layer.  Returns -1 on invalid arguments. */
+double rtn_plan_effective_bits(int n_layers, const int64_t module_params[4], int policy, int X,
+                               unsigned module_mask);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RTN_H_ */

@@ -1,0 +1,222 @@
+"""Thin ctypes binding over the C ABI of include/rtn.h.
+
+Argument marshalling only: every step of the path runs in the HIP kernels of the shared
+library.  PyTorch supplies device memory and the current stream, nothing else.  There is
+no fallback: if the library cannot be loaded, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+from . import build as _build
+
+RTN_SCALE_QMAX, RTN_SCALE_EQ2 = 0, 1
+RTN_POLICY_FIRST, RTN_POLICY_LAST, RTN_POLICY_MIDDLE = 0, 1, 2
+POLICY = {"first": RTN_POLICY_FIRST, "last": RTN_POLICY_LAST, "middle": RTN_POLICY_MIDDLE}
+
+
+class RtnError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: rtn_status {status} ({_lib.rtn_status_str(status).decode()})")
+
+
+class rtn_linear_cfg(C.Structure):
+    _fields_ = [("path", C.c_int), ("r_tiles", C.c_int), ("waves_n", C.c_int),
+                ("waves_k", C.c_int), ("split_k", C.c_int)]
+
+
+class rtn_module(C.Structure):
+    _fields_ = [("dev_A", C.c_void_p), ("M", C.c_int64), ("dev_qweight", C.c_void_p),
+                ("dev_scales", C.c_void_p), ("N", C.c_int64), ("K", C.c_int64),
+                ("bits", C.c_int), ("group_size", C.c_int), ("dev_C", C.c_void_p)]
+
+
+def _load() -> C.CDLL:
+    path = _build.LIB_PATH
+    if not os.path.exists(path):
+        _build.build_library()
+    lib = C.CDLL(path)
+    vp, i64, ci, sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
+    lib.rtn_status_str.restype = C.c_char_p
+    lib.rtn_status_str.argtypes = [ci]
+    lib.rtn_layout_version.restype = ci
+    lib.rtn_qweight_nbytes.restype = sz
+    lib.rtn_qweight_nbytes.argtypes = [i64, i64, ci]
+    lib.rtn_scales_nbytes.restype = sz
+    lib.rtn_scales_nbytes.argtypes = [i64, i64, ci]
+    lib.rtn_workspace_nbytes.restype = sz
+    lib.rtn_workspace_nbytes.argtypes = [i64, i64, i64, ci, ci]
+    lib.rtn_quantize.restype = ci
+    lib.rtn_quantize.argtypes = [vp, i64, i64, ci, ci, ci, vp, vp, vp]
+    lib.rtn_linear.restype = ci
+    lib.rtn_linear.argtypes = [vp, i64, vp, vp, i64, i64, ci, ci, vp, vp, sz, vp]
+    lib.rtn_linear_ex.restype = ci
+    lib.rtn_linear_ex.argtypes = [vp, i64, vp, vp, i64, i64, ci, ci, vp, vp, sz, vp, C.POINTER(rtn_linear_cfg)]
+    lib.rtn_linear_query.restype = ci
+    lib.rtn_linear_query.argtypes = [i64, i64, i64, ci, ci, C.POINTER(rtn_linear_cfg)]
+    lib.rtn_unpack.restype = ci
+    lib.rtn_unpack.argtypes = [vp, i64, i64, ci, vp, vp]
+    lib.rtn_dequantize.restype = ci
+    lib.rtn_dequantize.argtypes = [vp, vp, i64, i64, ci, ci, vp, vp]
+    lib.rtn_layer_forward.restype = ci
+    lib.rtn_layer_forward.argtypes = [C.POINTER(rtn_module), ci, vp, sz, vp]
+    lib.rtn_plan_bits.restype = ci
+    lib.rtn_plan_bits.argtypes = [ci, ci, ci, ci, ci, C.c_uint]
+    lib.rtn_plan_effective_bits.restype = C.c_double
+    lib.rtn_plan_effective_bits.argtypes = [ci, C.POINTER(i64), ci, ci, C.c_uint]
+    return lib
+
+
+_lib = _load()
+EXPORTS = ["rtn_status_str", "rtn_layout_version", "rtn_qweight_nbytes", "rtn_scales_nbytes",
+           "rtn_workspace_nbytes", "rtn_quantize", "rtn_linear", "rtn_linear_ex", "rtn_linear_query",
+           "rtn_unpack", "rtn_dequantize", "rtn_layer_forward", "rtn_plan_bits", "rtn_plan_effective_bits"]
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise RtnError(status, what)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _dev_fp16(t: torch.Tensor, name: str):
+    if not (t.is_cuda and t.dtype == torch.float16 and t.is_contiguous() and t.dim() == 2):
+        raise ValueError(f"{name} must be a contiguous fp16 CUDA matrix")
+
+
+def rtn_layout_version() -> int:
+    return _lib.rtn_layout_version()
+
+
+def rtn_qweight_nbytes(N, K, bits):
+    return _lib.rtn_qweight_nbytes(N, K, bits)
+
+
+def rtn_scales_nbytes(N, K, group_size):
+    return _lib.rtn_scales_nbytes(N, K, group_size)
+
+
+def rtn_workspace_nbytes(M, N, K, bits, group_size):
+    return _lib.rtn_workspace_nbytes(M, N, K, bits, group_size)
+
+
+def rtn_quantize(W: torch.Tensor, bits: int, group_size: int, flags: int = RTN_SCALE_QMAX, out=None):
+    """W fp16 [N, K] on the GPU -> (qweight uint8 [N*K*bits/8], scales fp16 [N, K/g])."""
+    _dev_fp16(W, "W")
+    N, K = W.shape
+    g = K if group_size <= 0 else group_size
+    if out is None:
+        nb = _lib.rtn_qweight_nbytes(N, K, bits)
+        ns = _lib.rtn_scales_nbytes(N, K, g)
+        if nb == 0 or ns == 0:
+            _check(_lib.rtn_quantize(W.data_ptr(), N, K, bits, group_size, flags, 1, 1, None), "rtn_quantize")
+        qweight = torch.empty(nb, dtype=torch.uint8, device=W.device)
+        scales = torch.empty((N, K // g), dtype=torch.float16, device=W.device)
+    else:
+        qweight, scales = out
+    _check(_lib.rtn_quantize(W.data_ptr(), N, K, bits, group_size, flags, qweight.data_ptr(),
+                             scales.data_ptr(), _stream()), "rtn_quantize")
+    return qweight, scales
+
+
+def make_cfg(cfg):
+    if cfg is None:
+        return None
+    if isinstance(cfg, rtn_linear_cfg):
+        return cfg
+    return rtn_linear_cfg(**cfg)
+
+
+def rtn_linear(A: torch.Tensor, qweight: torch.Tensor, scales: torch.Tensor, bits: int, group_size: int,
+               out: torch.Tensor = None, workspace: torch.Tensor = None, cfg=None) -> torch.Tensor:
+    """A fp16 [M, K], packed qweight, scales fp16 [N, K/g] -> C fp16 [M, N]."""
+    _dev_fp16(A, "A")
+    M, K = A.shape
+    N = scales.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=A.device)
+    if workspace is None:
+        workspace = torch.empty(max(256, _lib.rtn_workspace_nbytes(M, N, K, bits, group_size)),
+                                dtype=torch.uint8, device=A.device)
+    c = make_cfg(cfg)
+    st = _lib.rtn_linear_ex(A.data_ptr(), M, qweight.data_ptr(), scales.data_ptr(), N, K, bits, group_size,
+                            out.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                            _stream(), C.byref(c) if c is not None else None)
+    _check(st, "rtn_linear")
+    return out
+
+
+def rtn_linear_query(M, N, K, bits, group_size) -> dict:
+    c = rtn_linear_cfg()
+    _check(_lib.rtn_linear_query(M, N, K, bits, group_size, C.byref(c)), "rtn_linear_query")
+    return {k: getattr(c, k) for k, _ in rtn_linear_cfg._fields_}
+
+
+def rtn_unpack(qweight: torch.Tensor, N: int, K: int, bits: int) -> torch.Tensor:
+    codes = torch.empty((N, K), dtype=torch.int8, device=qweight.device)
+    _check(_lib.rtn_unpack(qweight.data_ptr(), N, K, bits, codes.data_ptr(), _stream()), "rtn_unpack")
+    return codes
+
+
+def rtn_dequantize(qweight: torch.Tensor, scales: torch.Tensor, K: int, bits: int, group_size: int) -> torch.Tensor:
+    N = scales.shape[0]
+    W = torch.empty((N, K), dtype=torch.float16, device=qweight.device)
+    _check(_lib.rtn_dequantize(qweight.data_ptr(), scales.data_ptr(), N, K, bits, group_size, W.data_ptr(),
+                               _stream()), "rtn_dequantize")
+    return W
+
+
+class LayerPlan:
+    """A prepared rtn_layer_forward call: the module descriptor array is built once."""
+
+    def __init__(self, modules, workspace: torch.Tensor = None):
+        """modules: list of dicts {A, qweight, scales, bits, group_size, C}."""
+        self.n = len(modules)
+        self.arr = (rtn_module * self.n)()
+        self.keep = modules
+        need = 256
+        for i, m in enumerate(modules):
+            M, K = m["A"].shape
+            N = m["scales"].shape[0]
+            self.arr[i] = rtn_module(m["A"].data_ptr(), M, m["qweight"].data_ptr(), m["scales"].data_ptr(),
+                                     N, K, m["bits"], m["group_size"], m["C"].data_ptr())
+            need = max(need, _lib.rtn_workspace_nbytes(M, N, K, m["bits"], m["group_size"]))
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=modules[0]["A"].device)
+        self.workspace = workspace
+
+    def run(self):
+        _check(_lib.rtn_layer_forward(self.arr, self.n, self.workspace.data_ptr(), self.workspace.numel(),
+                                      _stream()), "rtn_layer_forward")
+
+
+def rtn_layer_forward(modules, workspace: torch.Tensor = None):
+    LayerPlan(modules, workspace).run()
+
+
+def rtn_plan_bits(layer, n_layers, module_id, policy, X, modules=(1, 2, 3, 4)) -> int:
+    mask = 0
+    for m in modules:
+        mask |= 1 << (m - 1)
+    pol = POLICY[policy] if isinstance(policy, str) else policy
+    return _lib.rtn_plan_bits(layer, n_layers, module_id, pol, X, mask)
+
+
+def rtn_plan_effective_bits(n_layers, module_params, policy, X, modules=(1, 2, 3, 4)) -> float:
+    mask = 0
+    for m in modules:
+        mask |= 1 << (m - 1)
+    pol = POLICY[policy] if isinstance(policy, str) else policy
+    arr = (C.c_int64 * 4)(*[int(v) for v in module_params])
+    return _lib.rtn_plan_effective_bits(n_layers, arr, pol, X, mask)

@@ -1,0 +1,268 @@
+// C ABI of the library (see include/rtn.h): argument validation, kernel-plan selection,
+// selective-precision dispatch.  No device code here.
+#include "../../include/rtn.h"
+#include "rtn_internal.h"
+
+#include <stdlib.h>
+#include <string.h>
+
+using rtn::LinearArgs;
+using rtn::LinearPlan;
+
+namespace {
+
+constexpr size_t kWorkspaceCap = (size_t)16 << 20;     // split-K partials never exceed this
+constexpr int kMaxSplitK = 16;
+constexpr size_t kMaxLds = 64 * 1024;
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+
+int chunk_k(int bits) { return bits == 4 ? 512 : 256; }
+int tile_k(int bits) { return bits == 4 ? 128 : 64; }
+
+// Normalises group_size (<= 0 or K means per-channel) and checks it.
+rtn_status check_problem(int64_t N, int64_t K, int bits, int group_size, int64_t* g_out) {
+    if (bits != 4 && bits != 8) return RTN_ERR_BITS;
+    if (N <= 0 || K <= 0 || N % 16 != 0 || K % chunk_k(bits) != 0) return RTN_ERR_SHAPE;
+    if (N > (int64_t)1 << 30 || K > (int64_t)1 << 30) return RTN_ERR_SHAPE;
+    int64_t g = (group_size <= 0) ? K : group_size;
+    if (g > K || K % g != 0) return RTN_ERR_GROUP;
+    const int ck = chunk_k(bits), tk = tile_k(bits);
+    if (g < ck) {
+        if (g != tk && g != 2 * tk && g != 4 * tk) return RTN_ERR_GROUP;
+    } else if (g % ck != 0) {
+        return RTN_ERR_GROUP;
+    }
+    *g_out = g;
+    return RTN_OK;
+}
+
+size_t workspace_bound(int64_t M, int64_t N) {
+    size_t one = (size_t)M * (size_t)N * sizeof(float);
+    size_t want = one * kMaxSplitK;
+    if (want > kWorkspaceCap) want = kWorkspaceCap;
+    if (want < 256) want = 256;
+    return (want + 255) & ~(size_t)255;
+}
+
+// Default plan.  Small batches split K across the wavefronts of a workgroup so that many
+// wavefronts stream disjoint parts of the weights; larger batches put the wavefronts side by
+// side along N so that they share the staged activations.
+LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits) {
+    LinearPlan p;
+    const int rows = (int)(M < 16 ? M : 16);
+    const int cap = (bits == 4) ? 4 : 8;       // activation rows one N-wavefront can stage
+    p.path = 1;
+    p.m_blocks = (int)((M + 15) / 16);
+    p.waves_n = 1;
+    while (p.waves_n * cap < rows) p.waves_n *= 2;
+    p.waves_k = 4 / p.waves_n;
+    if (p.waves_k < 1) p.waves_k = 1;
+    p.r_tiles = (rows <= 4) ? 1 : 2;
+    const int64_t NT = N / 16, KC = K / chunk_k(bits);
+    while (p.waves_k > 1 && p.waves_k > KC) p.waves_k /= 2;
+    int64_t blocks_n = (NT + p.waves_n * p.r_tiles - 1) / (p.waves_n * p.r_tiles);
+    int64_t split = 1;
+    const int64_t target = 1024;               // ~4 workgroups per compute unit
+    while (split * 2 <= kMaxSplitK && blocks_n * p.m_blocks * split < target &&
+           KC / (split * 2) >= p.waves_k &&
+           (size_t)M * N * sizeof(float) * (split * 2) <= kWorkspaceCap)
+        split *= 2;
+    p.split_k = (int)split;
+    return p;
+}
+
+rtn_status resolve_plan(const LinearArgs& a, const rtn_linear_cfg* cfg, size_t workspace_nbytes, LinearPlan* out) {
+    LinearPlan p = auto_plan(a.M, a.N, a.K, a.bits);
+    if (cfg) {
+        if (cfg->path) p.path = cfg->path;
+        if (cfg->r_tiles) p.r_tiles = cfg->r_tiles;
+        if (cfg->waves_n) p.waves_n = cfg->waves_n;
+        if (cfg->waves_k) p.waves_k = cfg->waves_k;
+        if (cfg->split_k) p.split_k = cfg->split_k;
+    }
+    const int rows = (int)(a.M < 16 ? a.M : 16);
+    const int cap = (a.bits == 4) ? 4 : 8;
+    const int64_t KC = a.K / chunk_k(a.bits);
+    if (p.path != 1) return RTN_ERR_CONFIG;
+    if (p.r_tiles != 1 && p.r_tiles != 2 && p.r_tiles != 4) return RTN_ERR_CONFIG;
+    if (!pow2(p.waves_n) || !pow2(p.waves_k) || p.waves_n * p.waves_k > 8) return RTN_ERR_CONFIG;
+    if (p.waves_n * cap < rows) return RTN_ERR_CONFIG;           // staging capacity
+    if (p.split_k < 1 || p.split_k > kMaxSplitK || p.split_k > KC) return RTN_ERR_CONFIG;
+    if (rtn::linear_lds_bytes(a, p) > kMaxLds) return RTN_ERR_CONFIG;
+    if (p.split_k > 1) {
+        const size_t need = (size_t)a.M * a.N * sizeof(float) * p.split_k;
+        if (a.workspace == nullptr || workspace_nbytes < need) return RTN_ERR_WORKSPACE;
+    }
+    *out = p;
+    return RTN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* rtn_status_str(rtn_status s) {
+    switch (s) {
+        case RTN_OK: return "ok";
+        case RTN_ERR_NULL: return "null pointer";
+        case RTN_ERR_BITS: return "bits must be 4 or 8";
+        case RTN_ERR_GROUP: return "unsupported group size";
+        case RTN_ERR_SHAPE: return "unsupported shape";
+        case RTN_ERR_ALIGN: return "device pointer not 16-byte aligned";
+        case RTN_ERR_WORKSPACE: return "workspace too small";
+        case RTN_ERR_CONFIG: return "invalid kernel configuration";
+        case RTN_ERR_HIP: return "HIP launch error";
+    }
+    return "unknown status";
+}
+
+int rtn_layout_version(void) { return 1; }
+
+size_t rtn_qweight_nbytes(int64_t N, int64_t K, int bits) {
+    int64_t g;
+    if (check_problem(N, K, bits, 0, &g) != RTN_OK) return 0;
+    return (size_t)N * (size_t)K * (size_t)bits / 8;
+}
+
+size_t rtn_scales_nbytes(int64_t N, int64_t K, int group_size) {
+    if (N <= 0 || K <= 0) return 0;
+    int64_t g = group_size <= 0 ? K : group_size;
+    if (g > K || K % g != 0) return 0;
+    return (size_t)N * (size_t)(K / g) * 2;
+}
+
+size_t rtn_workspace_nbytes(int64_t M, int64_t N, int64_t K, int bits, int group_size) {
+    int64_t g;
+    if (M <= 0 || check_problem(N, K, bits, group_size, &g) != RTN_OK) return 0;
+    return workspace_bound(M, N);
+}
+
+rtn_status rtn_quantize(const void* dev_W, int64_t N, int64_t K, int bits, int group_size, int flags,
+                        void* dev_qweight, void* dev_scales, void* stream) {
+    if (!dev_W || !dev_qweight || !dev_scales) return RTN_ERR_NULL;
+    int64_t g;
+    rtn_status st = check_problem(N, K, bits, group_size, &g);
+    if (st != RTN_OK) return st;
+    if (flags != RTN_SCALE_QMAX && flags != RTN_SCALE_EQ2) return RTN_ERR_CONFIG;
+    if (!aligned16(dev_W) || !aligned16(dev_qweight) || !aligned16(dev_scales)) return RTN_ERR_ALIGN;
+    const float qmax = (float)((1 << (bits - 1)) - 1);
+    const float divisor = (flags == RTN_SCALE_EQ2) ? qmax + 0.5f : qmax;
+    hipError_t e = rtn::launch_quantize(dev_W, N, K, bits, g, divisor, dev_qweight, dev_scales,
+                                        static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RTN_OK : RTN_ERR_HIP;
+}
+
+rtn_status rtn_linear_ex(const void* dev_A, int64_t M, const void* dev_qweight, const void* dev_scales,
+                         int64_t N, int64_t K, int bits, int group_size, void* dev_C,
+                         void* dev_workspace, size_t workspace_nbytes, void* stream,
+                         const rtn_linear_cfg* cfg) {
+    if (!dev_A || !dev_qweight || !dev_scales || !dev_C) return RTN_ERR_NULL;
+    int64_t g;
+    rtn_status st = check_problem(N, K, bits, group_size, &g);
+    if (st != RTN_OK) return st;
+    if (M <= 0 || M > (1 << 20)) return RTN_ERR_SHAPE;
+    if (!aligned16(dev_A) || !aligned16(dev_qweight) || !aligned16(dev_scales) || !aligned16(dev_C) ||
+        !aligned16(dev_workspace))
+        return RTN_ERR_ALIGN;
+    LinearArgs a;
+    a.A = dev_A; a.qweight = dev_qweight; a.scales = dev_scales; a.C = dev_C;
+    a.workspace = static_cast<float*>(dev_workspace);
+    a.M = M; a.N = N; a.K = K; a.g = g; a.bits = bits;
+    LinearPlan p;
+    st = resolve_plan(a, cfg, workspace_nbytes, &p);
+    if (st != RTN_OK) return st;
+    hipError_t e = rtn::launch_linear(a, p, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RTN_OK : RTN_ERR_HIP;
+}
+
+rtn_status rtn_linear(const void* dev_A, int64_t M, const void* dev_qweight, const void* dev_scales,
+                      int64_t N, int64_t K, int bits, int group_size, void* dev_C,
+                      void* dev_workspace, size_t workspace_nbytes, void* stream) {
+    return rtn_linear_ex(dev_A, M, dev_qweight, dev_scales, N, K, bits, group_size, dev_C, dev_workspace,
+                         workspace_nbytes, stream, nullptr);
+}
+
+rtn_status rtn_linear_query(int64_t M, int64_t N, int64_t K, int bits, int group_size, rtn_linear_cfg* out) {
+    if (!out) return RTN_ERR_NULL;
+    int64_t g;
+    rtn_status st = check_problem(N, K, bits, group_size, &g);
+    if (st != RTN_OK) return st;
+    if (M <= 0) return RTN_ERR_SHAPE;
+    LinearPlan p = auto_plan(M, N, K, bits);
+    out->path = p.path; out->r_tiles = p.r_tiles; out->waves_n = p.waves_n;
+    out->waves_k = p.waves_k; out->split_k = p.split_k;
+    return RTN_OK;
+}
+
+rtn_status rtn_unpack(const void* dev_qweight, int64_t N, int64_t K, int bits, void* dev_codes_i8, void* stream) {
+    if (!dev_qweight || !dev_codes_i8) return RTN_ERR_NULL;
+    int64_t g;
+    rtn_status st = check_problem(N, K, bits, 0, &g);
+    if (st != RTN_OK) return st;
+    if (!aligned16(dev_qweight) || !aligned16(dev_codes_i8)) return RTN_ERR_ALIGN;
+    hipError_t e = rtn::launch_unpack(dev_qweight, nullptr, N, K, bits, K, false, dev_codes_i8,
+                                      static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RTN_OK : RTN_ERR_HIP;
+}
+
+rtn_status rtn_dequantize(const void* dev_qweight, const void* dev_scales, int64_t N, int64_t K, int bits,
+                          int group_size, void* dev_W_fp16, void* stream) {
+    if (!dev_qweight || !dev_scales || !dev_W_fp16) return RTN_ERR_NULL;
+    int64_t g;
+    rtn_status st = check_problem(N, K, bits, group_size, &g);
+    if (st != RTN_OK) return st;
+    if (!aligned16(dev_qweight) || !aligned16(dev_scales) || !aligned16(dev_W_fp16)) return RTN_ERR_ALIGN;
+    hipError_t e = rtn::launch_unpack(dev_qweight, dev_scales, N, K, bits, g, true, dev_W_fp16,
+                                      static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RTN_OK : RTN_ERR_HIP;
+}
+
+rtn_status rtn_layer_forward(const rtn_module* mods, int n_mods, void* dev_workspace, size_t workspace_nbytes,
+                             void* stream) {
+    if (!mods) return RTN_ERR_NULL;
+    if (n_mods <= 0) return RTN_ERR_SHAPE;
+    for (int i = 0; i < n_mods; ++i) {
+        const rtn_module& m = mods[i];
+        rtn_status st = rtn_linear(m.dev_A, m.M, m.dev_qweight, m.dev_scales, m.N, m.K, m.bits, m.group_size,
+                                   m.dev_C, dev_workspace, workspace_nbytes, stream);
+        if (st != RTN_OK) return st;
+    }
+    return RTN_OK;
+}
+
+static int layer_selected(int layer, int n_layers, int policy, int X) {
+    int start;
+    switch (policy) {
+        case RTN_POLICY_FIRST: start = 0; break;
+        case RTN_POLICY_LAST: start = n_layers - X; break;
+        case RTN_POLICY_MIDDLE: start = (n_layers - X) / 2; break;
+        default: return -1;
+    }
+    return (layer >= start && layer < start + X) ? 1 : 0;
+}
+
+int rtn_plan_bits(int layer, int n_layers, int module_id, int policy, int X, unsigned module_mask) {
+    if (n_layers <= 0 || layer < 0 || layer >= n_layers || X < 0 || X > n_layers) return -1;
+    if (module_id < 1 || module_id > 4 || module_mask > 15u) return -1;
+    const int sel = layer_selected(layer, n_layers, policy, X);
+    if (sel < 0) return -1;
+    return (sel && (module_mask >> (module_id - 1) & 1u)) ? 8 : 4;
+}
+
+double rtn_plan_effective_bits(int n_layers, const int64_t module_params[4], int policy, int X,
+                               unsigned module_mask) {
+    if (!module_params || n_layers <= 0) return -1.0;
+    long double total = 0, bits = 0;
+    for (int l = 0; l < n_layers; ++l)
+        for (int m = 1; m <= 4; ++m) {
+            const int b = rtn_plan_bits(l, n_layers, m, policy, X, module_mask);
+            if (b < 0 || module_params[m - 1] < 0) return -1.0;
+            total += (long double)module_params[m - 1];
+            bits += (long double)module_params[m - 1] * b;
+        }
+    return total > 0 ? (double)(bits / total) : -1.0;
+}
+
+}  // extern "C"

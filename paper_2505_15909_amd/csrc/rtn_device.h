@@ -1,0 +1,90 @@
+// Device-side building blocks shared by the gfx950 kernels: packed-layout geometry and the
+// in-register unpack of 4-/8-bit codes to exact fp16 integers.
+//
+// Packed layout (layout version 1): tiles of 16 rows x TK columns (TK = 128 for 4-bit, 64 for
+// 8-bit), 1024 bytes each, stored [N/16][K/TK]; lane l of a wavefront owns the 16-byte chunk l
+// of a tile: row l % 16, column-quarter kq = l / 16; word/byte order as documented in rtn.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rtn {
+
+typedef _Float16 half_t;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+template <int BITS> struct Layout;
+template <> struct Layout<4> {
+    static constexpr int TK = 128;       // columns per 1 KiB tile
+    static constexpr int MFMA_PER_TILE = 4;
+    static constexpr int QMAX = 7;
+    static constexpr int QMIN = -8;
+    static constexpr int BIAS = 8;
+};
+template <> struct Layout<8> {
+    static constexpr int TK = 64;
+    static constexpr int MFMA_PER_TILE = 2;
+    static constexpr int QMAX = 127;
+    static constexpr int QMIN = -128;
+    static constexpr int BIAS = 128;
+};
+
+__device__ __forceinline__ half2_t as_half2(uint32_t u) { return __builtin_bit_cast(half2_t, u); }
+
+union Half8Words {
+    half8_t v;
+    half2_t h2[4];
+};
+
+// One 32-bit word of 4-bit codes (offset binary, nibble order {0,4,1,5,2,6,3,7}) -> the 8 fp16
+// values one lane feeds to one 16x16x32 MFMA.  0x6400 is fp16 1024, whose ulp is 1: or-ing a
+// nibble into the mantissa gives 1024 + n exactly (or 1024 + 16 n for a nibble sitting 4 bits
+// up), and one packed add / fma removes the offset exactly.  9 vector ops per 8 weights.
+__device__ __forceinline__ half8_t unpack_word4(uint32_t w) {
+    const uint32_t MAGIC = 0x64006400u;
+    const half2_t k1032 = {(half_t)1032.0f, (half_t)1032.0f};
+    const half2_t k16th = {(half_t)0.0625f, (half_t)0.0625f};
+    const half2_t k72 = {(half_t)-72.0f, (half_t)-72.0f};
+    uint32_t w8 = w >> 8;
+    Half8Words r;
+    r.h2[0] = as_half2((w & 0x000F000Fu) | MAGIC) - k1032;                              // nibbles 0,4
+    r.h2[1] = __builtin_elementwise_fma(as_half2((w & 0x00F000F0u) | MAGIC), k16th, k72);   // nibbles 1,5
+    r.h2[2] = as_half2((w8 & 0x000F000Fu) | MAGIC) - k1032;                             // nibbles 2,6
+    r.h2[3] = __builtin_elementwise_fma(as_half2((w8 & 0x00F000F0u) | MAGIC), k16th, k72);  // nibbles 3,7
+    return r.v;
+}
+
+// Two 32-bit words of 8-bit codes (offset binary, natural byte order) -> 8 fp16 values.
+// A byte permute places each byte under a 0x64 exponent byte (1024 + byte), one packed add
+// removes 1024 + 128.  8 vector ops per 8 weights.
+__device__ __forceinline__ half8_t unpack_words8(uint32_t w0, uint32_t w1) {
+    const half2_t k1152 = {(half_t)1152.0f, (half_t)1152.0f};
+    const uint32_t E = 0x64646464u;
+    Half8Words r;
+    r.h2[0] = as_half2(__builtin_amdgcn_perm(E, w0, 0x04010400u)) - k1152;
+    r.h2[1] = as_half2(__builtin_amdgcn_perm(E, w0, 0x04030402u)) - k1152;
+    r.h2[2] = as_half2(__builtin_amdgcn_perm(E, w1, 0x04010400u)) - k1152;
+    r.h2[3] = as_half2(__builtin_amdgcn_perm(E, w1, 0x04030402u)) - k1152;
+    return r.v;
+}
+
+// MFMA operand number i (0 .. MFMA_PER_TILE-1) of a 16-byte tile chunk.
+template <int BITS>
+__device__ __forceinline__ half8_t unpack_operand(const u32x4_t& chunk, int i) {
+    if constexpr (BITS == 4) {
+        return unpack_word4(chunk[i]);
+    } else {
+        return unpack_words8(chunk[2 * i], chunk[2 * i + 1]);
+    }
+}
+
+// Streaming (read-once) 16-byte load of packed weights.
+__device__ __forceinline__ u32x4_t load_stream16(const void* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+}
+
+}  // namespace rtn

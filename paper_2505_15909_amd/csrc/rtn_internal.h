@@ -1,0 +1,38 @@
+// Host-side interfaces between the C-ABI translation unit and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rtn {
+
+// Resolved launch configuration of the fused dequantise-GEMM.
+struct LinearPlan {
+    int path;       // 1 = MFMA skinny kernel, 2 = vector-ALU dot kernel
+    int r_tiles;    // 16-row weight tiles per wavefront
+    int waves_n;    // wavefronts along N per workgroup
+    int waves_k;    // wavefronts along K per workgroup
+    int split_k;    // workgroups along K
+    int m_blocks;   // 16-row blocks of activations (grid.z)
+};
+
+struct LinearArgs {
+    const void* A;
+    const void* qweight;
+    const void* scales;
+    void* C;
+    float* workspace;
+    int64_t M, N, K, g;
+    int bits;
+};
+
+hipError_t launch_quantize(const void* W, int64_t N, int64_t K, int bits, int64_t g, float divisor,
+                           void* qweight, void* scales, hipStream_t st);
+hipError_t launch_unpack(const void* qweight, const void* scales, int64_t N, int64_t K, int bits, int64_t g,
+                         bool dequant, void* out, hipStream_t st);
+hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t st);
+
+// LDS bytes the skinny kernel needs for a plan (activation staging, double buffered, and the
+// in-workgroup split-K reduction buffer, whichever is larger).
+size_t linear_lds_bytes(const LinearArgs& a, const LinearPlan& p);
+
+}  // namespace rtn

@@ -1,0 +1,60 @@
+"""Shared helpers of the GPU parity tests: workload definitions and comparison metrics."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import rtn_oracle as O
+from paper_2505_15909_amd import synth
+
+REL_FRO_TOL = 2e-3       # relative Frobenius error bound of the linear layer
+MAX_ABS_TOL = 1e-2       # max abs error bound ...
+HALF_ULP_REL = 2.0 ** -11  # ... plus one fp16 rounding of the result itself (|C| >= 8 has half-ulp >= 3.9e-3)
+
+
+def linear_errors(C_gpu: np.ndarray, C_ref: np.ndarray):
+    d = C_gpu.astype(np.float64) - C_ref
+    fro = float(np.linalg.norm(d) / max(np.linalg.norm(C_ref), 1e-300))
+    max_abs = float(np.max(np.abs(d))) if d.size else 0.0
+    excess = float(np.max(np.abs(d) - (MAX_ABS_TOL + HALF_ULP_REL * np.abs(C_ref)))) if d.size else -1.0
+    return fro, max_abs, excess
+
+
+def assert_linear_close(C_gpu, C_ref, what=""):
+    fro, max_abs, excess = linear_errors(C_gpu, C_ref)
+    assert fro <= REL_FRO_TOL, f"{what}: rel Frobenius {fro:.3e} > {REL_FRO_TOL}"
+    assert excess <= 0.0, f"{what}: max abs {max_abs:.3e} exceeds 1e-2 + 2^-11 |C|"
+    return fro, max_abs
+
+
+def tile_rows(row_tiles, N):
+    """Row indices of the given 16-row tiles."""
+    rows = np.concatenate([np.arange(t * 16, t * 16 + 16) for t in row_tiles])
+    assert rows.max() < N
+    return rows
+
+
+def packed_rows_image(packed: np.ndarray, row_tiles, K: int, bits: int) -> np.ndarray:
+    """Bytes of the given row tiles from a full packed image (tiles are row-tile-major)."""
+    per_tile_row = 16 * K * bits // 8
+    return np.concatenate([packed[t * per_tile_row:(t + 1) * per_tile_row] for t in row_tiles])
+
+
+def pick_row_tiles(N: int, count: int, seed: int):
+    NT = N // 16
+    if NT <= count:
+        return np.arange(NT)
+    rng = np.random.default_rng(seed)
+    picks = set(rng.choice(NT, size=count - 2, replace=False).tolist())
+    picks.update([0, NT - 1])                                   # always the first and last tile row
+    return np.array(sorted(picks))
+
+
+def make_weight(cfg_dist: str, N: int, K: int, seed: int, device):
+    if cfg_dist == "normal02":
+        return synth.normal_weight(N, K, 0.02, seed, device)
+    if cfg_dist == "normal01":
+        return synth.normal_weight(N, K, 0.01, seed, device)
+    if cfg_dist == "heavy":
+        return synth.heavy_tail_weight(N, K, 0.02, seed, device)
+    raise ValueError(cfg_dist)

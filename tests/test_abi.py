@@ -1,0 +1,134 @@
+"""CPU-side tests of the C-ABI library: it loads, exports everything include/rtn.h declares,
+validates arguments before touching the GPU, and its host-only planning functions agree with
+the oracle's selective-precision bookkeeping (Section 4)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2505_15909_amd as rtn
+from oracle import rtn_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+lib = rtn._lib
+FAKE = 0x1000   # a 16-byte aligned non-null "device pointer"; never dereferenced by validation
+
+
+def test_every_declared_symbol_is_exported():
+    text = open(os.path.join(ROOT, "include", "rtn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(rtn_[a-z_]+)\s*\(", text))
+    assert declared == set(rtn.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_sizes_and_status_strings():
+    assert rtn.rtn_layout_version() == 1
+    assert rtn.rtn_qweight_nbytes(4096, 4096, 4) == 4096 * 4096 // 2
+    assert rtn.rtn_qweight_nbytes(4096, 4096, 8) == 4096 * 4096
+    assert rtn.rtn_scales_nbytes(4096, 4096, 128) == 4096 * 32 * 2
+    assert rtn.rtn_scales_nbytes(4096, 4096, 0) == 4096 * 2
+    assert rtn.rtn_qweight_nbytes(4096, 4096, 5) == 0
+    assert rtn.rtn_qweight_nbytes(4100, 4096, 4) == 0
+    assert 256 <= rtn.rtn_workspace_nbytes(1, 4096, 4096, 4, 128) <= 16 << 20
+    assert rtn.rtn_workspace_nbytes(128, 106496, 16384, 4, 128) <= 16 << 20
+    for s in range(9):
+        assert lib.rtn_status_str(s)
+    assert lib.rtn_status_str(0) == b"ok"
+
+
+def _quant(W=FAKE, N=64, K=512, bits=4, g=128, flags=0, q=FAKE, s=FAKE):
+    return lib.rtn_quantize(W, N, K, bits, g, flags, q, s, None)
+
+
+def _linear(A=FAKE, M=1, q=FAKE, s=FAKE, N=64, K=512, bits=4, g=128, Cp=FAKE, ws=FAKE, wsn=1 << 20, cfg=None):
+    return lib.rtn_linear_ex(A, M, q, s, N, K, bits, g, Cp, ws, wsn, None, cfg)
+
+
+def test_argument_validation_happens_before_any_launch():
+    assert _quant(W=None) == 1 and _quant(q=None) == 1 and _quant(s=None) == 1
+    assert _quant(bits=3) == 2 and _quant(bits=16) == 2
+    assert _quant(g=96) == 3 and _quant(g=32) == 3 and _quant(g=1024) == 3      # 1024 > K
+    assert _quant(N=60) == 4 and _quant(K=640) == 4 and _quant(N=0) == 4
+    assert _quant(W=FAKE + 8) == 5 and _quant(q=FAKE + 2) == 5
+    assert _quant(flags=7) == 7
+    assert _linear(A=None) == 1 and _linear(Cp=None) == 1
+    assert _linear(bits=5) == 2
+    assert _linear(g=100) == 3
+    assert _linear(M=0) == 4 and _linear(K=500) == 4
+    assert _linear(A=FAKE + 4) == 5
+    cfg = rtn.rtn_linear_cfg(path=1, r_tiles=3)
+    assert _linear(cfg=C.byref(cfg)) == 7
+    cfg = rtn.rtn_linear_cfg(waves_n=1, waves_k=1)
+    assert _linear(M=16, cfg=C.byref(cfg)) == 7                   # 16 rows need >= 4 wavefronts along N
+    cfg = rtn.rtn_linear_cfg(split_k=2)
+    assert _linear(K=1024, wsn=16, cfg=C.byref(cfg)) == 6         # workspace too small
+    cfg = rtn.rtn_linear_cfg(split_k=4)
+    assert _linear(K=1024, cfg=C.byref(cfg)) == 7                 # more splits than chunks
+    assert lib.rtn_unpack(None, 64, 512, 4, FAKE, None) == 1
+    assert lib.rtn_dequantize(FAKE, FAKE, 64, 512, 4, 100, FAKE, None) == 3
+    assert lib.rtn_layer_forward(None, 1, FAKE, 256, None) == 1
+
+
+def test_bad_valid_combination_is_not_launched_without_gpu():
+    # a per-channel request is g <= 0 or g == K
+    q = rtn.rtn_linear_query(1, 4096, 4096, 4, 0)
+    assert q["path"] == 1 and q["split_k"] >= 1
+    with pytest.raises(rtn.RtnError):
+        rtn.rtn_linear_query(1, 4096, 4000, 4, 128)
+
+
+@pytest.mark.parametrize("n_layers", [16, 32, 80, 126])
+def test_plan_bits_matches_oracle(n_layers):
+    for policy in ("first", "last", "middle"):
+        for X in (0, 1, n_layers // 4, n_layers // 2, n_layers):
+            for modules in ((1, 2, 3, 4), (1, 3, 4), (2,), ()):
+                for layer in range(n_layers):
+                    for mid in (1, 2, 3, 4):
+                        assert rtn.rtn_plan_bits(layer, n_layers, mid, policy, X, modules) == \
+                            O.plan_bits(layer, n_layers, mid, policy, X, modules)
+    assert rtn.rtn_plan_bits(n_layers, n_layers, 1, "first", 1) == -1
+    assert rtn.rtn_plan_bits(0, n_layers, 5, "first", 1) == -1
+
+
+def test_effective_bits_matches_oracle_and_paper():
+    p8b = [4096 * 6144, 4096 * 4096, 4096 * 28672, 14336 * 4096]
+    p70 = [8192 * 10240, 8192 * 8192, 8192 * 57344, 28672 * 8192]
+    assert rtn.rtn_plan_effective_bits(32, p8b, "first", 8) == 5.0          # Section 4.3
+    assert rtn.rtn_plan_effective_bits(32, p8b, "first", 16) == 6.0
+    extra = rtn.rtn_plan_effective_bits(80, p70, "first", 1, (1, 3, 4)) - 4
+    assert 0 < extra < 0.05                                                # Sections 1, 6
+    for pol in ("first", "last", "middle"):
+        for X in (0, 3, 20, 80):
+            for mods in ((1, 2, 3, 4), (1, 3, 4), (3,)):
+                a = rtn.rtn_plan_effective_bits(80, p70, pol, X, mods)
+                b = O.effective_bits(80, p70, pol, X, mods)
+                assert abs(a - b) < 1e-12
+
+
+def test_fp32_arithmetic_of_the_gpu_path_equals_exact_rounding():
+    """Host-logic check of the arithmetic the quantise kernel uses: IEEE fp32 division followed by
+    fp16 rounding (scales) or rint (codes) equals the oracle's single rounding of the exact quotient."""
+    halves = np.arange(1, 0x7C00, dtype=np.uint16).view(np.float16)
+    for bits in (4, 8):
+        for rule in ("qmax", "eq2"):
+            D = np.float32(O.scale_divisor(bits, rule))
+            s32 = (halves.astype(np.float32) / D).astype(np.float16)
+            assert np.array_equal(s32.view(np.uint16), O.rtn_scale(halves, bits, rule).view(np.uint16))
+    rng = np.random.default_rng(0)
+    w = rng.integers(1, 0x7C00, size=2_000_000).astype(np.uint16).view(np.float16)
+    s = rng.integers(1, 0x7C00, size=2_000_000).astype(np.uint16).view(np.float16)
+    keep = np.abs(w.astype(np.float64) / s.astype(np.float64)) < 300
+    w, s = w[keep], s[keep]
+    q32 = np.rint(w.astype(np.float32) / s.astype(np.float32))
+    q64 = np.rint(w.astype(np.float64) / s.astype(np.float64))
+    assert np.array_equal(q32.astype(np.float64), q64)
+    # exact ties are hit, not avoided
+    t = np.array([0.5, 1.5, 2.5, 6.5, 126.5], dtype=np.float16)
+    for sc in (np.float16(1.0), np.float16(0.0123), np.float16(2.0 ** -14)):
+        ws = (t.astype(np.float32) * np.float32(sc)).astype(np.float16)
+        if np.array_equal(ws.astype(np.float64), t.astype(np.float64) * float(sc)):
+            assert np.rint(ws.astype(np.float32) / np.float32(sc)).tolist() == [0, 2, 2, 6, 126]

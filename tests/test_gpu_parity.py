@@ -1,0 +1,244 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, on the same seeded inputs.
+
+Quantise / pack: bit-exact on packed bytes and scales (Section 2.2, Eq. 1-2; layout of rtn.h).
+Linear: relative Frobenius error <= 2e-3 and max abs error <= 1e-2 (+ one fp16 rounding of the
+result, 2^-11 |C|, which matters only where |C| >= 8) against the float64 GEMM on the oracle's
+own dequantised weights (Sections 2.3, 5).
+"""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import rtn_oracle as O
+from paper_2505_15909_amd import synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _to_np(t):
+    return t.detach().cpu().numpy()
+
+
+def _quantize_both(W_t, bits, g, flags=0):
+    rtn = pytest.importorskip("paper_2505_15909_amd")
+    qw, sc = rtn.rtn_quantize(W_t, bits, g, flags)
+    torch.cuda.synchronize()
+    W = _to_np(W_t)
+    gg = W.shape[1] if g <= 0 else g
+    codes, scales = O.rtn_quantize(W, bits, gg, "eq2" if flags else "qmax")
+    return qw, sc, codes, scales
+
+
+# ----------------------------------------------------------------------------------------
+# quantise + pack
+# ----------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bits,g", [(4, 128), (4, 256), (4, 512), (4, 1024), (4, 0), (8, 64), (8, 128),
+                                     (8, 256), (8, 512), (8, 0)])
+@pytest.mark.parametrize("N,K", [(80, 2048), (16, 512), (272, 3072)])
+def test_quantize_bit_exact_small(rtn, bits, g, N, K):
+    if g > K or (g > 0 and K % g):
+        pytest.skip("group does not divide K")
+    W_t = synth.normal_weight(N, K, 0.02, seed=N + K + bits, device=DEV)
+    qw, sc, codes, scales = _quantize_both(W_t, bits, g)
+    assert np.array_equal(_to_np(sc).view(np.uint16), scales.view(np.uint16))
+    assert np.array_equal(_to_np(qw), O.pack_gfx950(codes, bits))
+    assert np.array_equal(_to_np(rtn.rtn_unpack(qw, N, K, bits)), codes)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("flags", [0, 1])
+def test_quantize_adversarial(rtn, bits, flags):
+    """Exact ties, all-zero groups, fp16 subnormals, +-65504, -0.0, one huge outlier per group."""
+    N, K, g = 64, 1024, 128 if bits == 4 else 64
+    rng = np.random.default_rng(11)
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+    qmax = (1 << (bits - 1)) - 1
+    W[0, :g] = ((np.arange(g) % 29) - 14) * 0.5 * 2.0 ** -8          # ties at every half step
+    W[0, 0] = qmax * 2.0 ** -8
+    W[1, :g] = 0.0
+    W[2, :g] = -0.0
+    W[3, :g] = (rng.integers(-20, 21, size=g) * 2.0 ** -24).astype(np.float16)   # subnormals
+    W[4, :g] = (rng.integers(-3, 4, size=g) * 2.0 ** -24).astype(np.float16)     # scale underflows to 0 / 1 ulp
+    W[5, 0], W[5, 1] = 65504.0, -65504.0
+    W[6, 7] = 300.0                                                   # outlier: the rest rounds to 0
+    W[7, :g] = np.float16(0.3)                                        # constant group
+    W[8, g:2 * g] = (np.arange(g) - g // 2) * np.float16(0.011)        # inexact scale, near-ties
+    for r in range(9, 32):                                            # multiples of half a scale step
+        s = np.float16(rng.uniform(0.001, 0.1))
+        W[r, :g] = (rng.integers(-2 * qmax, 2 * qmax + 1, size=g) * 0.5 * float(s)).astype(np.float16)
+    W_t = torch.from_numpy(W).to(DEV)
+    qw, sc, codes, scales = _quantize_both(W_t, bits, g, flags)
+    assert np.array_equal(_to_np(sc).view(np.uint16), scales.view(np.uint16))
+    assert np.array_equal(_to_np(qw), O.pack_gfx950(codes, bits))
+    # per-channel on the same tensor
+    qw, sc, codes, scales = _quantize_both(W_t, bits, 0, flags)
+    assert np.array_equal(_to_np(sc).view(np.uint16), scales.view(np.uint16))
+    assert np.array_equal(_to_np(qw), O.pack_gfx950(codes, bits))
+
+
+def test_quantize_is_deterministic_and_dequantize_matches(rtn):
+    N, K = 256, 2048
+    W_t = synth.heavy_tail_weight(N, K, 0.02, seed=5, device=DEV)
+    for bits, g in ((4, 128), (8, 0)):
+        q1, s1 = rtn.rtn_quantize(W_t, bits, g)
+        q2, s2 = rtn.rtn_quantize(W_t, bits, g)
+        assert torch.equal(q1, q2) and torch.equal(s1, s2)
+        codes, scales = O.rtn_quantize(_to_np(W_t), bits, K if g == 0 else g)
+        deq = rtn.rtn_dequantize(q1, s1, K, bits, g)
+        want = O.rtn_dequantize(codes, scales, K if g == 0 else g).astype(np.float16)
+        assert np.array_equal(_to_np(deq).view(np.uint16), want.view(np.uint16))
+
+
+# ----------------------------------------------------------------------------------------
+# linear: small shapes, every kernel configuration
+# ----------------------------------------------------------------------------------------
+def _oracle_operands(N, K, bits, g, seed, dist="normal02"):
+    W_t = H.make_weight(dist, N, K, seed, DEV)
+    W = _to_np(W_t)
+    gg = K if g <= 0 else g
+    codes, scales = O.rtn_quantize(W, bits, gg)
+    qw = torch.from_numpy(O.pack_gfx950(codes, bits)).to(DEV)
+    sc = torch.from_numpy(scales).to(DEV)
+    return codes, scales, qw, sc, gg
+
+
+CFGS = [dict(r_tiles=r, waves_n=wn, waves_k=wk, split_k=sk)
+        for r, wn, wk, sk in [(1, 1, 1, 1), (1, 1, 4, 1), (2, 1, 2, 2), (1, 2, 2, 1), (2, 2, 1, 3), (4, 1, 1, 1),
+                              (1, 4, 1, 1), (2, 4, 2, 2), (4, 4, 1, 1), (1, 1, 8, 1), (1, 8, 1, 2), (4, 2, 4, 4)]]
+
+
+@pytest.mark.parametrize("bits,g", [(4, 128), (4, 256), (4, 512), (4, 0), (8, 64), (8, 128), (8, 256), (8, 0)])
+def test_linear_all_configs_small(rtn, bits, g):
+    N, K = 272, 3072            # 17 tile rows (ragged against every WN*R), 6 / 12 chunks
+    codes, scales, qw, sc, gg = _oracle_operands(N, K, bits, g, seed=3)
+    for M in (1, 2, 3, 4, 5, 8, 13, 16):
+        A_t = synth.activation(M, K, seed=100 + M, device=DEV)
+        ref = O.rtn_linear(_to_np(A_t), codes, scales, gg)
+        cap = 4 if bits == 4 else 8
+        for cfg in CFGS:
+            if cfg["waves_n"] * cap < min(M, 16):
+                continue                                   # staging capacity of the N-wavefronts
+            ck = 512 if bits == 4 else 256
+            if 2 * min(M, 16) * (cfg["waves_k"] * ck + 8) * 2 > 65536:
+                continue                                   # LDS budget
+            C = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=cfg)
+            torch.cuda.synchronize()
+            H.assert_linear_close(_to_np(C), ref, f"bits={bits} g={g} M={M} cfg={cfg}")
+        C = rtn.rtn_linear(A_t, qw, sc, bits, g)          # automatic plan
+        torch.cuda.synchronize()
+        H.assert_linear_close(_to_np(C), ref, f"bits={bits} g={g} M={M} auto")
+
+
+@pytest.mark.parametrize("bits,g", [(4, 128), (8, 0)])
+@pytest.mark.parametrize("M", [17, 32, 33, 64, 100, 128])
+def test_linear_larger_batches(rtn, bits, g, M):
+    N, K = 528, 2048
+    codes, scales, qw, sc, gg = _oracle_operands(N, K, bits, g, seed=4)
+    A_t = synth.activation(M, K, seed=100 + M, device=DEV)
+    ref = O.rtn_linear(_to_np(A_t), codes, scales, gg)
+    C = rtn.rtn_linear(A_t, qw, sc, bits, g)
+    torch.cuda.synchronize()
+    H.assert_linear_close(_to_np(C), ref, f"bits={bits} g={g} M={M}")
+
+
+@pytest.mark.parametrize("bits,g", [(4, 128), (8, 64), (8, 0)])
+def test_linear_special_cases(rtn, bits, g):
+    N, K = 64, 1024
+    codes, scales, qw, sc, gg = _oracle_operands(N, K, bits, g, seed=9)
+    # one-hot activations select single dequantised weights: exact in fp16
+    ks = [0, 1, 7, 8, 31, 32, 127, 128, 511, 512, 640, 1023]
+    A = np.zeros((len(ks), K), dtype=np.float16)
+    for i, k in enumerate(ks):
+        A[i, k] = 1.0
+    C = rtn.rtn_linear(torch.from_numpy(A).to(DEV), qw, sc, bits, g)
+    want = O.rtn_dequantize(codes, scales, gg)[:, ks].T.astype(np.float16)
+    assert np.array_equal(_to_np(C).view(np.uint16), want.view(np.uint16))
+    # zero activations
+    C = rtn.rtn_linear(torch.zeros((3, K), dtype=torch.float16, device=DEV), qw, sc, bits, g)
+    assert not _to_np(C).any()
+    # unit scales and small-integer activations: an integer matrix product, exact in fp32 and fp16
+    rng = np.random.default_rng(2)
+    qmax = (1 << (bits - 1)) - 1
+    c2 = rng.integers(-qmax - 1, qmax + 1, size=(N, K)).astype(np.int8)
+    if bits == 8:
+        c2 = (c2 // 16).astype(np.int8)
+    ones = np.ones((N, K // gg), dtype=np.float16)
+    A2 = rng.integers(-1, 2, size=(4, K)).astype(np.float16)
+    C = rtn.rtn_linear(torch.from_numpy(A2).to(DEV), torch.from_numpy(O.pack_gfx950(c2, bits)).to(DEV),
+                       torch.from_numpy(ones).to(DEV), bits, g)
+    want = (A2.astype(np.int64) @ c2.astype(np.int64).T)
+    assert np.abs(want).max() < 2048
+    assert np.array_equal(_to_np(C).astype(np.int64), want)
+
+
+def test_linear_is_deterministic(rtn):
+    N, K = 512, 4096
+    codes, scales, qw, sc, gg = _oracle_operands(N, K, 4, 128, seed=12)
+    for M, cfg in ((1, dict(waves_k=4, split_k=2)), (16, dict(waves_n=4, waves_k=1, split_k=4)), (8, dict(waves_n=2, waves_k=2, split_k=2)), (3, None)):
+        A_t = synth.activation(M, K, seed=1, device=DEV)
+        outs = [rtn.rtn_linear(A_t, qw, sc, 4, 128, cfg=cfg).clone() for _ in range(5)]
+        torch.cuda.synchronize()
+        for o in outs[1:]:
+            assert torch.equal(o, outs[0])
+
+
+# ----------------------------------------------------------------------------------------
+# the paper-shaped configurations at full size (rows of the weight matrix are independent, so the
+# oracle checks a stripe of 16-row tiles; the GPU runs the full shape in its default configuration)
+# ----------------------------------------------------------------------------------------
+FULL = [
+    # name, dist, bits, g, modules, Ms, stripe tiles
+    ("single_4096", "normal02", 4, 128, {"o": (4096, 4096)}, (1,), 256),
+    ("llama8b_w4", "normal02", 4, 128, synth.LLAMA_8B, (1, 2, 4, 8, 16), 24),
+    ("llama8b_w8", "normal02", 8, 0, synth.LLAMA_8B, (1, 4, 16, 64), 24),
+    ("llama70b_w4", "heavy", 4, 128, synth.LLAMA_70B, (1, 8, 32, 64), 12),
+]
+
+
+@pytest.mark.parametrize("case", FULL, ids=lambda c: c[0])
+def test_full_size_quantize_and_linear(rtn, case):
+    name, dist, bits, g, modules, Ms, n_tiles = case
+    for idx, (mod, (K, N)) in enumerate(modules.items()):
+        W_t = H.make_weight(dist, N, K, seed=idx, device=DEV)
+        qw, sc = rtn.rtn_quantize(W_t, bits, g)
+        tiles = H.pick_row_tiles(N, n_tiles, seed=idx)
+        rows = H.tile_rows(tiles, N)
+        Wr = _to_np(W_t[torch.from_numpy(rows).to(DEV)])
+        gg = K if g <= 0 else g
+        codes, scales = O.rtn_quantize(Wr, bits, gg)
+        assert np.array_equal(_to_np(sc)[rows].view(np.uint16), scales.view(np.uint16)), (name, mod)
+        assert np.array_equal(H.packed_rows_image(_to_np(qw), tiles, K, bits), O.pack_gfx950(codes, bits)), (name, mod)
+        del W_t
+        for M in Ms:
+            A_t = synth.activation(M, K, seed=100 + M, device=DEV)
+            C = rtn.rtn_linear(A_t, qw, sc, bits, g)
+            torch.cuda.synchronize()
+            ref = O.rtn_linear(_to_np(A_t), codes, scales, gg)
+            H.assert_linear_close(_to_np(C)[:, rows], ref, f"{name} {mod} M={M}")
+            print(f"{name} {mod} M={M} ok", flush=True)
+
+
+def test_selective_precision_layer(rtn):
+    """Mixed 4-/8-bit decoder layer through rtn_layer_forward (Section 4.3), 405B-shaped at 1/8 width
+    here; the full-width layer is exercised by the benchmark."""
+    shapes = {"qkv": (2048, 2304, 4, 128), "o": (2048, 2048, 8, 0), "gate_up": (2048, 13312, 4, 128),
+              "down": (6656 - 6656 % 512, 2048, 8, 0)}
+    for M in (1, 16, 128):
+        mods, refs = [], []
+        for idx, (mod, (K, N, bits, g)) in enumerate(shapes.items()):
+            W = _to_np(synth.normal_weight(N, K, 0.01, seed=idx, device=DEV))
+            gg = K if g <= 0 else g
+            codes, scales = O.rtn_quantize(W, bits, gg)
+            A_t = synth.activation(M, K, seed=200 + idx, device=DEV)
+            mods.append(dict(A=A_t, qweight=torch.from_numpy(O.pack_gfx950(codes, bits)).to(DEV),
+                             scales=torch.from_numpy(scales).to(DEV), bits=bits, group_size=g,
+                             C=torch.empty((M, N), dtype=torch.float16, device=DEV)))
+            refs.append(O.rtn_linear(_to_np(A_t), codes, scales, gg))
+        rtn.rtn_layer_forward(mods)
+        torch.cuda.synchronize()
+        for m, ref, mod in zip(mods, refs, shapes):
+            H.assert_linear_close(_to_np(m["C"]), ref, f"layer {mod} M={M}")
