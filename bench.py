@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the RTN weight-only quantised linear path on one MI355X.
+
+Workload (benchmark configs[1]): the four linear modules of a Llama-3.1-8B-shaped
+Transformer layer (Section 4: QKV 4096->6144, attention output 4096->4096, gate_up
+4096->28672, down 14336->4096), symmetric RTN int4 with group 128 and fp16 scales
+(Section 2.2), fp16 activations at the token-generation batch sizes M = 1, 2, 4, 8, 16
+(Sections 1, 5).  Weights ~ N(0, 0.02), activations ~ N(0, 1), seeded, synthetic.
+
+One step = one pass of the hot path over one batch of input: for every M, the layer's four
+modules through rtn_layer_forward (20 fused dequantise-GEMMs).  Every pass streams a different
+copy of the packed layer (enough copies to exceed twice the 256 MB Infinity Cache), as token
+generation does when it walks a model's layers, so the weights come from HBM, not from cache.
+The load-time quantise/pack pass (Section 5) runs once during set-up, is checked to reproduce,
+and its throughput is reported in the "quantize" object; it is not inside the timed steps,
+which measure the metric itself: weight-stream GB/s of the linear layers.
+
+Prints one JSON line (see the design doc for the field definitions).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+BATCHES = (1, 2, 4, 8, 16)
+BITS, GROUP = 4, 128
+CACHE_BYTES = 256e6
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# very command, scaled by a copy kernel of known size; see profiles/ (None until measured).
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=12)
+    ap.add_argument("--no-graph", action="store_true", help="launch every step directly instead of replaying HIP graphs")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (--gpus 1); nothing here uses a second GPU.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2505_15909_amd as rtn
+    from paper_2505_15909_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    modules = list(synth.LLAMA_8B.items())
+
+    # ---- set-up: synthetic fp16 weights, load-time quantise (timed separately) ---------------
+    W = [synth.normal_weight(N, K, 0.02, seed=i, device=dev) for i, (_, (K, N)) in enumerate(modules)]
+    packed = [rtn.rtn_quantize(w, BITS, GROUP) for w in W]           # warm-up + the copy used below
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    q_reps = 5
+    e0.record()
+    for _ in range(q_reps):
+        for w, (q, s) in zip(W, packed):
+            rtn.rtn_quantize(w, BITS, GROUP, out=(q, s))
+    e1.record()
+    torch.cuda.synchronize()
+    q_ms = e0.elapsed_time(e1) / q_reps
+    q_bytes = sum(w.numel() * 2 + q.numel() + s.numel() * 2 for w, (q, s) in zip(W, packed))
+    del W
+
+    layer_bytes = sum(q.numel() + s.numel() * 2 for q, s in packed)   # packed codes + scales of one layer
+    n_copies = max(2, int(np.ceil(2.4 * CACHE_BYTES / layer_bytes)))
+    copies = [packed] + [[(q.clone(), s.clone()) for q, s in packed] for _ in range(n_copies - 1)]
+    acts = {M: [synth.activation(M, K, seed=100 + M, device=dev) for _, (K, N) in modules] for M in BATCHES}
+    outs = {M: [torch.empty((M, N), dtype=torch.float16, device=dev) for _, (K, N) in modules] for M in BATCHES}
+    ws = torch.empty(16 << 20, dtype=torch.uint8, device=dev)
+
+    # one prepared rtn_layer_forward call per (weight copy, M)
+    plans = [[rtn.LayerPlan([dict(A=acts[M][i], qweight=cp[i][0], scales=cp[i][1], bits=BITS, group_size=GROUP,
+                                  C=outs[M][i]) for i in range(len(modules))], workspace=ws)
+              for M in BATCHES] for cp in copies]
+    pass_no = [0]
+
+    def step_direct():
+        for j in range(len(BATCHES)):
+            plans[pass_no[0] % n_copies][j].run()
+            pass_no[0] += 1
+
+    stream = torch.cuda.Stream()
+    graphs = []
+    if not args.no_graph:
+        # a step replays one HIP graph; n_copies graphs cover every phase of the weight rotation
+        with torch.cuda.stream(stream):
+            for _ in range(2):
+                step_direct()
+            stream.synchronize()
+            for v in range(n_copies):
+                pass_no[0] = v * len(BATCHES)
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    step_direct()
+                graphs.append(g)
+    step_no = [0]
+
+    def step():
+        if graphs:
+            graphs[step_no[0] % n_copies].replay()
+        else:
+            step_direct()
+        step_no[0] += 1
+
+    with torch.cuda.stream(stream):
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    step_weight_bytes = layer_bytes * len(BATCHES)
+    value = step_weight_bytes / (ms_per_step * 1e-3) / 1e9
+    flops = sum(2.0 * M * N * K for M in BATCHES for _, (K, N) in modules)
+
+    # ---- roofline of the dominant kernel (the int4 skinny MFMA dequantise-GEMM: all 20 launches of a
+    # step): HIP events around every launch, on the launch stream, over the same steps -------------
+    algo_bytes = 0.0
+    dur_ms = 0.0
+    n_launch = 0
+    with torch.cuda.stream(stream):
+        evs = []
+        for s_i in range(min(args.steps, 20)):
+            for j, M in enumerate(BATCHES):
+                cp = copies[pass_no[0] % n_copies]
+                pass_no[0] += 1
+                for i, (_, (K, N)) in enumerate(modules):
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record(stream)
+                    rtn.rtn_linear(acts[M][i], cp[i][0], cp[i][1], BITS, GROUP, out=outs[M][i], workspace=ws)
+                    b.record(stream)
+                    evs.append((a, b))
+                    algo_bytes += cp[i][0].numel() + cp[i][1].numel() * 2 + 2 * M * K + 2 * M * N
+                    n_launch += 1
+        torch.cuda.synchronize()
+        dur_ms = sum(a.elapsed_time(b) for a, b in evs)
+    achieved = algo_bytes / (dur_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH,
+                "kernel": "skinny_mfma_kernel<4,...> (fused int4 dequantise-GEMM)",
+                "launches": n_launch, "avg_launch_us": round(dur_ms * 1e3 / n_launch, 3),
+                "algorithmic_bytes_per_launch": round(algo_bytes / n_launch, 1)}
+
+    # ---- CPU oracle timed beside it (bounded sample of the same workload) ------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import rtn_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        sample = []
+        for i, (name, (K, N)) in enumerate(modules):
+            w = synth.normal_weight(N, K, 0.02, seed=i, device="cpu").numpy()
+            codes, scales = O.rtn_quantize(w, BITS, GROUP)
+            sample.append((codes, scales, K, N))
+        cpu_bytes = 0
+        tc = time.perf_counter()
+        for M in BATCHES:
+            for i, (codes, scales, K, N) in enumerate(sample):
+                O.rtn_linear(acts[M][i].cpu().numpy(), codes, scales, GROUP)
+                cpu_bytes += codes.size * BITS // 8 + scales.size * 2
+        tc = time.perf_counter() - tc
+        cpu = {"value": round(cpu_bytes / tc / 1e9, 4), "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+               "sample": "one full step (20 float64 linears of the same layer set, M=1,2,4,8,16), "
+                         f"{tc:.1f} s wall; quantisation of the sample not timed"}
+
+    line = {
+        "metric": "weight-stream GB/s (% HBM peak) of RTN W4A16/W8A16 linear at M=1..16",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "llama8b_w4a16_g128_layer_set_M1-16", "bits": BITS, "group_size": GROUP,
+                   "batches": list(BATCHES), "modules": {k: list(v) for k, v in synth.LLAMA_8B.items()},
+                   "weight_copies_rotated": n_copies, "launch": "hip_graph_replay" if graphs else "direct"},
+        "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "tflops": round(flops / (ms_per_step * 1e-3) / 1e12, 3),
+        "weight_bytes_per_step": int(step_weight_bytes),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "quantize": {"GB/s": round(q_bytes / (q_ms * 1e-3) / 1e9, 1), "ms_per_layer": round(q_ms, 4),
+                     "bytes": "fp16 read + packed codes and scales written, four modules"},
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
