@@ -77,7 +77,7 @@ int rtn_layout_version(void);
 /* Sizes in bytes of the buffers the caller must provide; 0 if the arguments are invalid.
  * qweight: N*K*bits/8.  scales: N*(K/g)*2.  workspace (rtn_linear, rtn_layer_forward):
  * fp32 split-K partial sums; an upper bound over every configuration the library may
- * choose for this problem; never more than a few MiB. */
+ * choose for this problem; never more than 16 MiB. */
 size_t rtn_qweight_nbytes(int64_t N, int64_t K, int bits);
 size_t rtn_scales_nbytes(int64_t N, int64_t K, int group_size);
 size_t rtn_workspace_nbytes(int64_t M, int64_t N, int64_t K, int bits, int group_size);
@@ -116,9 +116,9 @@ rtn_status rtn_linear(const void* dev_A, int64_t M, const void* dev_qweight, con
  * A zeroed struct means "choose automatically", field by field. */
 typedef struct {
     int path;      /* 0 auto, 1 MFMA skinny kernel, 2 vector-ALU dot-product kernel (M <= 4) */
-    int r_tiles;   /* 16-row weight tiles per wavefront: 1, 2 or 4 */
-    int waves_n;   /* wavefronts of a workgroup along N (share the staged activations) */
-    int waves_k;   /* wavefronts of a workgroup along K (in-workgroup split-K) */
+    int prefetch;  /* k-chunks (4 KiB each) a wavefront keeps in flight: 1 or 2 */
+    int waves_n;   /* wavefronts of a workgroup along N (share the staged activations): 1, 2, 4, 8, 16 */
+    int waves_k;   /* wavefronts of a workgroup along K (in-workgroup split-K): 1 .. 16; waves_n * waves_k <= 16 */
     int split_k;   /* workgroups along K (global split-K, reduced through the workspace) */
 } rtn_linear_cfg;
 

@@ -13,7 +13,6 @@ namespace {
 
 constexpr size_t kWorkspaceCap = (size_t)16 << 20;     // split-K partials never exceed this
 constexpr int kMaxSplitK = 16;
-constexpr size_t kMaxLds = 64 * 1024;
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
@@ -46,51 +45,68 @@ size_t workspace_bound(int64_t M, int64_t N) {
     return (want + 255) & ~(size_t)255;
 }
 
-// Default plan.  Small batches split K across the wavefronts of a workgroup so that many
-// wavefronts stream disjoint parts of the weights; larger batches put the wavefronts side by
-// side along N so that they share the staged activations.
-LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits) {
+int device_max_lds() {
+    static int cached = 0;
+    if (cached == 0) {
+        int v = 0, dev = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && v > 0)
+            cached = v < (int)rtn::kMaxLdsBytes ? v : (int)rtn::kMaxLdsBytes;
+        else
+            cached = 64 * 1024;
+    }
+    return cached;
+}
+
+int round_pow2(int64_t v, int lo, int hi) {
+    int p = lo;
+    while (p * 2 <= hi && (int64_t)p * 3 / 2 <= v) p *= 2;     // nearest power of two in the log sense
+    return p;
+}
+
+// Default plan (measured on MI355X; see the design notes).  Short-lived wavefronts at high occupancy
+// stream best: each wavefront gets 1-4 k-chunks (4-16 KiB of packed weights) of one tile-row, eight
+// wavefronts form a workgroup, and K is split inside the workgroup (reduced through LDS), never
+// across workgroups unless the staged activation slice would not fit in LDS.
+LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, size_t lds_limit) {
     LinearPlan p;
-    const int rows = (int)(M < 16 ? M : 16);
-    const int cap = (bits == 4) ? 4 : 8;       // activation rows one N-wavefront can stage
+    const int64_t NT = N / 16, KC = K / chunk_k(bits);
+    const int64_t steps = NT * KC;                             // 4 KiB chunk-steps in the whole matrix
     p.path = 1;
     p.m_blocks = (int)((M + 15) / 16);
-    p.waves_n = 1;
-    while (p.waves_n * cap < rows) p.waves_n *= 2;
-    p.waves_k = 4 / p.waves_n;
-    if (p.waves_k < 1) p.waves_k = 1;
-    p.r_tiles = (rows <= 4) ? 1 : 2;
-    const int64_t NT = N / 16, KC = K / chunk_k(bits);
-    while (p.waves_k > 1 && p.waves_k > KC) p.waves_k /= 2;
-    int64_t blocks_n = (NT + p.waves_n * p.r_tiles - 1) / (p.waves_n * p.r_tiles);
-    int64_t split = 1;
-    const int64_t target = 1024;               // ~4 workgroups per compute unit
-    while (split * 2 <= kMaxSplitK && blocks_n * p.m_blocks * split < target &&
-           KC / (split * 2) >= p.waves_k &&
-           (size_t)M * N * sizeof(float) * (split * 2) <= kWorkspaceCap)
-        split *= 2;
-    p.split_k = (int)split;
+    p.prefetch = 1;
+    p.split_k = 1;
+    const int64_t per_wave = steps <= 6144 ? 1 : (steps <= 24576 ? 2 : 4);
+    p.waves_k = round_pow2((KC + per_wave - 1) / per_wave, 1, 16);
+    while (p.waves_k > KC) p.waves_k /= 2;
+    p.waves_n = 8 / p.waves_k > 0 ? 8 / p.waves_k : 1;
+    while (p.waves_n > 1 && p.waves_n > NT) p.waves_n /= 2;
+    // a stage of rows x (waves_k x 512) activations is moved by the workgroup's threads, 8 pieces each
+    const int rows = (int)(M < 16 ? M + 1 : 16);
+    while (rows * p.prefetch > 8 * p.waves_n) p.waves_n *= 2;
+    while (p.waves_n * p.waves_k > 16) p.waves_k /= 2;
+    (void)lds_limit;                       // the kernel stages activations in pieces that always fit
     return p;
 }
 
 rtn_status resolve_plan(const LinearArgs& a, const rtn_linear_cfg* cfg, size_t workspace_nbytes, LinearPlan* out) {
-    LinearPlan p = auto_plan(a.M, a.N, a.K, a.bits);
+    const size_t lds_limit = (size_t)device_max_lds();
+    LinearPlan p = auto_plan(a.M, a.N, a.K, a.bits, lds_limit);
     if (cfg) {
         if (cfg->path) p.path = cfg->path;
-        if (cfg->r_tiles) p.r_tiles = cfg->r_tiles;
+        if (cfg->prefetch) p.prefetch = cfg->prefetch;
         if (cfg->waves_n) p.waves_n = cfg->waves_n;
         if (cfg->waves_k) p.waves_k = cfg->waves_k;
         if (cfg->split_k) p.split_k = cfg->split_k;
     }
-    const int rows = (int)(a.M < 16 ? a.M : 16);
-    const int cap = (a.bits == 4) ? 4 : 8;
     const int64_t KC = a.K / chunk_k(a.bits);
     if (p.path != 1) return RTN_ERR_CONFIG;
-    if (p.r_tiles != 1 && p.r_tiles != 2 && p.r_tiles != 4) return RTN_ERR_CONFIG;
-    if (!pow2(p.waves_n) || !pow2(p.waves_k) || p.waves_n * p.waves_k > 8) return RTN_ERR_CONFIG;
-    if (p.waves_n * cap < rows) return RTN_ERR_CONFIG;           // staging capacity
+    if (p.prefetch != 1 && p.prefetch != 2) return RTN_ERR_CONFIG;
+    if (!pow2(p.waves_n) || !pow2(p.waves_k) || p.waves_n * p.waves_k > 16) return RTN_ERR_CONFIG;
     if (p.split_k < 1 || p.split_k > kMaxSplitK || p.split_k > KC) return RTN_ERR_CONFIG;
-    if (rtn::linear_lds_bytes(a, p) > kMaxLds) return RTN_ERR_CONFIG;
+    if (!rtn::linear_plan_fits(a, p, lds_limit)) return RTN_ERR_CONFIG;
+    if ((uint64_t)a.N * a.K * a.bits / 8 >= 0x7FFF0000ull || (uint64_t)a.M * a.K * 2 >= 0x7FFF0000ull)
+        return RTN_ERR_SHAPE;                                   // 32-bit buffer offsets
     if (p.split_k > 1) {
         const size_t need = (size_t)a.M * a.N * sizeof(float) * p.split_k;
         if (a.workspace == nullptr || workspace_nbytes < need) return RTN_ERR_WORKSPACE;
@@ -190,8 +206,8 @@ rtn_status rtn_linear_query(int64_t M, int64_t N, int64_t K, int bits, int group
     rtn_status st = check_problem(N, K, bits, group_size, &g);
     if (st != RTN_OK) return st;
     if (M <= 0) return RTN_ERR_SHAPE;
-    LinearPlan p = auto_plan(M, N, K, bits);
-    out->path = p.path; out->r_tiles = p.r_tiles; out->waves_n = p.waves_n;
+    LinearPlan p = auto_plan(M, N, K, bits, (size_t)device_max_lds());
+    out->path = p.path; out->prefetch = p.prefetch; out->waves_n = p.waves_n;
     out->waves_k = p.waves_k; out->split_k = p.split_k;
     return RTN_OK;
 }

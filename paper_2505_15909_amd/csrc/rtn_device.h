@@ -40,21 +40,37 @@ union Half8Words {
     half2_t h2[4];
 };
 
+// fp16 1024.0 in both halves, materialised once in a vector register.  0x6400 is fp16 1024, whose
+// ulp is 1: or-ing a nibble or byte into the mantissa gives 1024 + n exactly.
+__device__ __forceinline__ uint32_t fp16_magic_vgpr() {
+    uint32_t m;
+    asm volatile("v_mov_b32 %0, 0x64006400" : "=v"(m));
+    return m;
+}
+
+// (x & mask) | magic in one instruction.  gfx9-family VOP3 encodings take no literal and at most
+// one scalar operand, so the mask lives in an SGPR and the magic in a VGPR; left to itself the
+// compiler emits a separate and + or with two literals.
+__device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic_v) {
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "s"(mask), "v"(magic_v));
+    return r;
+}
+
 // One 32-bit word of 4-bit codes (offset binary, nibble order {0,4,1,5,2,6,3,7}) -> the 8 fp16
-// values one lane feeds to one 16x16x32 MFMA.  0x6400 is fp16 1024, whose ulp is 1: or-ing a
-// nibble into the mantissa gives 1024 + n exactly (or 1024 + 16 n for a nibble sitting 4 bits
-// up), and one packed add / fma removes the offset exactly.  9 vector ops per 8 weights.
-__device__ __forceinline__ half8_t unpack_word4(uint32_t w) {
-    const uint32_t MAGIC = 0x64006400u;
+// values one lane feeds to one 16x16x32 MFMA: and_or puts two nibbles under the 1024 exponent
+// (1024 + n, or 1024 + 16 n for a nibble sitting 4 bits up), one packed add / fma removes the
+// offset exactly.  9 vector ops per 8 weights.
+__device__ __forceinline__ half8_t unpack_word4(uint32_t w, uint32_t magic_v) {
     const half2_t k1032 = {(half_t)1032.0f, (half_t)1032.0f};
     const half2_t k16th = {(half_t)0.0625f, (half_t)0.0625f};
     const half2_t k72 = {(half_t)-72.0f, (half_t)-72.0f};
-    uint32_t w8 = w >> 8;
+    const uint32_t w8 = w >> 8;
     Half8Words r;
-    r.h2[0] = as_half2((w & 0x000F000Fu) | MAGIC) - k1032;                              // nibbles 0,4
-    r.h2[1] = __builtin_elementwise_fma(as_half2((w & 0x00F000F0u) | MAGIC), k16th, k72);   // nibbles 1,5
-    r.h2[2] = as_half2((w8 & 0x000F000Fu) | MAGIC) - k1032;                             // nibbles 2,6
-    r.h2[3] = __builtin_elementwise_fma(as_half2((w8 & 0x00F000F0u) | MAGIC), k16th, k72);  // nibbles 3,7
+    r.h2[0] = as_half2(and_or(w, 0x000F000Fu, magic_v)) - k1032;                               // nibbles 0,4
+    r.h2[1] = __builtin_elementwise_fma(as_half2(and_or(w, 0x00F000F0u, magic_v)), k16th, k72);   // nibbles 1,5
+    r.h2[2] = as_half2(and_or(w8, 0x000F000Fu, magic_v)) - k1032;                              // nibbles 2,6
+    r.h2[3] = __builtin_elementwise_fma(as_half2(and_or(w8, 0x00F000F0u, magic_v)), k16th, k72);  // nibbles 3,7
     return r.v;
 }
 
@@ -74,9 +90,9 @@ __device__ __forceinline__ half8_t unpack_words8(uint32_t w0, uint32_t w1) {
 
 // MFMA operand number i (0 .. MFMA_PER_TILE-1) of a 16-byte tile chunk.
 template <int BITS>
-__device__ __forceinline__ half8_t unpack_operand(const u32x4_t& chunk, int i) {
+__device__ __forceinline__ half8_t unpack_operand(const u32x4_t& chunk, int i, uint32_t magic_v) {
     if constexpr (BITS == 4) {
-        return unpack_word4(chunk[i]);
+        return unpack_word4(chunk[i], magic_v);
     } else {
         return unpack_words8(chunk[2 * i], chunk[2 * i + 1]);
     }

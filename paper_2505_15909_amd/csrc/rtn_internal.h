@@ -5,10 +5,12 @@
 
 namespace rtn {
 
+constexpr size_t kMaxLdsBytes = 160 * 1024;   // LDS of one gfx950 compute unit, usable by one workgroup
+
 // Resolved launch configuration of the fused dequantise-GEMM.
 struct LinearPlan {
     int path;       // 1 = MFMA skinny kernel, 2 = vector-ALU dot kernel
-    int r_tiles;    // 16-row weight tiles per wavefront
+    int prefetch;   // k-chunks in flight per wavefront (register buffers): 1 or 2
     int waves_n;    // wavefronts along N per workgroup
     int waves_k;    // wavefronts along K per workgroup
     int split_k;    // workgroups along K
@@ -31,8 +33,10 @@ hipError_t launch_unpack(const void* qweight, const void* scales, int64_t N, int
                          bool dequant, void* out, hipStream_t st);
 hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t st);
 
-// LDS bytes the skinny kernel needs for a plan (activation staging, double buffered, and the
+// LDS bytes the skinny kernel needs for a plan (staged activation slice incl. the zero row, or the
 // in-workgroup split-K reduction buffer, whichever is larger).
 size_t linear_lds_bytes(const LinearArgs& a, const LinearPlan& p);
+// Whether the plan's activation staging fits the LDS limit and the per-thread staging registers.
+bool linear_plan_fits(const LinearArgs& a, const LinearPlan& p, size_t lds_limit);
 
 }  // namespace rtn

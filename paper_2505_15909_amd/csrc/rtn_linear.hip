@@ -4,18 +4,29 @@
 //
 //   C[m, n] = fp16( sum_k A[m, k] * q[n, k] * S[n, k / g] )
 //
-// Skinny MFMA kernel.  A wavefront owns R weight tiles-rows (16 output channels each) and a
-// slice of K.  Per step it streams one k-chunk (4 tiles = 4 KiB, four 16-byte-per-lane loads,
-// issued one step ahead) of one tile-row, unpacks the codes in registers to exact fp16
-// integers, and feeds them as the B operand of v_mfma_f32_16x16x32_f16; the A operand is the
-// (zero-padded to 16 rows) activation block, staged once per workgroup in LDS (double
-// buffered, padded rows -> conflict-free 16-byte reads) and held in registers across the R
-// tile-rows.  Scales multiply the fp32 partial sum of each group (exact codes into the matrix
-// cores, one fp32 multiply-add per group and output), never the individual weights.
-// Wavefronts of a workgroup are arranged WN along N (sharing the staged activations) times WK
-// along K (in-workgroup split-K, reduced through LDS in a fixed order); an optional global
-// split-K writes fp32 partials to the workspace and a second kernel sums them in a fixed
-// order, so results are bit-reproducible.
+// Skinny MFMA kernel.  A workgroup is WN x WK wavefronts: wavefront (wn, wk) owns one tile-row
+// (16 output channels) and a contiguous run of k-chunks (4 tiles = 4 KiB of packed codes each)
+// of the workgroup's K range.  Per chunk it issues four 16-byte-per-lane loads (1 KiB per
+// wavefront each, fully coalesced), unpacks the codes in registers to exact fp16 integers and
+// feeds them as the B operand of v_mfma_f32_16x16x32_f16.  The A operand is the activation
+// block, zero-padded to 16 rows, staged per workgroup in LDS (padded rows, one shared all-zero
+// row for the padding lanes; in one stage when the slice fits, else in stages of SC chunks per
+// wavefront whose global loads are issued one stage ahead) and read 16 bytes per lane right
+// before each MFMA.
+// Scales multiply the fp32 partial sum of each group (exact codes into the matrix cores, one
+// fp32 multiply-add per group and output), never the individual weights.  The WK partial
+// results of a tile-row are summed through LDS in a fixed order; an optional global split-K
+// writes fp32 partials to the workspace and a second kernel sums them in a fixed order, so
+// results are bit-reproducible.
+//
+// Memory pipeline.  All global reads go through buffer resources: a load whose offset is
+// beyond the resource's size returns zero without touching memory, so loads that fall outside
+// a wavefront's share (tail chunks, padding rows, padding tile-rows) are issued anyway with an
+// out-of-range offset.  Every wavefront therefore issues the same loads in the same order on
+// every path, which lets the compiler wait with exact vmcnt values instead of draining the
+// queue, and NB register buffers rotate so that NB-1 chunks are in flight while one is
+// consumed.  The activation loads are issued before the weight loads so that staging does
+// not wait behind the (longer) HBM latency of the weights.
 //
 // MFMA operand maps (16x16x32 f16): a-operand lane l = row l % 16, k-slot l / 16 (8 halves);
 // b-operand lane l = column l % 16, same k-slot; result lane l, register e = row 4 (l/16) + e,
@@ -26,9 +37,11 @@
 
 namespace rtn {
 
-constexpr int kChunkTiles = 4;       // tiles (16-byte loads per lane) per k-chunk
-constexpr int kStagePieces = 4;      // 16-byte pieces of activations a thread stages per stage
-constexpr int kLdsPadHalves = 8;     // row padding: row stride = 16 bytes mod 256 bytes
+constexpr int kChunkTiles = 4;            // tiles (16-byte loads per lane) per k-chunk
+constexpr int kStagePieces = 8;           // 16-byte pieces of activations a thread stages per stage (at most)
+constexpr int kLdsPadHalves = 8;          // row stride = 16 bytes mod 256 bytes: conflict-free b128 reads
+constexpr uint32_t kOutOfRange = 0x7FFF0000u;   // beyond any resource size used here (< 2 GiB)
+constexpr int kBufferFlags = 0x00020000;  // raw buffer, 32-bit data format
 
 struct SkinnyParams {
     const half_t* A;
@@ -42,10 +55,15 @@ struct SkinnyParams {
     int NT;           // N / 16
     int KL;           // tiles per row
     int KC;           // chunks per row
-    int WN, WK, wn_shift;   // wave = wk * WN + wn
-    int wk_shift;
+    int WN, WK, wn_shift, wk_shift;   // wave = wk * WN + wn
     int split_k;
-    int lds_rows;     // activation rows staged (min(M, 16))
+    int per;          // chunks per wavefront (largest)
+    int nstage;       // activation stages
+    int sc, sc_shift; // chunks per wavefront per stage (power of two, multiple of NB)
+    int lds_stride;   // halves per staged activation row = WK * sc * CK + pad
+    int srp;          // 16-byte pieces per staged row = WK * sc * CK / 8
+    uint32_t srp_inv; // floor(2^32 / srp) + 1: exact division of a piece index by srp
+    uint32_t qw_bytes, sc_bytes, a_bytes;
 };
 
 template <int BITS>
@@ -54,11 +72,9 @@ struct Geom {
     static constexpr int MPT = Layout<BITS>::MFMA_PER_TILE;
     static constexpr int CK = kChunkTiles * TK;           // k per chunk: 512 / 256
     static constexpr int NM = kChunkTiles * MPT;          // MFMAs per chunk: 16 / 8
-    static constexpr int CK8_SHIFT = (BITS == 4) ? 6 : 5; // log2(CK / 8)
 };
 
-template <int NGC>
-struct ScaleVec;
+template <int NGC> struct ScaleVec;
 template <> struct ScaleVec<1> { typedef uint16_t raw_t; };
 template <> struct ScaleVec<2> { typedef uint32_t raw_t; };
 template <> struct ScaleVec<4> { typedef u32x2_t raw_t; };
@@ -77,180 +93,156 @@ __device__ __forceinline__ float scale_at(const typename ScaleVec<NGC>::raw_t& r
     }
 }
 
-template <int BITS, int R, int NGC>
-__global__ __launch_bounds__(512) void skinny_mfma_kernel(const SkinnyParams p) {
+template <int NGC>
+__device__ __forceinline__ typename ScaleVec<NGC>::raw_t load_scales(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+    if constexpr (NGC == 1) return __builtin_amdgcn_raw_buffer_load_b16(r, off, 0, 0);
+    else if constexpr (NGC == 2) return __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0);
+    else return __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0);
+}
+
+template <int BITS, int NGC, int NB>
+__global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p) {
     typedef Geom<BITS> GM;
     typedef typename ScaleVec<NGC>::raw_t sraw_t;
     extern __shared__ __align__(16) uint8_t lds_bytes[];
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, kept scalar
     const int wn = wave & (p.WN - 1), wk = wave >> p.wn_shift;
     const int nl = lane & 15, kq = lane >> 4;
     const int nthreads = blockDim.x;
 
     const int m0 = blockIdx.z * 16;
     const int Mb = min(16, p.M - m0);
-    const half_t* __restrict__ A = p.A + (int64_t)m0 * p.K;
-
     const int sg = blockIdx.y;
-    const int cb0 = (int)((int64_t)p.KC * sg / p.split_k);
+    const int cb0 = (int)((int64_t)p.KC * sg / p.split_k);           // chunk range of this workgroup
     const int cb1 = (int)((int64_t)p.KC * (sg + 1) / p.split_k);
-    const int nstage = (cb1 - cb0 + p.WK - 1) >> p.wk_shift;
-    const int KS = p.WK * GM::CK;
-    const int ks8_shift = GM::CK8_SHIFT + p.wk_shift;      // log2(KS / 8)
-    const int lds_stride = KS + kLdsPadHalves;             // halves
+    const int cw0 = min(cb0 + wk * p.per, cb1), cw1 = min(cw0 + p.per, cb1);   // ... and of this wavefront
+    const int nt = blockIdx.x * p.WN + wn;
+    const bool nt_ok = nt < p.NT;
+
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.qw), 0, p.qw_bytes, kBufferFlags);
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<half_t*>(p.scales), 0, p.sc_bytes, kBufferFlags);
+    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<half_t*>(p.A), 0, p.a_bytes, kBufferFlags);
+    const uint32_t w_lane = (uint32_t)nt * (uint32_t)p.KL * 1024u + lane * 16;
+    const uint32_t s_lane = ((uint32_t)nt * 16 + nl) * (uint32_t)p.G * 2u;
+    const uint32_t magic = fp16_magic_vgpr();
+
+    // ---- activation staging --------------------------------------------------------------------
+    // A stage holds, for every row and every K-wavefront w, the sc chunks that wavefront w consumes
+    // in this stage: LDS [row][w][sc * CK] (+ pad).  Thread t moves pieces t, t + nthreads, ...; a
+    // piece is 16 bytes: piece -> (row, w, octet).  Rows >= Mb (the shared zero row) and columns past
+    // a wavefront's share are loaded out of range, i.e. as zeros, without memory traffic.
     half_t* lds_a = reinterpret_cast<half_t*>(lds_bytes);
-    const int lds_buf = p.lds_rows * lds_stride;           // halves per buffer
-
-    // tile-rows of this wavefront (clamped for loads, masked for stores)
-    const int ntile0 = (blockIdx.x * p.WN + wn) * R;
-    const uint8_t* wbase[R];
-    const half_t* sbase[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int nt = min(ntile0 + r, p.NT - 1);
-        wbase[r] = p.qw + ((int64_t)nt * p.KL) * 1024 + lane * 16;
-        sbase[r] = p.scales + ((int64_t)nt * 16 + nl) * p.G;
-    }
-
-    // ---- staging helpers -------------------------------------------------------------
+    const int rows_staged = Mb < 16 ? Mb + 1 : 16;
+    constexpr int CK8_SHIFT = (BITS == 4) ? 6 : 5;                     // log2(CK / 8)
+    const int seg_shift = p.sc_shift + CK8_SHIFT;                     // log2(pieces per wavefront segment)
     u32x4_t stg[kStagePieces];
-    auto stage_fetch = [&](int s) {
-        const int kbase = (cb0 + s * p.WK) * GM::CK;
-        const int klimit = cb1 * GM::CK;
-        const int total = Mb << ks8_shift;
+    int stg_off[kStagePieces];
+    auto stage_load = [&](int s) {
 #pragma unroll
         for (int i = 0; i < kStagePieces; ++i) {
-            const int idx = tid + i * nthreads;
-            const int m = idx >> ks8_shift, o = idx & ((1 << ks8_shift) - 1);
-            const int k = kbase + o * 8;
-            if (idx < total && k < klimit)
-                stg[i] = *reinterpret_cast<const u32x4_t*>(A + (int64_t)m * p.K + k);
+            const int piece = tid + i * nthreads;
+            const int row = (int)__umulhi((uint32_t)piece, p.srp_inv), rem = piece - row * p.srp;
+            const int w = rem >> seg_shift, o = rem & ((1 << seg_shift) - 1);
+            const int c0 = min(cb0 + w * p.per, cb1), c1 = min(c0 + p.per, cb1);
+            const int k8 = ((c0 + (s << p.sc_shift)) << CK8_SHIFT) + o;  // column / 8
+            const bool ok = row < Mb && k8 < (c1 << CK8_SHIFT);
+            const uint32_t goff = ok ? (uint32_t)(((int64_t)(m0 + row) * p.K + (int64_t)k8 * 8) * 2) : kOutOfRange;
+            stg[i] = __builtin_amdgcn_raw_buffer_load_b128(ra, goff, 0, 0);
+            stg_off[i] = row < rows_staged ? row * p.lds_stride + rem * 8 : -1;
         }
     };
-    auto stage_commit = [&](int s) {
-        const int kbase = (cb0 + s * p.WK) * GM::CK;
-        const int klimit = cb1 * GM::CK;
-        const int total = Mb << ks8_shift;
-        half_t* dst = lds_a + (s & 1) * lds_buf;
+    auto stage_store = [&]() {
 #pragma unroll
-        for (int i = 0; i < kStagePieces; ++i) {
-            const int idx = tid + i * nthreads;
-            const int m = idx >> ks8_shift, o = idx & ((1 << ks8_shift) - 1);
-            const int k = kbase + o * 8;
-            if (idx < total && k < klimit)
-                *reinterpret_cast<u32x4_t*>(dst + m * lds_stride + o * 8) = stg[i];
-        }
+        for (int i = 0; i < kStagePieces; ++i)
+            if (stg_off[i] >= 0) *reinterpret_cast<u32x4_t*>(lds_a + stg_off[i]) = stg[i];
     };
 
-    // ---- weight / scale prefetch -----------------------------------------------------
-    auto scale_index = [&](int ci) -> int64_t {
-        // first group of chunk ci: ci * CK / g
-        return (NGC > 1) ? (int64_t)ci * NGC : ((int64_t)ci * GM::CK) / p.g;
-    };
-    auto fetch_w = [&](int r, int ci, u32x4_t (&wv)[kChunkTiles], sraw_t& sv) {
-        const uint8_t* src = wbase[r] + (int64_t)ci * (kChunkTiles * 1024);
+    // ---- weight / scale prefetch: NB chunks in flight --------------------------------------------
+    u32x4_t wbuf[NB][kChunkTiles];
+    sraw_t sbuf[NB];
+    auto fetch = [&](int j, int ci) {
+        const bool ok = nt_ok && ci < cw1;                            // wave-uniform
+        const uint32_t si = (NGC > 1) ? (uint32_t)ci * NGC : ((uint32_t)ci * GM::CK) / (uint32_t)p.g;
+        const uint32_t so = ok ? s_lane + si * 2u : kOutOfRange;
+        const uint32_t wo = ok ? w_lane + (uint32_t)ci * (kChunkTiles * 1024u) : kOutOfRange;
+        sbuf[j] = load_scales<NGC>(rs, so);                           // scales first: never the last to arrive
 #pragma unroll
-        for (int c = 0; c < kChunkTiles; ++c) wv[c] = load_stream16(src + c * 1024);
-        sv = *reinterpret_cast<const sraw_t*>(sbase[r] + scale_index(ci));
+        for (int c = 0; c < kChunkTiles; ++c)
+            wbuf[j][c] = __builtin_amdgcn_raw_buffer_load_b128(rw, wo + c * 1024, 0, 2 /* nt: read-once stream */);
     };
 
-    float4_t acc[R];
+    stage_load(0);                        // activation loads first: the oldest loads in flight
 #pragma unroll
-    for (int r = 0; r < R; ++r) acc[r] = (float4_t){0.f, 0.f, 0.f, 0.f};
-
-    u32x4_t wnext[kChunkTiles];
-    sraw_t snext;
-    int ci = cb0 + wk;                                     // this wavefront's chunk in stage 0
-    if (ci < cb1) fetch_w(0, ci, wnext, snext);            // in flight while activations are staged
-    stage_fetch(0);
-    stage_commit(0);
+    for (int j = 0; j < NB; ++j) fetch(j, cw0 + j);
+    stage_store();
     __syncthreads();
 
-    for (int s = 0; s < nstage; ++s) {
-        const bool more = (s + 1 < nstage);
-        if (more) stage_fetch(s + 1);
-        const bool valid = ci < cb1;
-        half8_t areg[GM::NM];
-        if (valid) {
-            const half_t* src = lds_a + (s & 1) * lds_buf + nl * lds_stride + wk * GM::CK + kq * 8;
+    // ---- main loop -------------------------------------------------------------------------------
+    float4_t acc = {0.f, 0.f, 0.f, 0.f};
+    const half_t* arow = lds_a + min(nl, Mb) * p.lds_stride + ((wk << p.sc_shift) * GM::CK) + kq * 8;
+    int ci = cw0;
+    for (int s = 0; s < p.nstage; ++s) {
+        stage_load(s + 1);                // next stage's activations (out of range past the last stage)
+        const half_t* abase = arow;
+        for (int u = 0; u < p.sc; u += NB) {
 #pragma unroll
-            for (int i = 0; i < GM::NM; ++i) {
-                if (nl < Mb) areg[i] = *reinterpret_cast<const half8_t*>(src + i * 32);
-                else areg[i] = (half8_t){0, 0, 0, 0, 0, 0, 0, 0};
-            }
-        }
+            for (int j = 0; j < NB; ++j) {
+                if (ci < cw1) {                                       // scalar branch, no loads inside
+                    constexpr int MPG = GM::NM / NGC;                 // MFMAs per group
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            u32x4_t wcur[kChunkTiles];
-            sraw_t scur = snext;
+                    for (int gi = 0; gi < NGC; ++gi) {
+                        float4_t part = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int c = 0; c < kChunkTiles; ++c) wcur[c] = wnext[c];
-            // issue the next step's loads before computing this one
-            if (r + 1 < R) {
-                if (valid) fetch_w(r + 1, ci, wnext, snext);
-            } else {
-                if (ci + p.WK < cb1) fetch_w(0, ci + p.WK, wnext, snext);
-            }
-            if (valid) {
-                constexpr int TPGRP = kChunkTiles / NGC;   // tiles per group inside a chunk
-#pragma unroll
-                for (int gi = 0; gi < NGC; ++gi) {
-                    float4_t part = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int c = gi * TPGRP; c < (gi + 1) * TPGRP; ++c) {
-#pragma unroll
-                        for (int t = 0; t < GM::MPT; ++t) {
-                            const half8_t b = unpack_operand<BITS>(wcur[c], t);
-                            part = __builtin_amdgcn_mfma_f32_16x16x32_f16(areg[c * GM::MPT + t], b, part, 0, 0, 0);
+                        for (int q = 0; q < MPG; ++q) {
+                            const int i = gi * MPG + q;
+                            const half8_t a = *reinterpret_cast<const half8_t*>(abase + i * 32);
+                            const half8_t b = unpack_operand<BITS>(wbuf[j][i / GM::MPT], i % GM::MPT, magic);
+                            part = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, part, 0, 0, 0);
                         }
-                    }
-                    const float sc = scale_at<NGC>(scur, gi);
+                        const float sc = scale_at<NGC>(sbuf[j], gi);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[r][e] = fmaf(sc, part[e], acc[r][e]);
+                        for (int e = 0; e < 4; ++e) acc[e] = fmaf(sc, part[e], acc[e]);
+                    }
                 }
+                fetch(j, ci + NB);        // unconditional: out of range past the wavefront's share
+                abase += GM::CK;
+                ++ci;
             }
         }
-        if (more) stage_commit(s + 1);
-        __syncthreads();
-        ci += p.WK;
+        if (s + 1 < p.nstage) {           // uniform: swap in the next stage
+            __syncthreads();              // everyone is done reading this stage
+            stage_store();
+            __syncthreads();
+        }
     }
 
-    // ---- in-workgroup split-K reduction (fixed order) ----------------------------------
+    // ---- in-workgroup split-K reduction (fixed order) ------------------------------------------
     if (p.WK > 1) {
+        __syncthreads();                  // everyone is done reading the staged activations
         float4_t* red = reinterpret_cast<float4_t*>(lds_bytes);
-        if (wk > 0) {
-#pragma unroll
-            for (int r = 0; r < R; ++r) red[(((wk - 1) * p.WN + wn) * R + r) * 64 + lane] = acc[r];
-        }
+        if (wk > 0) red[((wk - 1) * p.WN + wn) * 64 + lane] = acc;
         __syncthreads();
         if (wk == 0) {
             for (int w = 1; w < p.WK; ++w) {
+                const float4_t v = red[((w - 1) * p.WN + wn) * 64 + lane];
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    const float4_t v = red[(((w - 1) * p.WN + wn) * R + r) * 64 + lane];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[r][e] += v[e];
-                }
+                for (int e = 0; e < 4; ++e) acc[e] += v[e];
             }
         }
     }
-    if (wk != 0) return;
+    if (wk != 0 || !nt_ok) return;
 
-    // ---- store: lane holds rows m = 4 kq + e, column n = 16 tile + nl --------------------
+    // ---- store: lane holds rows m = 4 kq + e, column n = 16 tile + nl ----------------------------
+    const int n = nt * 16 + nl;
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int nt = ntile0 + r;
-        if (nt >= p.NT) continue;
-        const int n = nt * 16 + nl;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int m = kq * 4 + e;
-            if (m < Mb) {
-                if (p.split_k == 1) p.C[(int64_t)(m0 + m) * p.N + n] = (half_t)acc[r][e];
-                else p.ws[((int64_t)sg * p.M + (m0 + m)) * p.N + n] = acc[r][e];
-            }
+    for (int e = 0; e < 4; ++e) {
+        const int m = kq * 4 + e;
+        if (m < Mb) {
+            if (p.split_k == 1) p.C[(int64_t)(m0 + m) * p.N + n] = (half_t)acc[e];
+            else p.ws[((int64_t)sg * p.M + (m0 + m)) * p.N + n] = acc[e];
         }
     }
 }
@@ -259,23 +251,12 @@ __global__ __launch_bounds__(512) void skinny_mfma_kernel(const SkinnyParams p) 
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ ws, half_t* __restrict__ C,
                                                             int64_t MN, int split_k) {
     const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-    if (i >= MN) return;
-    if (i + 4 <= MN) {
-        float4_t v = *reinterpret_cast<const float4_t*>(ws + i);
-        for (int s = 1; s < split_k; ++s) {
-            const float4_t u = *reinterpret_cast<const float4_t*>(ws + (int64_t)s * MN + i);
-            v += u;
-        }
-        typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
-        half4_t h = {(half_t)v[0], (half_t)v[1], (half_t)v[2], (half_t)v[3]};
-        *reinterpret_cast<half4_t*>(C + i) = h;
-    } else {
-        for (int64_t j = i; j < MN; ++j) {
-            float v = ws[j];
-            for (int s = 1; s < split_k; ++s) v += ws[(int64_t)s * MN + j];
-            C[j] = (half_t)v;
-        }
-    }
+    if (i >= MN) return;                                  // MN is a multiple of 16
+    float4_t v = *reinterpret_cast<const float4_t*>(ws + i);
+    for (int s = 1; s < split_k; ++s) v += *reinterpret_cast<const float4_t*>(ws + (int64_t)s * MN + i);
+    typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+    half4_t h = {(half_t)v[0], (half_t)v[1], (half_t)v[2], (half_t)v[3]};
+    *reinterpret_cast<half4_t*>(C + i) = h;
 }
 
 static int ilog2(int v) {
@@ -284,33 +265,83 @@ static int ilog2(int v) {
     return s;
 }
 
-size_t linear_lds_bytes(const LinearArgs& a, const LinearPlan& p) {
+// Geometry the kernel and the LDS budget share: chunks per wavefront, chunks per wavefront per
+// activation stage (power of two, multiple of the prefetch depth), number of stages.
+struct StageGeom {
+    int per, sc, nstage, rows;
+    size_t lds;
+};
+
+static StageGeom stage_geometry(const LinearArgs& a, const LinearPlan& p, size_t lds_budget) {
     const int ck = (a.bits == 4) ? 512 : 256;
-    const int rows = (int)(a.M < 16 ? a.M : 16);
-    const size_t stage = (size_t)2 * rows * (p.waves_k * ck + kLdsPadHalves) * 2;
-    const size_t red = p.waves_k > 1 ? (size_t)(p.waves_k - 1) * p.waves_n * p.r_tiles * 1024 : 0;
-    return stage > red ? stage : red;
+    const int kc = (int)(a.K / ck);
+    const int blk = (kc + p.split_k - 1) / p.split_k;                 // chunks per workgroup
+    StageGeom g;
+    g.per = (blk + p.waves_k - 1) / p.waves_k;
+    g.rows = (int)(a.M < 16 ? a.M + 1 : 16);
+    const int nthreads = 64 * p.waves_n * p.waves_k;
+    int sc = p.prefetch;
+    while (sc < g.per) sc *= 2;                                       // whole share in one stage if it fits
+    const size_t red = p.waves_k > 1 ? (size_t)(p.waves_k - 1) * p.waves_n * 1024 : 0;
+    for (;;) {
+        const size_t bytes = (size_t)g.rows * ((size_t)p.waves_k * sc * ck + kLdsPadHalves) * 2;
+        const int64_t pieces = (int64_t)g.rows * p.waves_k * sc * (ck / 8);
+        if ((bytes <= lds_budget && pieces <= (int64_t)nthreads * kStagePieces) || sc == p.prefetch) {
+            g.lds = bytes > red ? bytes : red;
+            break;
+        }
+        sc /= 2;
+    }
+    g.sc = sc;
+    g.nstage = (g.per + sc - 1) / sc;
+    return g;
 }
 
-template <int BITS, int R>
-static hipError_t launch_skinny_ngc(const SkinnyParams& sp, int ngc, dim3 grid, dim3 block, size_t lds,
-                                    hipStream_t st) {
+// Staging budget: a stage is kept to a quarter of the LDS of a compute unit when it must be split
+// anyway, so that several workgroups stay resident.
+static size_t stage_budget(const LinearArgs& a, const LinearPlan& p) {
+    (void)a; (void)p;
+    return 66 * 1024;                     // 64 KiB of activations plus the row padding
+}
+
+bool linear_plan_fits(const LinearArgs& a, const LinearPlan& p, size_t lds_limit) {
+    const StageGeom g = stage_geometry(a, p, stage_budget(a, p));
+    const int ck = (a.bits == 4) ? 512 : 256;
+    const int64_t pieces = (int64_t)g.rows * p.waves_k * g.sc * (ck / 8);
+    return g.lds <= lds_limit && pieces <= (int64_t)64 * p.waves_n * p.waves_k * kStagePieces;
+}
+
+size_t linear_lds_bytes(const LinearArgs& a, const LinearPlan& p) {
+    return stage_geometry(a, p, stage_budget(a, p)).lds;
+}
+
+template <typename K>
+static void allow_large_lds(K kernel) {
+    static bool done = false;             // per instantiation
+    if (!done) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)kMaxLdsBytes);
+        done = true;
+    }
+}
+
+template <int BITS, int NB>
+static hipError_t launch_skinny_ngc(const SkinnyParams& sp, int ngc, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
     switch (ngc) {
-        case 1: hipLaunchKernelGGL((skinny_mfma_kernel<BITS, R, 1>), grid, block, lds, st, sp); break;
-        case 2: hipLaunchKernelGGL((skinny_mfma_kernel<BITS, R, 2>), grid, block, lds, st, sp); break;
-        default: hipLaunchKernelGGL((skinny_mfma_kernel<BITS, R, 4>), grid, block, lds, st, sp); break;
+        case 1:
+            allow_large_lds(skinny_mfma_kernel<BITS, 1, NB>);
+            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 1, NB>), grid, block, lds, st, sp);
+            break;
+        case 2:
+            allow_large_lds(skinny_mfma_kernel<BITS, 2, NB>);
+            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 2, NB>), grid, block, lds, st, sp);
+            break;
+        default:
+            allow_large_lds(skinny_mfma_kernel<BITS, 4, NB>);
+            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 4, NB>), grid, block, lds, st, sp);
+            break;
     }
     return hipGetLastError();
-}
-
-template <int BITS>
-static hipError_t launch_skinny_r(const SkinnyParams& sp, int r, int ngc, dim3 grid, dim3 block, size_t lds,
-                                  hipStream_t st) {
-    switch (r) {
-        case 1: return launch_skinny_ngc<BITS, 1>(sp, ngc, grid, block, lds, st);
-        case 2: return launch_skinny_ngc<BITS, 2>(sp, ngc, grid, block, lds, st);
-        default: return launch_skinny_ngc<BITS, 4>(sp, ngc, grid, block, lds, st);
-    }
 }
 
 hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t st) {
@@ -332,18 +363,34 @@ hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t s
     sp.wn_shift = ilog2(p.waves_n);
     sp.wk_shift = ilog2(p.waves_k);
     sp.split_k = p.split_k;
-    sp.lds_rows = (int)(a.M < 16 ? a.M : 16);
+    const StageGeom sgm = stage_geometry(a, p, stage_budget(a, p));
+    sp.per = sgm.per;
+    sp.sc = sgm.sc;
+    sp.sc_shift = ilog2(sgm.sc);
+    sp.nstage = sgm.nstage;
+    sp.srp = p.waves_k * sgm.sc * (ck / 8);
+    sp.srp_inv = (uint32_t)(((uint64_t)1 << 32) / (uint32_t)sp.srp) + 1u;
+    sp.lds_stride = p.waves_k * sgm.sc * ck + kLdsPadHalves;
+    const int nthreads = 64 * p.waves_n * p.waves_k;
+    sp.qw_bytes = (uint32_t)((size_t)a.N * a.K * a.bits / 8);
+    sp.sc_bytes = (uint32_t)((size_t)a.N * sp.G * 2);
+    sp.a_bytes = (uint32_t)((size_t)a.M * a.K * 2);
     const int ngc = (a.g >= ck) ? 1 : (int)(ck / a.g);
-    const int rows_per_block = p.waves_n * p.r_tiles;
-    dim3 grid((unsigned)((sp.NT + rows_per_block - 1) / rows_per_block), (unsigned)p.split_k, (unsigned)p.m_blocks);
-    dim3 block((unsigned)(64 * p.waves_n * p.waves_k));
-    const size_t lds = linear_lds_bytes(a, p);
-    hipError_t e = (a.bits == 4) ? launch_skinny_r<4>(sp, p.r_tiles, ngc, grid, block, lds, st)
-                                 : launch_skinny_r<8>(sp, p.r_tiles, ngc, grid, block, lds, st);
+    dim3 grid((unsigned)((sp.NT + p.waves_n - 1) / p.waves_n), (unsigned)p.split_k, (unsigned)p.m_blocks);
+    dim3 block((unsigned)nthreads);
+    const size_t lds = sgm.lds;
+    hipError_t e;
+    if (a.bits == 4) {
+        e = (p.prefetch == 1) ? launch_skinny_ngc<4, 1>(sp, ngc, grid, block, lds, st)
+                              : launch_skinny_ngc<4, 2>(sp, ngc, grid, block, lds, st);
+    } else {
+        e = (p.prefetch == 1) ? launch_skinny_ngc<8, 1>(sp, ngc, grid, block, lds, st)
+                              : launch_skinny_ngc<8, 2>(sp, ngc, grid, block, lds, st);
+    }
     if (e != hipSuccess) return e;
     if (p.split_k > 1) {
         const int64_t MN = a.M * a.N;
-        dim3 rgrid((unsigned)((MN / 4 + 255) / 256 + 1)), rblock(256);
+        dim3 rgrid((unsigned)((MN / 4 + 255) / 256)), rblock(256);
         hipLaunchKernelGGL(splitk_reduce_kernel, rgrid, rblock, 0, st, a.workspace, sp.C, MN, p.split_k);
         e = hipGetLastError();
     }

@@ -181,9 +181,10 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t* __restrict__
     const int nl = lane & 15, kq = lane >> 4;
     const u32x4_t chunk = *reinterpret_cast<const u32x4_t*>(qweight + chunk_id * 16);
     const int64_t n = nt * 16 + nl;
+    const uint32_t magic = fp16_magic_vgpr();
 #pragma unroll
     for (int i = 0; i < MPT; ++i) {
-        const half8_t v = unpack_operand<BITS>(chunk, i);     // exact integers as fp16
+        const half8_t v = unpack_operand<BITS>(chunk, i, magic);     // exact integers as fp16
         const int64_t k = kt * TK + i * 32 + kq * 8;
         if constexpr (DEQUANT) {
             const half_t s = scales[n * (K / g) + k / g];

@@ -60,10 +60,14 @@ def test_argument_validation_happens_before_any_launch():
     assert _linear(g=100) == 3
     assert _linear(M=0) == 4 and _linear(K=500) == 4
     assert _linear(A=FAKE + 4) == 5
-    cfg = rtn.rtn_linear_cfg(path=1, r_tiles=3)
+    cfg = rtn.rtn_linear_cfg(path=1, prefetch=3)
     assert _linear(cfg=C.byref(cfg)) == 7
-    cfg = rtn.rtn_linear_cfg(waves_n=1, waves_k=1)
-    assert _linear(M=16, cfg=C.byref(cfg)) == 7                   # 16 rows need >= 4 wavefronts along N
+    cfg = rtn.rtn_linear_cfg(waves_n=3)
+    assert _linear(cfg=C.byref(cfg)) == 7                         # wavefront counts are powers of two
+    cfg = rtn.rtn_linear_cfg(waves_n=8, waves_k=4)
+    assert _linear(cfg=C.byref(cfg)) == 7                         # at most 16 wavefronts per workgroup
+    cfg = rtn.rtn_linear_cfg(path=2)
+    assert _linear(cfg=C.byref(cfg)) == 7
     cfg = rtn.rtn_linear_cfg(split_k=2)
     assert _linear(K=1024, wsn=16, cfg=C.byref(cfg)) == 6         # workspace too small
     cfg = rtn.rtn_linear_cfg(split_k=4)

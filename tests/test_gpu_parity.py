@@ -106,9 +106,10 @@ def _oracle_operands(N, K, bits, g, seed, dist="normal02"):
     return codes, scales, qw, sc, gg
 
 
-CFGS = [dict(r_tiles=r, waves_n=wn, waves_k=wk, split_k=sk)
-        for r, wn, wk, sk in [(1, 1, 1, 1), (1, 1, 4, 1), (2, 1, 2, 2), (1, 2, 2, 1), (2, 2, 1, 3), (4, 1, 1, 1),
-                              (1, 4, 1, 1), (2, 4, 2, 2), (4, 4, 1, 1), (1, 1, 8, 1), (1, 8, 1, 2), (4, 2, 4, 4)]]
+CFGS = [dict(prefetch=nb, waves_n=wn, waves_k=wk, split_k=sk)
+        for nb, wn, wk, sk in [(1, 1, 1, 1), (1, 1, 4, 1), (2, 1, 2, 2), (1, 2, 2, 1), (2, 2, 1, 3), (2, 1, 1, 1),
+                               (1, 4, 1, 1), (2, 4, 2, 2), (2, 4, 1, 1), (1, 1, 8, 1), (1, 8, 1, 2), (2, 2, 4, 4),
+                               (1, 1, 16, 1), (2, 16, 1, 1), (1, 2, 8, 1), (2, 8, 2, 1)]]
 
 
 @pytest.mark.parametrize("bits,g", [(4, 128), (4, 256), (4, 512), (4, 0), (8, 64), (8, 128), (8, 256), (8, 0)])
@@ -118,16 +119,22 @@ def test_linear_all_configs_small(rtn, bits, g):
     for M in (1, 2, 3, 4, 5, 8, 13, 16):
         A_t = synth.activation(M, K, seed=100 + M, device=DEV)
         ref = O.rtn_linear(_to_np(A_t), codes, scales, gg)
-        cap = 4 if bits == 4 else 8
+        ran = 0
         for cfg in CFGS:
-            if cfg["waves_n"] * cap < min(M, 16):
-                continue                                   # staging capacity of the N-wavefronts
-            ck = 512 if bits == 4 else 256
-            if 2 * min(M, 16) * (cfg["waves_k"] * ck + 8) * 2 > 65536:
-                continue                                   # LDS budget
-            C = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=cfg)
+            if cfg["split_k"] > K // (512 if bits == 4 else 256):
+                continue
+            try:
+                C = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=cfg)
+            except rtn.RtnError as e:
+                # the only legitimate refusal: too few threads to stage this many activation rows
+                rows = M + 1 if M < 16 else 16
+                assert e.status == 7
+                assert rows * cfg["prefetch"] * ((512 if bits == 4 else 256) // 8) > 512 * cfg["waves_n"]
+                continue
             torch.cuda.synchronize()
+            ran += 1
             H.assert_linear_close(_to_np(C), ref, f"bits={bits} g={g} M={M} cfg={cfg}")
+        assert ran >= 6
         C = rtn.rtn_linear(A_t, qw, sc, bits, g)          # automatic plan
         torch.cuda.synchronize()
         H.assert_linear_close(_to_np(C), ref, f"bits={bits} g={g} M={M} auto")
@@ -178,7 +185,7 @@ def test_linear_special_cases(rtn, bits, g):
 def test_linear_is_deterministic(rtn):
     N, K = 512, 4096
     codes, scales, qw, sc, gg = _oracle_operands(N, K, 4, 128, seed=12)
-    for M, cfg in ((1, dict(waves_k=4, split_k=2)), (16, dict(waves_n=4, waves_k=1, split_k=4)), (8, dict(waves_n=2, waves_k=2, split_k=2)), (3, None)):
+    for M, cfg in ((1, dict(waves_k=4, split_k=2)), (16, dict(waves_n=4, waves_k=1, split_k=4)), (8, dict(waves_n=4, waves_k=2, split_k=2, prefetch=2)), (3, None)):
         A_t = synth.activation(M, K, seed=1, device=DEV)
         outs = [rtn.rtn_linear(A_t, qw, sc, 4, 128, cfg=cfg).clone() for _ in range(5)]
         torch.cuda.synchronize()
