@@ -64,28 +64,45 @@ int round_pow2(int64_t v, int lo, int hi) {
     return p;
 }
 
-// Default plan (measured on MI355X; see the design notes).  Short-lived wavefronts at high occupancy
-// stream best: each wavefront gets 1-4 k-chunks (4-16 KiB of packed weights) of one tile-row, eight
-// wavefronts form a workgroup, and K is split inside the workgroup (reduced through LDS), never
-// across workgroups unless the staged activation slice would not fit in LDS.
+// Default plan, from sweeps on MI355X (see the design notes).  Short-lived wavefronts at high
+// occupancy stream best: a wavefront gets 1-4 k-chunks (4-16 KiB of packed weights) of one tile-row
+// and K is split inside the workgroup (reduced through LDS).  With more than two activation rows the
+// staged slice grows, so workgroups widen along N (sharing it) and, for long K, K is also split across
+// workgroups so that a slice stays a few chunks long; those partials go through the workspace.
 LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, size_t lds_limit) {
     LinearPlan p;
     const int64_t NT = N / 16, KC = K / chunk_k(bits);
     const int64_t steps = NT * KC;                             // 4 KiB chunk-steps in the whole matrix
+    const int rows = (int)(M < 16 ? M + 1 : 16);
     p.path = 1;
     p.m_blocks = (int)((M + 15) / 16);
     p.prefetch = 1;
     p.split_k = 1;
-    const int64_t per_wave = steps <= 6144 ? 1 : (steps <= 24576 ? 2 : 4);
-    p.waves_k = round_pow2((KC + per_wave - 1) / per_wave, 1, 16);
-    while (p.waves_k > KC) p.waves_k /= 2;
-    p.waves_n = 8 / p.waves_k > 0 ? 8 / p.waves_k : 1;
+    if (rows <= 3) {
+        const int64_t per_wave = steps <= 6144 ? 1 : (steps <= 24576 ? 2 : 4);
+        p.waves_k = round_pow2((KC + per_wave - 1) / per_wave, 1, 16);
+        while (p.waves_k > KC) p.waves_k /= 2;
+        p.waves_n = 8 / p.waves_k > 0 ? 8 / p.waves_k : 1;
+    } else if (steps <= 6144) {
+        p.waves_k = round_pow2(KC, 1, 8);
+        while (p.waves_k > KC) p.waves_k /= 2;
+        p.waves_n = NT >= 384 ? 2 : 1;
+    } else {
+        p.waves_n = 4;
+        p.waves_k = (KC <= 16 && rows <= 9) ? 4 : 2;
+        if (KC > 16) {
+            int64_t split = (KC + 7) / 8;                      // about 8 chunks per workgroup
+            while (split > 1 && (split > kMaxSplitK || (size_t)M * N * sizeof(float) * split > kWorkspaceCap)) --split;
+            p.split_k = (int)split;
+        }
+    }
     while (p.waves_n > 1 && p.waves_n > NT) p.waves_n /= 2;
-    // a stage of rows x (waves_k x 512) activations is moved by the workgroup's threads, 8 pieces each
-    const int rows = (int)(M < 16 ? M + 1 : 16);
-    while (rows * p.prefetch > 8 * p.waves_n) p.waves_n *= 2;
-    while (p.waves_n * p.waves_k > 16) p.waves_k /= 2;
-    (void)lds_limit;                       // the kernel stages activations in pieces that always fit
+    LinearArgs a;
+    a.M = M; a.N = N; a.K = K; a.bits = bits; a.g = K;
+    while (!rtn::linear_plan_fits(a, p, lds_limit) && p.waves_n < 16) {   // more threads to stage the rows
+        p.waves_n *= 2;
+        while (p.waves_n * p.waves_k > 16) p.waves_k /= 2;
+    }
     return p;
 }
 

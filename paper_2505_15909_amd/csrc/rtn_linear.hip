@@ -38,7 +38,7 @@
 namespace rtn {
 
 constexpr int kChunkTiles = 4;            // tiles (16-byte loads per lane) per k-chunk
-constexpr int kStagePieces = 8;           // 16-byte pieces of activations a thread stages per stage (at most)
+constexpr int kStagePieces = 4;           // 16-byte pieces of activations a thread moves per staging round
 constexpr int kLdsPadHalves = 8;          // row stride = 16 bytes mod 256 bytes: conflict-free b128 reads
 constexpr uint32_t kOutOfRange = 0x7FFF0000u;   // beyond any resource size used here (< 2 GiB)
 constexpr int kBufferFlags = 0x00020000;  // raw buffer, 32-bit data format
@@ -58,7 +58,8 @@ struct SkinnyParams {
     int WN, WK, wn_shift, wk_shift;   // wave = wk * WN + wn
     int split_k;
     int per;          // chunks per wavefront (largest)
-    int nstage;       // activation stages
+    int nstage;       // activation stages (1 unless MULTI)
+    int stage_rounds; // staging rounds of kStagePieces pieces per thread for the single stage
     int sc, sc_shift; // chunks per wavefront per stage (power of two, multiple of NB)
     int lds_stride;   // halves per staged activation row = WK * sc * CK + pad
     int srp;          // 16-byte pieces per staged row = WK * sc * CK / 8
@@ -100,7 +101,9 @@ __device__ __forceinline__ typename ScaleVec<NGC>::raw_t load_scales(__amdgpu_bu
     else return __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0);
 }
 
-template <int BITS, int NGC, int NB>
+// MULTI = false: the workgroup's whole activation slice is staged once, before the main loop.
+// MULTI = true: it is staged sc chunks per wavefront at a time, one stage ahead, one round per stage.
+template <int BITS, int NGC, int NB, bool MULTI>
 __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p) {
     typedef Geom<BITS> GM;
     typedef typename ScaleVec<NGC>::raw_t sraw_t;
@@ -140,10 +143,10 @@ __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p)
     const int seg_shift = p.sc_shift + CK8_SHIFT;                     // log2(pieces per wavefront segment)
     u32x4_t stg[kStagePieces];
     int stg_off[kStagePieces];
-    auto stage_load = [&](int s) {
+    auto stage_load = [&](int s, int round) {
 #pragma unroll
         for (int i = 0; i < kStagePieces; ++i) {
-            const int piece = tid + i * nthreads;
+            const int piece = tid + (round * kStagePieces + i) * nthreads;
             const int row = (int)__umulhi((uint32_t)piece, p.srp_inv), rem = piece - row * p.srp;
             const int w = rem >> seg_shift, o = rem & ((1 << seg_shift) - 1);
             const int c0 = min(cb0 + w * p.per, cb1), c1 = min(c0 + p.per, cb1);
@@ -174,10 +177,16 @@ __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p)
             wbuf[j][c] = __builtin_amdgcn_raw_buffer_load_b128(rw, wo + c * 1024, 0, 2 /* nt: read-once stream */);
     };
 
-    stage_load(0);                        // activation loads first: the oldest loads in flight
+    stage_load(0, 0);                     // activation loads first: the oldest loads in flight
 #pragma unroll
     for (int j = 0; j < NB; ++j) fetch(j, cw0 + j);
     stage_store();
+    if constexpr (!MULTI) {
+        for (int r = 1; r < p.stage_rounds; ++r) {                    // rest of a large single stage
+            stage_load(0, r);
+            stage_store();
+        }
+    }
     __syncthreads();
 
     // ---- main loop -------------------------------------------------------------------------------
@@ -185,7 +194,7 @@ __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p)
     const half_t* arow = lds_a + min(nl, Mb) * p.lds_stride + ((wk << p.sc_shift) * GM::CK) + kq * 8;
     int ci = cw0;
     for (int s = 0; s < p.nstage; ++s) {
-        stage_load(s + 1);                // next stage's activations (out of range past the last stage)
+        if constexpr (MULTI) stage_load(s + 1, 0);   // next stage's activations (out of range past the last)
         const half_t* abase = arow;
         for (int u = 0; u < p.sc; u += NB) {
 #pragma unroll
@@ -212,10 +221,12 @@ __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p)
                 ++ci;
             }
         }
-        if (s + 1 < p.nstage) {           // uniform: swap in the next stage
-            __syncthreads();              // everyone is done reading this stage
-            stage_store();
-            __syncthreads();
+        if constexpr (MULTI) {
+            if (s + 1 < p.nstage) {       // uniform: swap in the next stage
+                __syncthreads();          // everyone is done reading this stage
+                stage_store();
+                __syncthreads();
+            }
         }
     }
 
@@ -266,13 +277,19 @@ static int ilog2(int v) {
 }
 
 // Geometry the kernel and the LDS budget share: chunks per wavefront, chunks per wavefront per
-// activation stage (power of two, multiple of the prefetch depth), number of stages.
+// activation stage (power of two, multiple of the prefetch depth), number of stages.  A slice that
+// fits kSingleStageLds is staged at once (any number of rounds); otherwise stages are sized so that
+// one round of kStagePieces pieces per thread moves a stage and it stays within kMultiStageLds.
+constexpr size_t kSingleStageLds = 64 * 1024 + 1024;
+constexpr size_t kMultiStageLds = 32 * 1024 + 1024;
+
 struct StageGeom {
-    int per, sc, nstage, rows;
+    int per, sc, nstage, rows, rounds;
+    bool multi, fits;
     size_t lds;
 };
 
-static StageGeom stage_geometry(const LinearArgs& a, const LinearPlan& p, size_t lds_budget) {
+static StageGeom stage_geometry(const LinearArgs& a, const LinearPlan& p) {
     const int ck = (a.bits == 4) ? 512 : 256;
     const int kc = (int)(a.K / ck);
     const int blk = (kc + p.split_k - 1) / p.split_k;                 // chunks per workgroup
@@ -280,40 +297,39 @@ static StageGeom stage_geometry(const LinearArgs& a, const LinearPlan& p, size_t
     g.per = (blk + p.waves_k - 1) / p.waves_k;
     g.rows = (int)(a.M < 16 ? a.M + 1 : 16);
     const int nthreads = 64 * p.waves_n * p.waves_k;
-    int sc = p.prefetch;
-    while (sc < g.per) sc *= 2;                                       // whole share in one stage if it fits
     const size_t red = p.waves_k > 1 ? (size_t)(p.waves_k - 1) * p.waves_n * 1024 : 0;
-    for (;;) {
-        const size_t bytes = (size_t)g.rows * ((size_t)p.waves_k * sc * ck + kLdsPadHalves) * 2;
-        const int64_t pieces = (int64_t)g.rows * p.waves_k * sc * (ck / 8);
-        if ((bytes <= lds_budget && pieces <= (int64_t)nthreads * kStagePieces) || sc == p.prefetch) {
-            g.lds = bytes > red ? bytes : red;
-            break;
+    auto bytes_of = [&](int sc) { return (size_t)g.rows * ((size_t)p.waves_k * sc * ck + kLdsPadHalves) * 2; };
+    auto pieces_of = [&](int sc) { return (int64_t)g.rows * p.waves_k * sc * (ck / 8); };
+    int sc_full = p.prefetch;
+    while (sc_full < g.per) sc_full *= 2;                             // whole share in one stage
+    int sc = sc_full;
+    g.fits = true;
+    g.multi = false;
+    if (bytes_of(sc_full) > kSingleStageLds) {
+        // largest stage that one round moves and that leaves room for several workgroups per CU
+        int m = sc_full / 2;
+        while (m >= p.prefetch && (bytes_of(m) > kMultiStageLds || pieces_of(m) > (int64_t)nthreads * kStagePieces)) m /= 2;
+        if (m >= p.prefetch && m > 0) {
+            g.multi = true;
+            sc = m;
+        } else {
+            g.fits = bytes_of(sc_full) <= kMaxLdsBytes;               // one large stage, several rounds
         }
-        sc /= 2;
     }
     g.sc = sc;
-    g.nstage = (g.per + sc - 1) / sc;
+    g.nstage = g.multi ? (g.per + sc - 1) / sc : 1;
+    g.rounds = (int)((pieces_of(sc) + (int64_t)nthreads * kStagePieces - 1) / ((int64_t)nthreads * kStagePieces));
+    const size_t bytes = bytes_of(sc);
+    g.lds = bytes > red ? bytes : red;
     return g;
 }
 
-// Staging budget: a stage is kept to a quarter of the LDS of a compute unit when it must be split
-// anyway, so that several workgroups stay resident.
-static size_t stage_budget(const LinearArgs& a, const LinearPlan& p) {
-    (void)a; (void)p;
-    return 66 * 1024;                     // 64 KiB of activations plus the row padding
-}
-
 bool linear_plan_fits(const LinearArgs& a, const LinearPlan& p, size_t lds_limit) {
-    const StageGeom g = stage_geometry(a, p, stage_budget(a, p));
-    const int ck = (a.bits == 4) ? 512 : 256;
-    const int64_t pieces = (int64_t)g.rows * p.waves_k * g.sc * (ck / 8);
-    return g.lds <= lds_limit && pieces <= (int64_t)64 * p.waves_n * p.waves_k * kStagePieces;
+    const StageGeom g = stage_geometry(a, p);
+    return g.fits && g.lds <= lds_limit;
 }
 
-size_t linear_lds_bytes(const LinearArgs& a, const LinearPlan& p) {
-    return stage_geometry(a, p, stage_budget(a, p)).lds;
-}
+size_t linear_lds_bytes(const LinearArgs& a, const LinearPlan& p) { return stage_geometry(a, p).lds; }
 
 template <typename K>
 static void allow_large_lds(K kernel) {
@@ -325,23 +341,32 @@ static void allow_large_lds(K kernel) {
     }
 }
 
-template <int BITS, int NB>
+template <int BITS, int NB, bool MULTI>
 static hipError_t launch_skinny_ngc(const SkinnyParams& sp, int ngc, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
     switch (ngc) {
         case 1:
-            allow_large_lds(skinny_mfma_kernel<BITS, 1, NB>);
-            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 1, NB>), grid, block, lds, st, sp);
+            allow_large_lds(skinny_mfma_kernel<BITS, 1, NB, MULTI>);
+            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 1, NB, MULTI>), grid, block, lds, st, sp);
             break;
         case 2:
-            allow_large_lds(skinny_mfma_kernel<BITS, 2, NB>);
-            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 2, NB>), grid, block, lds, st, sp);
+            allow_large_lds(skinny_mfma_kernel<BITS, 2, NB, MULTI>);
+            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 2, NB, MULTI>), grid, block, lds, st, sp);
             break;
         default:
-            allow_large_lds(skinny_mfma_kernel<BITS, 4, NB>);
-            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 4, NB>), grid, block, lds, st, sp);
+            allow_large_lds(skinny_mfma_kernel<BITS, 4, NB, MULTI>);
+            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 4, NB, MULTI>), grid, block, lds, st, sp);
             break;
     }
     return hipGetLastError();
+}
+
+template <int BITS>
+static hipError_t launch_skinny(const SkinnyParams& sp, int ngc, int nb, bool multi, dim3 grid, dim3 block, size_t lds,
+                                hipStream_t st) {
+    if (nb == 1) return multi ? launch_skinny_ngc<BITS, 1, true>(sp, ngc, grid, block, lds, st)
+                              : launch_skinny_ngc<BITS, 1, false>(sp, ngc, grid, block, lds, st);
+    return multi ? launch_skinny_ngc<BITS, 2, true>(sp, ngc, grid, block, lds, st)
+                 : launch_skinny_ngc<BITS, 2, false>(sp, ngc, grid, block, lds, st);
 }
 
 hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t st) {
@@ -363,11 +388,12 @@ hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t s
     sp.wn_shift = ilog2(p.waves_n);
     sp.wk_shift = ilog2(p.waves_k);
     sp.split_k = p.split_k;
-    const StageGeom sgm = stage_geometry(a, p, stage_budget(a, p));
+    const StageGeom sgm = stage_geometry(a, p);
     sp.per = sgm.per;
     sp.sc = sgm.sc;
     sp.sc_shift = ilog2(sgm.sc);
     sp.nstage = sgm.nstage;
+    sp.stage_rounds = sgm.rounds;
     sp.srp = p.waves_k * sgm.sc * (ck / 8);
     sp.srp_inv = (uint32_t)(((uint64_t)1 << 32) / (uint32_t)sp.srp) + 1u;
     sp.lds_stride = p.waves_k * sgm.sc * ck + kLdsPadHalves;
@@ -379,14 +405,8 @@ hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t s
     dim3 grid((unsigned)((sp.NT + p.waves_n - 1) / p.waves_n), (unsigned)p.split_k, (unsigned)p.m_blocks);
     dim3 block((unsigned)nthreads);
     const size_t lds = sgm.lds;
-    hipError_t e;
-    if (a.bits == 4) {
-        e = (p.prefetch == 1) ? launch_skinny_ngc<4, 1>(sp, ngc, grid, block, lds, st)
-                              : launch_skinny_ngc<4, 2>(sp, ngc, grid, block, lds, st);
-    } else {
-        e = (p.prefetch == 1) ? launch_skinny_ngc<8, 1>(sp, ngc, grid, block, lds, st)
-                              : launch_skinny_ngc<8, 2>(sp, ngc, grid, block, lds, st);
-    }
+    hipError_t e = (a.bits == 4) ? launch_skinny<4>(sp, ngc, p.prefetch, sgm.multi, grid, block, lds, st)
+                                 : launch_skinny<8>(sp, ngc, p.prefetch, sgm.multi, grid, block, lds, st);
     if (e != hipSuccess) return e;
     if (p.split_k > 1) {
         const int64_t MN = a.M * a.N;
