@@ -82,7 +82,7 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, size_t lds_limit
         const int64_t per_wave = steps <= 6144 ? 1 : (steps <= 24576 ? 2 : 4);
         p.waves_k = round_pow2((KC + per_wave - 1) / per_wave, 1, 16);
         while (p.waves_k > KC) p.waves_k /= 2;
-        p.waves_n = 8 / p.waves_k > 0 ? 8 / p.waves_k : 1;
+        p.waves_n = (steps > 24576 && p.waves_k < 8) ? 8 / p.waves_k : 1;    // eight wavefronts only for the largest
     } else if (steps <= 6144) {
         p.waves_k = round_pow2(KC, 1, 8);
         while (p.waves_k > KC) p.waves_k /= 2;

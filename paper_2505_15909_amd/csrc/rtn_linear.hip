@@ -57,6 +57,8 @@ struct SkinnyParams {
     int KC;           // chunks per row
     int WN, WK, wn_shift, wk_shift;   // wave = wk * WN + wn
     int split_k;
+    int kc_base, kc_rem;   // workgroup sg covers chunks [sg*kc_base + min(sg, kc_rem), ...): KC split evenly
+    uint32_t cpg_inv;      // floor(2^32 / (g / CK)) + 1 when g > CK (0 when g == CK): chunk -> group by multiply-high
     int per;          // chunks per wavefront (largest)
     int nstage;       // activation stages (1 unless MULTI)
     int stage_rounds; // staging rounds of kStagePieces pieces per thread for the single stage
@@ -119,8 +121,8 @@ __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p)
     const int m0 = blockIdx.z * 16;
     const int Mb = min(16, p.M - m0);
     const int sg = blockIdx.y;
-    const int cb0 = (int)((int64_t)p.KC * sg / p.split_k);           // chunk range of this workgroup
-    const int cb1 = (int)((int64_t)p.KC * (sg + 1) / p.split_k);
+    const int cb0 = sg * p.kc_base + min(sg, p.kc_rem);               // chunk range of this workgroup
+    const int cb1 = cb0 + p.kc_base + (sg < p.kc_rem ? 1 : 0);
     const int cw0 = min(cb0 + wk * p.per, cb1), cw1 = min(cw0 + p.per, cb1);   // ... and of this wavefront
     const int nt = blockIdx.x * p.WN + wn;
     const bool nt_ok = nt < p.NT;
@@ -152,7 +154,7 @@ __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p)
             const int c0 = min(cb0 + w * p.per, cb1), c1 = min(c0 + p.per, cb1);
             const int k8 = ((c0 + (s << p.sc_shift)) << CK8_SHIFT) + o;  // column / 8
             const bool ok = row < Mb && k8 < (c1 << CK8_SHIFT);
-            const uint32_t goff = ok ? (uint32_t)(((int64_t)(m0 + row) * p.K + (int64_t)k8 * 8) * 2) : kOutOfRange;
+            const uint32_t goff = ok ? ((uint32_t)(m0 + row) * (uint32_t)p.K + (uint32_t)k8 * 8u) * 2u : kOutOfRange;
             stg[i] = __builtin_amdgcn_raw_buffer_load_b128(ra, goff, 0, 0);
             stg_off[i] = row < rows_staged ? row * p.lds_stride + rem * 8 : -1;
         }
@@ -168,7 +170,7 @@ __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p)
     sraw_t sbuf[NB];
     auto fetch = [&](int j, int ci) {
         const bool ok = nt_ok && ci < cw1;                            // wave-uniform
-        const uint32_t si = (NGC > 1) ? (uint32_t)ci * NGC : ((uint32_t)ci * GM::CK) / (uint32_t)p.g;
+        const uint32_t si = (NGC > 1) ? (uint32_t)ci * NGC : (p.cpg_inv == 0 ? (uint32_t)ci : __umulhi((uint32_t)ci, p.cpg_inv));
         const uint32_t so = ok ? s_lane + si * 2u : kOutOfRange;
         const uint32_t wo = ok ? w_lane + (uint32_t)ci * (kChunkTiles * 1024u) : kOutOfRange;
         sbuf[j] = load_scales<NGC>(rs, so);                           // scales first: never the last to arrive
@@ -201,13 +203,22 @@ __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p)
             for (int j = 0; j < NB; ++j) {
                 if (ci < cw1) {                                       // scalar branch, no loads inside
                     constexpr int MPG = GM::NM / NGC;                 // MFMAs per group
+#ifdef RTN_AREG
+                    half8_t areg[GM::NM];
+#pragma unroll
+                    for (int i = 0; i < GM::NM; ++i) areg[i] = *reinterpret_cast<const half8_t*>(abase + i * 32);
+#endif
 #pragma unroll
                     for (int gi = 0; gi < NGC; ++gi) {
                         float4_t part = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                         for (int q = 0; q < MPG; ++q) {
                             const int i = gi * MPG + q;
+#ifdef RTN_AREG
+                            const half8_t a = areg[i];
+#else
                             const half8_t a = *reinterpret_cast<const half8_t*>(abase + i * 32);
+#endif
                             const half8_t b = unpack_operand<BITS>(wbuf[j][i / GM::MPT], i % GM::MPT, magic);
                             part = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, part, 0, 0, 0);
                         }
@@ -388,6 +399,12 @@ hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t s
     sp.wn_shift = ilog2(p.waves_n);
     sp.wk_shift = ilog2(p.waves_k);
     sp.split_k = p.split_k;
+    sp.kc_base = sp.KC / p.split_k;
+    sp.kc_rem = sp.KC % p.split_k;
+    {
+        const uint32_t cpg = (a.g >= ck) ? (uint32_t)(a.g / ck) : 1u;      // chunks per group
+        sp.cpg_inv = cpg == 1 ? 0u : (uint32_t)(((uint64_t)1 << 32) / cpg) + 1u;    // 0: one chunk per group
+    }
     const StageGeom sgm = stage_geometry(a, p);
     sp.per = sgm.per;
     sp.sc = sgm.sc;
