@@ -120,6 +120,7 @@ typedef struct {
     int waves_n;   /* wavefronts of a workgroup along N (share the staged activations): 1, 2, 4, 8, 16 */
     int waves_k;   /* wavefronts of a workgroup along K (in-workgroup split-K): 1 .. 16; waves_n * waves_k <= 16 */
     int split_k;   /* workgroups along K (global split-K, reduced through the workspace) */
+    int m_rows16;  /* 16-row activation blocks each wavefront multiplies per weight tile: 1, 2 or 4 */
 } rtn_linear_cfg;
 
 rtn_status rtn_linear_ex(const void* dev_A, int64_t M, const void* dev_qweight, const void* dev_scales,

@@ -73,9 +73,11 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, size_t lds_limit
     LinearPlan p;
     const int64_t NT = N / 16, KC = K / chunk_k(bits);
     const int64_t steps = NT * KC;                             // 4 KiB chunk-steps in the whole matrix
-    const int rows = (int)(M < 16 ? M + 1 : 16);
+    p.m_rows16 = M <= 16 ? 1 : (M <= 32 ? 2 : 4);              // weights are streamed once per 16/32/64 rows
+    const int mrows = 16 * p.m_rows16;
+    const int rows = (int)(M < mrows ? M + 1 : mrows);
     p.path = 1;
-    p.m_blocks = (int)((M + 15) / 16);
+    p.m_blocks = (int)((M + mrows - 1) / mrows);
     p.prefetch = 1;
     p.split_k = 1;
     if (rows <= 3) {
@@ -87,7 +89,7 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, size_t lds_limit
         p.waves_k = round_pow2(KC, 1, 8);
         while (p.waves_k > KC) p.waves_k /= 2;
         p.waves_n = NT >= 384 ? 2 : 1;
-    } else {
+    } else if (rows <= 16) {
         p.waves_n = 4;
         p.waves_k = (KC <= 16 && rows <= 9) ? 4 : 2;
         if (KC > 16) {
@@ -95,6 +97,15 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, size_t lds_limit
             while (split > 1 && (split > kMaxSplitK || (size_t)M * N * sizeof(float) * split > kWorkspaceCap)) --split;
             p.split_k = (int)split;
         }
+    } else {
+        // more than 16 rows: wide workgroups share the staged rows; K is split across workgroups
+        // only as far as needed to occupy the compute units
+        p.waves_n = 8;
+        p.waves_k = 1;
+        int64_t wgs = ((NT + 15) / 16) * p.m_blocks;
+        while (wgs * p.split_k < 256 && p.split_k * 2 <= kMaxSplitK && p.split_k * 2 <= KC &&
+               (size_t)M * N * sizeof(float) * (p.split_k * 2) <= kWorkspaceCap)
+            p.split_k *= 2;
     }
     while (p.waves_n > 1 && p.waves_n > NT) p.waves_n /= 2;
     LinearArgs a;
@@ -115,10 +126,16 @@ rtn_status resolve_plan(const LinearArgs& a, const rtn_linear_cfg* cfg, size_t w
         if (cfg->waves_n) p.waves_n = cfg->waves_n;
         if (cfg->waves_k) p.waves_k = cfg->waves_k;
         if (cfg->split_k) p.split_k = cfg->split_k;
+        if (cfg->m_rows16) {
+            p.m_rows16 = cfg->m_rows16;
+            p.m_blocks = (int)((a.M + 16 * p.m_rows16 - 1) / (16 * p.m_rows16));
+        }
     }
     const int64_t KC = a.K / chunk_k(a.bits);
     if (p.path != 1) return RTN_ERR_CONFIG;
     if (p.prefetch != 1 && p.prefetch != 2) return RTN_ERR_CONFIG;
+    if (p.m_rows16 != 1 && p.m_rows16 != 2 && p.m_rows16 != 4) return RTN_ERR_CONFIG;
+    if (p.m_rows16 > 1 && p.prefetch != 1) return RTN_ERR_CONFIG;
     if (!pow2(p.waves_n) || !pow2(p.waves_k) || p.waves_n * p.waves_k > 16) return RTN_ERR_CONFIG;
     if (p.split_k < 1 || p.split_k > kMaxSplitK || p.split_k > KC) return RTN_ERR_CONFIG;
     if (!rtn::linear_plan_fits(a, p, lds_limit)) return RTN_ERR_CONFIG;
@@ -225,7 +242,7 @@ rtn_status rtn_linear_query(int64_t M, int64_t N, int64_t K, int bits, int group
     if (M <= 0) return RTN_ERR_SHAPE;
     LinearPlan p = auto_plan(M, N, K, bits, (size_t)device_max_lds());
     out->path = p.path; out->prefetch = p.prefetch; out->waves_n = p.waves_n;
-    out->waves_k = p.waves_k; out->split_k = p.split_k;
+    out->waves_k = p.waves_k; out->split_k = p.split_k; out->m_rows16 = p.m_rows16;
     return RTN_OK;
 }
 

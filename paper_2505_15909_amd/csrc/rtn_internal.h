@@ -14,7 +14,8 @@ struct LinearPlan {
     int waves_n;    // wavefronts along N per workgroup
     int waves_k;    // wavefronts along K per workgroup
     int split_k;    // workgroups along K
-    int m_blocks;   // 16-row blocks of activations (grid.z)
+    int m_rows16;   // 16-row activation blocks per wavefront: 1, 2 or 4 (prefetch must be 1 above 1)
+    int m_blocks;   // activation blocks of 16 * m_rows16 rows (grid.z)
 };
 
 struct LinearArgs {

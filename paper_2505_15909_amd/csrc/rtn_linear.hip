@@ -105,7 +105,9 @@ __device__ __forceinline__ typename ScaleVec<NGC>::raw_t load_scales(__amdgpu_bu
 
 // MULTI = false: the workgroup's whole activation slice is staged once, before the main loop.
 // MULTI = true: it is staged sc chunks per wavefront at a time, one stage ahead, one round per stage.
-template <int BITS, int NGC, int NB, bool MULTI>
+// MB: 16-row activation blocks per wavefront (batch rows per workgroup = 16 MB); every unpacked weight
+// operand feeds MB MFMAs, so the weights are streamed once for up to 16 MB batch rows.
+template <int BITS, int NGC, int NB, bool MULTI, int MB>
 __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p) {
     typedef Geom<BITS> GM;
     typedef typename ScaleVec<NGC>::raw_t sraw_t;
@@ -118,8 +120,9 @@ __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p)
     const int nl = lane & 15, kq = lane >> 4;
     const int nthreads = blockDim.x;
 
-    const int m0 = blockIdx.z * 16;
-    const int Mb = min(16, p.M - m0);
+    constexpr int MROWS = 16 * MB;                                      // batch rows per workgroup
+    const int m0 = blockIdx.z * MROWS;
+    const int Mb = min(MROWS, p.M - m0);
     const int sg = blockIdx.y;
     const int cb0 = sg * p.kc_base + min(sg, p.kc_rem);               // chunk range of this workgroup
     const int cb1 = cb0 + p.kc_base + (sg < p.kc_rem ? 1 : 0);
@@ -140,7 +143,7 @@ __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p)
     // piece is 16 bytes: piece -> (row, w, octet).  Rows >= Mb (the shared zero row) and columns past
     // a wavefront's share are loaded out of range, i.e. as zeros, without memory traffic.
     half_t* lds_a = reinterpret_cast<half_t*>(lds_bytes);
-    const int rows_staged = Mb < 16 ? Mb + 1 : 16;
+    const int rows_staged = Mb < MROWS ? Mb + 1 : MROWS;               // + the shared zero row
     constexpr int CK8_SHIFT = (BITS == 4) ? 6 : 5;                     // log2(CK / 8)
     const int seg_shift = p.sc_shift + CK8_SHIFT;                     // log2(pieces per wavefront segment)
     u32x4_t stg[kStagePieces];
@@ -192,43 +195,46 @@ __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p)
     __syncthreads();
 
     // ---- main loop -------------------------------------------------------------------------------
-    float4_t acc = {0.f, 0.f, 0.f, 0.f};
-    const half_t* arow = lds_a + min(nl, Mb) * p.lds_stride + ((wk << p.sc_shift) * GM::CK) + kq * 8;
+    float4_t acc[MB];
+    const half_t* arow[MB];
+#pragma unroll
+    for (int b = 0; b < MB; ++b) {
+        acc[b] = (float4_t){0.f, 0.f, 0.f, 0.f};
+        arow[b] = lds_a + min(b * 16 + nl, Mb) * p.lds_stride + ((wk << p.sc_shift) * GM::CK) + kq * 8;
+    }
     int ci = cw0;
     for (int s = 0; s < p.nstage; ++s) {
         if constexpr (MULTI) stage_load(s + 1, 0);   // next stage's activations (out of range past the last)
-        const half_t* abase = arow;
+        int aoff = 0;
         for (int u = 0; u < p.sc; u += NB) {
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
                 if (ci < cw1) {                                       // scalar branch, no loads inside
                     constexpr int MPG = GM::NM / NGC;                 // MFMAs per group
-#ifdef RTN_AREG
-                    half8_t areg[GM::NM];
-#pragma unroll
-                    for (int i = 0; i < GM::NM; ++i) areg[i] = *reinterpret_cast<const half8_t*>(abase + i * 32);
-#endif
 #pragma unroll
                     for (int gi = 0; gi < NGC; ++gi) {
-                        float4_t part = {0.f, 0.f, 0.f, 0.f};
+                        float4_t part[MB];
+#pragma unroll
+                        for (int b = 0; b < MB; ++b) part[b] = (float4_t){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                         for (int q = 0; q < MPG; ++q) {
                             const int i = gi * MPG + q;
-#ifdef RTN_AREG
-                            const half8_t a = areg[i];
-#else
-                            const half8_t a = *reinterpret_cast<const half8_t*>(abase + i * 32);
-#endif
-                            const half8_t b = unpack_operand<BITS>(wbuf[j][i / GM::MPT], i % GM::MPT, magic);
-                            part = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, part, 0, 0, 0);
+                            const half8_t bw = unpack_operand<BITS>(wbuf[j][i / GM::MPT], i % GM::MPT, magic);
+#pragma unroll
+                            for (int b = 0; b < MB; ++b) {
+                                const half8_t a = *reinterpret_cast<const half8_t*>(arow[b] + aoff + i * 32);
+                                part[b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bw, part[b], 0, 0, 0);
+                            }
                         }
                         const float sc = scale_at<NGC>(sbuf[j], gi);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) acc[e] = fmaf(sc, part[e], acc[e]);
+                        for (int b = 0; b < MB; ++b)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) acc[b][e] = fmaf(sc, part[b][e], acc[b][e]);
                     }
                 }
                 fetch(j, ci + NB);        // unconditional: out of range past the wavefront's share
-                abase += GM::CK;
+                aoff += GM::CK;
                 ++ci;
             }
         }
@@ -245,26 +251,35 @@ __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p)
     if (p.WK > 1) {
         __syncthreads();                  // everyone is done reading the staged activations
         float4_t* red = reinterpret_cast<float4_t*>(lds_bytes);
-        if (wk > 0) red[((wk - 1) * p.WN + wn) * 64 + lane] = acc;
+        if (wk > 0) {
+#pragma unroll
+            for (int b = 0; b < MB; ++b) red[(((wk - 1) * p.WN + wn) * MB + b) * 64 + lane] = acc[b];
+        }
         __syncthreads();
         if (wk == 0) {
             for (int w = 1; w < p.WK; ++w) {
-                const float4_t v = red[((w - 1) * p.WN + wn) * 64 + lane];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) acc[e] += v[e];
+                for (int b = 0; b < MB; ++b) {
+                    const float4_t v = red[(((w - 1) * p.WN + wn) * MB + b) * 64 + lane];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[b][e] += v[e];
+                }
             }
         }
     }
     if (wk != 0 || !nt_ok) return;
 
-    // ---- store: lane holds rows m = 4 kq + e, column n = 16 tile + nl ----------------------------
+    // ---- store: lane holds rows m = 16 b + 4 kq + e, column n = 16 tile + nl -----------------------
     const int n = nt * 16 + nl;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const int m = kq * 4 + e;
-        if (m < Mb) {
-            if (p.split_k == 1) p.C[(int64_t)(m0 + m) * p.N + n] = (half_t)acc[e];
-            else p.ws[((int64_t)sg * p.M + (m0 + m)) * p.N + n] = acc[e];
+    for (int b = 0; b < MB; ++b) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int m = b * 16 + kq * 4 + e;
+            if (m < Mb) {
+                if (p.split_k == 1) p.C[(int64_t)(m0 + m) * p.N + n] = (half_t)acc[b][e];
+                else p.ws[((int64_t)sg * p.M + (m0 + m)) * p.N + n] = acc[b][e];
+            }
         }
     }
 }
@@ -293,6 +308,7 @@ static int ilog2(int v) {
 // one round of kStagePieces pieces per thread moves a stage and it stays within kMultiStageLds.
 constexpr size_t kSingleStageLds = 64 * 1024 + 1024;
 constexpr size_t kMultiStageLds = 32 * 1024 + 1024;
+constexpr size_t kMultiStageLdsWide = 72 * 1024;       // more than 16 activation rows: one chunk of 64 rows
 
 struct StageGeom {
     int per, sc, nstage, rows, rounds;
@@ -306,9 +322,10 @@ static StageGeom stage_geometry(const LinearArgs& a, const LinearPlan& p) {
     const int blk = (kc + p.split_k - 1) / p.split_k;                 // chunks per workgroup
     StageGeom g;
     g.per = (blk + p.waves_k - 1) / p.waves_k;
-    g.rows = (int)(a.M < 16 ? a.M + 1 : 16);
+    const int mrows = 16 * p.m_rows16;                               // batch rows per workgroup
+    g.rows = (int)(a.M < mrows ? a.M + 1 : mrows);
     const int nthreads = 64 * p.waves_n * p.waves_k;
-    const size_t red = p.waves_k > 1 ? (size_t)(p.waves_k - 1) * p.waves_n * 1024 : 0;
+    const size_t red = p.waves_k > 1 ? (size_t)(p.waves_k - 1) * p.waves_n * p.m_rows16 * 1024 : 0;
     auto bytes_of = [&](int sc) { return (size_t)g.rows * ((size_t)p.waves_k * sc * ck + kLdsPadHalves) * 2; };
     auto pieces_of = [&](int sc) { return (int64_t)g.rows * p.waves_k * sc * (ck / 8); };
     int sc_full = p.prefetch;
@@ -319,7 +336,8 @@ static StageGeom stage_geometry(const LinearArgs& a, const LinearPlan& p) {
     if (bytes_of(sc_full) > kSingleStageLds) {
         // largest stage that one round moves and that leaves room for several workgroups per CU
         int m = sc_full / 2;
-        while (m >= p.prefetch && (bytes_of(m) > kMultiStageLds || pieces_of(m) > (int64_t)nthreads * kStagePieces)) m /= 2;
+        const size_t budget = g.rows > 16 ? kMultiStageLdsWide : kMultiStageLds;
+        while (m >= p.prefetch && (bytes_of(m) > budget || pieces_of(m) > (int64_t)nthreads * kStagePieces)) m /= 2;
         if (m >= p.prefetch && m > 0) {
             g.multi = true;
             sc = m;
@@ -352,32 +370,36 @@ static void allow_large_lds(K kernel) {
     }
 }
 
-template <int BITS, int NB, bool MULTI>
+template <int BITS, int NB, bool MULTI, int MB>
 static hipError_t launch_skinny_ngc(const SkinnyParams& sp, int ngc, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
     switch (ngc) {
         case 1:
-            allow_large_lds(skinny_mfma_kernel<BITS, 1, NB, MULTI>);
-            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 1, NB, MULTI>), grid, block, lds, st, sp);
+            allow_large_lds(skinny_mfma_kernel<BITS, 1, NB, MULTI, MB>);
+            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 1, NB, MULTI, MB>), grid, block, lds, st, sp);
             break;
         case 2:
-            allow_large_lds(skinny_mfma_kernel<BITS, 2, NB, MULTI>);
-            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 2, NB, MULTI>), grid, block, lds, st, sp);
+            allow_large_lds(skinny_mfma_kernel<BITS, 2, NB, MULTI, MB>);
+            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 2, NB, MULTI, MB>), grid, block, lds, st, sp);
             break;
         default:
-            allow_large_lds(skinny_mfma_kernel<BITS, 4, NB, MULTI>);
-            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 4, NB, MULTI>), grid, block, lds, st, sp);
+            allow_large_lds(skinny_mfma_kernel<BITS, 4, NB, MULTI, MB>);
+            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 4, NB, MULTI, MB>), grid, block, lds, st, sp);
             break;
     }
     return hipGetLastError();
 }
 
 template <int BITS>
-static hipError_t launch_skinny(const SkinnyParams& sp, int ngc, int nb, bool multi, dim3 grid, dim3 block, size_t lds,
-                                hipStream_t st) {
-    if (nb == 1) return multi ? launch_skinny_ngc<BITS, 1, true>(sp, ngc, grid, block, lds, st)
-                              : launch_skinny_ngc<BITS, 1, false>(sp, ngc, grid, block, lds, st);
-    return multi ? launch_skinny_ngc<BITS, 2, true>(sp, ngc, grid, block, lds, st)
-                 : launch_skinny_ngc<BITS, 2, false>(sp, ngc, grid, block, lds, st);
+static hipError_t launch_skinny(const SkinnyParams& sp, int ngc, int nb, bool multi, int mb, dim3 grid, dim3 block,
+                                size_t lds, hipStream_t st) {
+    if (mb == 4) return multi ? launch_skinny_ngc<BITS, 1, true, 4>(sp, ngc, grid, block, lds, st)
+                              : launch_skinny_ngc<BITS, 1, false, 4>(sp, ngc, grid, block, lds, st);
+    if (mb == 2) return multi ? launch_skinny_ngc<BITS, 1, true, 2>(sp, ngc, grid, block, lds, st)
+                              : launch_skinny_ngc<BITS, 1, false, 2>(sp, ngc, grid, block, lds, st);
+    if (nb == 1) return multi ? launch_skinny_ngc<BITS, 1, true, 1>(sp, ngc, grid, block, lds, st)
+                              : launch_skinny_ngc<BITS, 1, false, 1>(sp, ngc, grid, block, lds, st);
+    return multi ? launch_skinny_ngc<BITS, 2, true, 1>(sp, ngc, grid, block, lds, st)
+                 : launch_skinny_ngc<BITS, 2, false, 1>(sp, ngc, grid, block, lds, st);
 }
 
 hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t st) {
@@ -422,8 +444,8 @@ hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t s
     dim3 grid((unsigned)((sp.NT + p.waves_n - 1) / p.waves_n), (unsigned)p.split_k, (unsigned)p.m_blocks);
     dim3 block((unsigned)nthreads);
     const size_t lds = sgm.lds;
-    hipError_t e = (a.bits == 4) ? launch_skinny<4>(sp, ngc, p.prefetch, sgm.multi, grid, block, lds, st)
-                                 : launch_skinny<8>(sp, ngc, p.prefetch, sgm.multi, grid, block, lds, st);
+    hipError_t e = (a.bits == 4) ? launch_skinny<4>(sp, ngc, p.prefetch, sgm.multi, p.m_rows16, grid, block, lds, st)
+                                 : launch_skinny<8>(sp, ngc, p.prefetch, sgm.multi, p.m_rows16, grid, block, lds, st);
     if (e != hipSuccess) return e;
     if (p.split_k > 1) {
         const int64_t MN = a.M * a.N;

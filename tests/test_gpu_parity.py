@@ -148,6 +148,17 @@ def test_linear_larger_batches(rtn, bits, g, M):
     C = rtn.rtn_linear(A_t, qw, sc, bits, g)
     torch.cuda.synchronize()
     H.assert_linear_close(_to_np(C), ref, f"bits={bits} g={g} M={M}")
+    # every activation-block width, wide and K-split workgroups
+    for cfg in (dict(m_rows16=1, waves_n=4, waves_k=2), dict(m_rows16=2, waves_n=8, waves_k=1),
+                dict(m_rows16=2, waves_n=4, waves_k=2, split_k=2), dict(m_rows16=4, waves_n=16, waves_k=1),
+                dict(m_rows16=4, waves_n=8, waves_k=2, split_k=4), dict(m_rows16=4, waves_n=4, waves_k=4)):
+        try:
+            C = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=cfg)
+        except rtn.RtnError as e:
+            assert e.status == 7
+            continue
+        torch.cuda.synchronize()
+        H.assert_linear_close(_to_np(C), ref, f"bits={bits} g={g} M={M} cfg={cfg}")
 
 
 @pytest.mark.parametrize("bits,g", [(4, 128), (8, 64), (8, 0)])
