@@ -34,8 +34,8 @@ BATCHES = (1, 2, 4, 8, 16)
 BITS, GROUP = 4, 128
 CACHE_BYTES = 256e6
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# very command, scaled by a copy kernel of known size; see profiles/ (None until measured).
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = None
+# very command, scaled by a copy kernel of known size (FETCH_SIZE x 1.998, WRITE_SIZE x 1.000).
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 29068733   # profiles/skinny_mfma_llama8b_w4a16_hbm_traffic.txt
 
 
 def main() -> int:
@@ -132,31 +132,38 @@ def main() -> int:
     flops = sum(2.0 * M * N * K for M in BATCHES for _, (K, N) in modules)
 
     # ---- roofline of the dominant kernel (the int4 skinny MFMA dequantise-GEMM: all 20 launches of a
-    # step): HIP events around every launch, on the launch stream, over the same steps -------------
+    # step).  A pair of HIP events on the launch stream brackets the launches of the same passes issued
+    # back to back (one rtn_linear per launch, direct launches, no graph); the stream is first held busy
+    # so that the host has enqueued everything before the GPU gets there, and the bracket times the GPU.
+    # (Events around every single launch cost several microseconds each on this runtime and were not
+    # usable.)  Average launch duration = bracket / launches; dispatch gaps are inside it.
     algo_bytes = 0.0
-    dur_ms = 0.0
-    n_launch = 0
+    calls = []
+    for s_i in range(min(args.steps, 20)):
+        for j, M in enumerate(BATCHES):
+            cp = copies[pass_no[0] % n_copies]
+            pass_no[0] += 1
+            for i, (_, (K, N)) in enumerate(modules):
+                calls.append((acts[M][i], cp[i][0], cp[i][1], outs[M][i]))
+                algo_bytes += cp[i][0].numel() + cp[i][1].numel() * 2 + 2 * M * K + 2 * M * N
+    n_launch = len(calls)
+    hold = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     with torch.cuda.stream(stream):
-        evs = []
-        for s_i in range(min(args.steps, 20)):
-            for j, M in enumerate(BATCHES):
-                cp = copies[pass_no[0] % n_copies]
-                pass_no[0] += 1
-                for i, (_, (K, N)) in enumerate(modules):
-                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    a.record(stream)
-                    rtn.rtn_linear(acts[M][i], cp[i][0], cp[i][1], BITS, GROUP, out=outs[M][i], workspace=ws)
-                    b.record(stream)
-                    evs.append((a, b))
-                    algo_bytes += cp[i][0].numel() + cp[i][1].numel() * 2 + 2 * M * K + 2 * M * N
-                    n_launch += 1
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(12):
+            hold.fill_(1)                                   # a few milliseconds of head start for the host
+        ev0.record(stream)
+        for A_, q_, s_, o_ in calls:
+            rtn.rtn_linear(A_, q_, s_, BITS, GROUP, out=o_, workspace=ws)
+        ev1.record(stream)
         torch.cuda.synchronize()
-        dur_ms = sum(a.elapsed_time(b) for a, b in evs)
-    achieved = algo_bytes / (dur_ms * 1e-3) / 1e9
+        launch_us = ev0.elapsed_time(ev1) * 1e3 / n_launch
+    del hold
+    achieved = algo_bytes / n_launch / (launch_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH,
-                "kernel": "skinny_mfma_kernel<4,...> (fused int4 dequantise-GEMM)",
-                "launches": n_launch, "avg_launch_us": round(dur_ms * 1e3 / n_launch, 3),
+                "kernel": "rtn::skinny_mfma_kernel<4,4,1,*,1> (fused int4 g128 dequantise-GEMM; a launch = one rtn_linear)",
+                "launches": n_launch, "avg_launch_us": round(launch_us, 3),
                 "algorithmic_bytes_per_launch": round(algo_bytes / n_launch, 1)}
 
     # ---- CPU oracle timed beside it (bounded sample of the same workload) ------------------------
@@ -174,14 +181,18 @@ def main() -> int:
             codes, scales = O.rtn_quantize(w, BITS, GROUP)
             sample.append((codes, scales, K, N))
         cpu_bytes = 0
+        cpu_steps = 0
+        host_acts = {M: [a.cpu().numpy() for a in acts[M]] for M in BATCHES}
         tc = time.perf_counter()
-        for M in BATCHES:
-            for i, (codes, scales, K, N) in enumerate(sample):
-                O.rtn_linear(acts[M][i].cpu().numpy(), codes, scales, GROUP)
-                cpu_bytes += codes.size * BITS // 8 + scales.size * 2
+        while time.perf_counter() - tc < 10.0:
+            for M in BATCHES:
+                for i, (codes, scales, K, N) in enumerate(sample):
+                    O.rtn_linear(host_acts[M][i], codes, scales, GROUP)
+                    cpu_bytes += codes.size * BITS // 8 + scales.size * 2
+            cpu_steps += 1
         tc = time.perf_counter() - tc
         cpu = {"value": round(cpu_bytes / tc / 1e9, 4), "unit": "GB/s", "cores": int(cores), "kind": "oracle",
-               "sample": "one full step (20 float64 linears of the same layer set, M=1,2,4,8,16), "
+               "sample": f"{cpu_steps} full steps (each 20 float64 linears of the same layer set, M=1,2,4,8,16), "
                          f"{tc:.1f} s wall; quantisation of the sample not timed"}
 
     line = {
