@@ -238,6 +238,43 @@ def test_full_size_quantize_and_linear(rtn, case):
             print(f"{name} {mod} M={M} ok", flush=True)
 
 
+def test_full_size_405b_selective_layer(rtn):
+    """The 405B-shaped selective-precision decoder layer at full width (qkv and gate_up int4 g128, o and
+    down int8 per-channel), quantised on the GPU and run through rtn_layer_forward at M = 1, 16, 128;
+    the oracle checks a stripe of 16-row tiles of every module (rows are independent)."""
+    plan = {"qkv": (4, 128), "o": (8, 0), "gate_up": (4, 128), "down": (8, 0)}
+    packed, stripes = {}, {}
+    for idx, (mod, (K, N)) in enumerate(synth.LLAMA_405B.items()):
+        bits, g = plan[mod]
+        W_t = synth.normal_weight(N, K, 0.01, seed=idx, device=DEV)
+        qw, sc = rtn.rtn_quantize(W_t, bits, g)
+        tiles = H.pick_row_tiles(N, 6, seed=idx)
+        rows = H.tile_rows(tiles, N)
+        Wr = _to_np(W_t[torch.from_numpy(rows).to(DEV)])
+        del W_t
+        gg = K if g <= 0 else g
+        codes, scales = O.rtn_quantize(Wr, bits, gg)
+        assert np.array_equal(_to_np(sc[torch.from_numpy(rows).to(DEV)]).view(np.uint16), scales.view(np.uint16)), mod
+        per_tile_row = 16 * K * bits // 8
+        got = np.concatenate([_to_np(qw[t * per_tile_row:(t + 1) * per_tile_row]) for t in tiles])
+        assert np.array_equal(got, O.pack_gfx950(codes, bits)), mod
+        packed[mod] = (qw, sc, bits, g, K, N)
+        stripes[mod] = (rows, codes, scales, gg)
+        print(f"405b {mod} quantise ok", flush=True)
+    for M in (1, 16, 128):
+        mods = []
+        for idx, (mod, (qw, sc, bits, g, K, N)) in enumerate(packed.items()):
+            mods.append(dict(A=synth.activation(M, K, seed=300 + idx, device=DEV), qweight=qw, scales=sc, bits=bits,
+                             group_size=g, C=torch.empty((M, N), dtype=torch.float16, device=DEV)))
+        rtn.rtn_layer_forward(mods)
+        torch.cuda.synchronize()
+        for m, mod in zip(mods, packed):
+            rows, codes, scales, gg = stripes[mod]
+            ref = O.rtn_linear(_to_np(m["A"]), codes, scales, gg)
+            H.assert_linear_close(_to_np(m["C"][:, torch.from_numpy(rows).to(DEV)]), ref, f"405b {mod} M={M}")
+        print(f"405b layer M={M} ok", flush=True)
+
+
 def test_selective_precision_layer(rtn):
     """Mixed 4-/8-bit decoder layer through rtn_layer_forward (Section 4.3), 405B-shaped at 1/8 width
     here; the full-width layer is exercised by the benchmark."""
