@@ -38,6 +38,76 @@ CACHE_BYTES = 256e6
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 29068733   # profiles/skinny_mfma_llama8b_w4a16_hbm_traffic.txt
 
 
+def _time_linear(rtn, torch, np, A, qws, sc, bits, g, cfg, ws, reps=3):
+    """Microseconds per rtn_linear launch: HIP-graph replay of launches that rotate over distinct weight copies."""
+    M, K = A.shape
+    N = sc.shape[0]
+    out = torch.empty((M, N), dtype=torch.float16, device=A.device)
+    for q in qws[:2]:
+        rtn.rtn_linear(A, q, sc, bits, g, out=out, workspace=ws, cfg=cfg)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        with torch.cuda.graph(graph, stream=st):
+            for _ in range(reps):
+                for q in qws:
+                    rtn.rtn_linear(A, q, sc, bits, g, out=out, workspace=ws, cfg=cfg)
+    n = reps * len(qws)
+    graph.replay()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1) * 1e3 / n)
+    return float(np.median(ts))
+
+
+def report(args, rtn, synth, torch, np, dev) -> int:
+    """Per (matrix, M): launch time, weight-stream GB/s, % of the 8 TB/s HBM peak, useful TFLOP/s; and per layer set."""
+    shapes = {"8b": synth.LLAMA_8B, "70b": synth.LLAMA_70B, "405b": synth.LLAMA_405B}[args.report]
+    std = {"8b": 0.02, "70b": 0.02, "405b": 0.01}[args.report]
+    bits = args.bits
+    g = 128 if bits == 4 else 0
+    Ms = [int(x) for x in args.batches.split(",")]
+    ws = torch.empty(16 << 20, dtype=torch.uint8, device=dev)
+    tot = {M: 0.0 for M in Ms}
+    totb = 0
+    print(f"# {args.report} shapes, int{bits} {'group 128' if bits == 4 else 'per-channel'}; launches rotate over >= 600 MB of "
+          f"distinct packed copies; HIP-graph replay; times include the ~1.5 us dispatch gap")
+    for idx, (name, (K, N)) in enumerate(shapes.items()):
+        W = synth.normal_weight(N, K, std, idx, dev)
+        qw, sc = rtn.rtn_quantize(W, bits, g)
+        del W
+        nbytes = qw.numel() + sc.numel() * 2
+        totb += nbytes
+        L = max(2, int(np.ceil(600e6 / nbytes)))
+        qws = [qw] + [qw.clone() for _ in range(L - 1)]
+        for M in Ms:
+            A = synth.activation(M, K, 100 + M, dev)
+            t = _time_linear(rtn, torch, np, A, qws, sc, bits, g, None, ws)
+            tot[M] += t
+            plan = rtn.rtn_linear_query(M, N, K, bits, g)
+            line = (f"{name:8s} {K:6d}->{N:6d} M={M:3d}  {t:8.2f} us  {nbytes / t / 1e3:7.0f} GB/s  "
+                    f"{nbytes / t / 80e3:5.1f} %  {2.0 * M * N * K / t / 1e6:7.2f} TFLOP/s  plan {plan['waves_n']}x{plan['waves_k']}"
+                    f" split {plan['split_k']} rows16 {plan['m_rows16']}")
+            if args.compare_paths and M <= 4:
+                c2 = dict(path=2, waves_n=plan["waves_n"], waves_k=plan["waves_k"], split_k=plan["split_k"])
+                try:
+                    line += f"  | v_dot2 variant {_time_linear(rtn, torch, np, A, qws, sc, bits, g, c2, ws):8.2f} us"
+                except rtn.RtnError:
+                    line += "  | v_dot2 variant n/a"
+            print(line, flush=True)
+        del qws, qw
+    for M in Ms:
+        print(f"layer set M={M:3d}: {tot[M]:8.2f} us  {totb / tot[M] / 1e3:7.0f} GB/s  {totb / tot[M] / 80e3:5.1f} % of 8 TB/s")
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -45,6 +115,12 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=12)
     ap.add_argument("--no-graph", action="store_true", help="launch every step directly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--report", choices=["8b", "70b", "405b"], default=None,
+                    help="instead of the JSON line, print a per-matrix, per-M table for that model's shapes")
+    ap.add_argument("--bits", type=int, default=4, help="--report only: 4 (group 128) or 8 (per-channel)")
+    ap.add_argument("--batches", type=str, default="1,2,4,8,16", help="--report only")
+    ap.add_argument("--compare-paths", action="store_true",
+                    help="--report only: also time the vector-ALU v_dot2 variant (M <= 4) in the same workgroup shape")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (--gpus 1); nothing here uses a second GPU.", file=sys.stderr)
@@ -58,6 +134,8 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.report:
+        return report(args, rtn, synth, torch, np, dev)
     modules = list(synth.LLAMA_8B.items())
 
     # ---- set-up: synthetic fp16 weights, load-time quantise (timed separately) ---------------

@@ -107,7 +107,11 @@ __device__ __forceinline__ typename ScaleVec<NGC>::raw_t load_scales(__amdgpu_bu
 // MULTI = true: it is staged sc chunks per wavefront at a time, one stage ahead, one round per stage.
 // MB: 16-row activation blocks per wavefront (batch rows per workgroup = 16 MB); every unpacked weight
 // operand feeds MB MFMAs, so the weights are streamed once for up to 16 MB batch rows.
-template <int BITS, int NGC, int NB, bool MULTI, int MB>
+// DOT = true (M <= 4, MB = 1): the same wavefront layout, but the products are done by the vector ALU
+// (v_dot2_f32_f16, 4 per weight word and batch row; lane l accumulates row l % 16 over its own k-slots
+// and the four k-slot lanes of a row are summed by two cross-lane adds at the end) instead of the matrix
+// cores -- the wavefront-reduction GEMV the skinny MFMA path is measured against.
+template <int BITS, int NGC, int NB, bool MULTI, int MB, bool DOT = false>
 __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p) {
     typedef Geom<BITS> GM;
     typedef typename ScaleVec<NGC>::raw_t sraw_t;
@@ -202,6 +206,8 @@ __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p)
         acc[b] = (float4_t){0.f, 0.f, 0.f, 0.f};
         arow[b] = lds_a + min(b * 16 + nl, Mb) * p.lds_stride + ((wk << p.sc_shift) * GM::CK) + kq * 8;
     }
+    const half_t* adot = lds_a + ((wk << p.sc_shift) * GM::CK) + kq * 8;   // DOT: row 0 of this k-slot
+    (void)adot;
     int ci = cw0;
     for (int s = 0; s < p.nstage; ++s) {
         if constexpr (MULTI) stage_load(s + 1, 0);   // next stage's activations (out of range past the last)
@@ -210,27 +216,53 @@ __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p)
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
                 if (ci < cw1) {                                       // scalar branch, no loads inside
-                    constexpr int MPG = GM::NM / NGC;                 // MFMAs per group
+                    constexpr int MPG = GM::NM / NGC;                 // MFMAs (weight words per lane) per group
+                    if constexpr (DOT) {
 #pragma unroll
-                    for (int gi = 0; gi < NGC; ++gi) {
-                        float4_t part[MB];
+                        for (int gi = 0; gi < NGC; ++gi) {
+                            float part[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                        for (int b = 0; b < MB; ++b) part[b] = (float4_t){0.f, 0.f, 0.f, 0.f};
+                            for (int q = 0; q < MPG; ++q) {
+                                const int i = gi * MPG + q;
+                                Half8Words bw;
+                                bw.v = unpack_operand<BITS>(wbuf[j][i / GM::MPT], i % GM::MPT, magic);
 #pragma unroll
-                        for (int q = 0; q < MPG; ++q) {
-                            const int i = gi * MPG + q;
-                            const half8_t bw = unpack_operand<BITS>(wbuf[j][i / GM::MPT], i % GM::MPT, magic);
+                                for (int m = 0; m < 4; ++m) {
+                                    if (m < Mb) {                     // uniform
+                                        Half8Words a;                 // same address for the 16 lanes of a k-slot
+                                        a.v = *reinterpret_cast<const half8_t*>(adot + m * p.lds_stride + aoff + i * 32);
 #pragma unroll
-                            for (int b = 0; b < MB; ++b) {
-                                const half8_t a = *reinterpret_cast<const half8_t*>(arow[b] + aoff + i * 32);
-                                part[b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bw, part[b], 0, 0, 0);
+                                        for (int h = 0; h < 4; ++h)
+                                            part[m] = __builtin_amdgcn_fdot2(a.h2[h], bw.h2[h], part[m], false);
+                                    }
+                                }
                             }
+                            const float sc = scale_at<NGC>(sbuf[j], gi);
+#pragma unroll
+                            for (int m = 0; m < 4; ++m) acc[0][m] = fmaf(sc, part[m], acc[0][m]);
                         }
-                        const float sc = scale_at<NGC>(sbuf[j], gi);
+                    } else {
 #pragma unroll
-                        for (int b = 0; b < MB; ++b)
+                        for (int gi = 0; gi < NGC; ++gi) {
+                            float4_t part[MB];
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) acc[b][e] = fmaf(sc, part[b][e], acc[b][e]);
+                            for (int b = 0; b < MB; ++b) part[b] = (float4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                            for (int q = 0; q < MPG; ++q) {
+                                const int i = gi * MPG + q;
+                                const half8_t bw = unpack_operand<BITS>(wbuf[j][i / GM::MPT], i % GM::MPT, magic);
+#pragma unroll
+                                for (int b = 0; b < MB; ++b) {
+                                    const half8_t a = *reinterpret_cast<const half8_t*>(arow[b] + aoff + i * 32);
+                                    part[b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bw, part[b], 0, 0, 0);
+                                }
+                            }
+                            const float sc = scale_at<NGC>(sbuf[j], gi);
+#pragma unroll
+                            for (int b = 0; b < MB; ++b)
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) acc[b][e] = fmaf(sc, part[b][e], acc[b][e]);
+                        }
                     }
                 }
                 fetch(j, ci + NB);        // unconditional: out of range past the wavefront's share
@@ -244,6 +276,16 @@ __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p)
                 stage_store();
                 __syncthreads();
             }
+        }
+    }
+
+    if constexpr (DOT) {                  // sum the four k-slot lanes of every weight row (fixed order)
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            float v = acc[0][m];
+            v += __shfl_xor(v, 16);
+            v += __shfl_xor(v, 32);
+            acc[0][m] = v;
         }
     }
 
@@ -269,14 +311,15 @@ __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p)
     }
     if (wk != 0 || !nt_ok) return;
 
-    // ---- store: lane holds rows m = 16 b + 4 kq + e, column n = 16 tile + nl -----------------------
+    // ---- store: lane holds rows m = 16 b + 4 kq + e (DOT: rows m = e, in the lanes of k-slot 0), column
+    // n = 16 tile + nl --------------------------------------------------------------------------------
     const int n = nt * 16 + nl;
 #pragma unroll
     for (int b = 0; b < MB; ++b) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const int m = b * 16 + kq * 4 + e;
-            if (m < Mb) {
+            const int m = DOT ? e : b * 16 + kq * 4 + e;
+            if (m < Mb && (!DOT || kq == 0)) {
                 if (p.split_k == 1) p.C[(int64_t)(m0 + m) * p.N + n] = (half_t)acc[b][e];
                 else p.ws[((int64_t)sg * p.M + (m0 + m)) * p.N + n] = acc[b][e];
             }
@@ -355,6 +398,7 @@ static StageGeom stage_geometry(const LinearArgs& a, const LinearPlan& p) {
 
 bool linear_plan_fits(const LinearArgs& a, const LinearPlan& p, size_t lds_limit) {
     const StageGeom g = stage_geometry(a, p);
+    if (p.path == 2 && g.multi) return false;            // the dot-product variant stages once
     return g.fits && g.lds <= lds_limit;
 }
 
@@ -384,6 +428,25 @@ static hipError_t launch_skinny_ngc(const SkinnyParams& sp, int ngc, dim3 grid, 
         default:
             allow_large_lds(skinny_mfma_kernel<BITS, 4, NB, MULTI, MB>);
             hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 4, NB, MULTI, MB>), grid, block, lds, st, sp);
+            break;
+    }
+    return hipGetLastError();
+}
+
+template <int BITS>
+static hipError_t launch_dot(const SkinnyParams& sp, int ngc, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
+    switch (ngc) {
+        case 1:
+            allow_large_lds(skinny_mfma_kernel<BITS, 1, 1, false, 1, true>);
+            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 1, 1, false, 1, true>), grid, block, lds, st, sp);
+            break;
+        case 2:
+            allow_large_lds(skinny_mfma_kernel<BITS, 2, 1, false, 1, true>);
+            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 2, 1, false, 1, true>), grid, block, lds, st, sp);
+            break;
+        default:
+            allow_large_lds(skinny_mfma_kernel<BITS, 4, 1, false, 1, true>);
+            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 4, 1, false, 1, true>), grid, block, lds, st, sp);
             break;
     }
     return hipGetLastError();
@@ -444,8 +507,13 @@ hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t s
     dim3 grid((unsigned)((sp.NT + p.waves_n - 1) / p.waves_n), (unsigned)p.split_k, (unsigned)p.m_blocks);
     dim3 block((unsigned)nthreads);
     const size_t lds = sgm.lds;
-    hipError_t e = (a.bits == 4) ? launch_skinny<4>(sp, ngc, p.prefetch, sgm.multi, p.m_rows16, grid, block, lds, st)
-                                 : launch_skinny<8>(sp, ngc, p.prefetch, sgm.multi, p.m_rows16, grid, block, lds, st);
+    hipError_t e;
+    if (p.path == 2) {
+        e = (a.bits == 4) ? launch_dot<4>(sp, ngc, grid, block, lds, st) : launch_dot<8>(sp, ngc, grid, block, lds, st);
+    } else {
+        e = (a.bits == 4) ? launch_skinny<4>(sp, ngc, p.prefetch, sgm.multi, p.m_rows16, grid, block, lds, st)
+                          : launch_skinny<8>(sp, ngc, p.prefetch, sgm.multi, p.m_rows16, grid, block, lds, st);
+    }
     if (e != hipSuccess) return e;
     if (p.split_k > 1) {
         const int64_t MN = a.M * a.N;

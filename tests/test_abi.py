@@ -66,8 +66,10 @@ def test_argument_validation_happens_before_any_launch():
     assert _linear(cfg=C.byref(cfg)) == 7                         # wavefront counts are powers of two
     cfg = rtn.rtn_linear_cfg(waves_n=8, waves_k=4)
     assert _linear(cfg=C.byref(cfg)) == 7                         # at most 16 wavefronts per workgroup
-    cfg = rtn.rtn_linear_cfg(path=2)
+    cfg = rtn.rtn_linear_cfg(path=3)
     assert _linear(cfg=C.byref(cfg)) == 7
+    cfg = rtn.rtn_linear_cfg(path=2)
+    assert _linear(M=5, cfg=C.byref(cfg)) == 7                    # the vector-ALU path is for M <= 4
     cfg = rtn.rtn_linear_cfg(split_k=2)
     assert _linear(K=1024, wsn=16, cfg=C.byref(cfg)) == 6         # workspace too small
     cfg = rtn.rtn_linear_cfg(split_k=4)

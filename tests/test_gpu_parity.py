@@ -138,6 +138,22 @@ def test_linear_all_configs_small(rtn, bits, g):
         H.assert_linear_close(_to_np(C), ref, f"bits={bits} g={g} M={M} auto")
 
 
+@pytest.mark.parametrize("bits,g", [(4, 128), (4, 0), (8, 128), (8, 0)])
+def test_linear_vector_alu_path(rtn, bits, g):
+    """The v_dot2 wavefront-reduction variant (path 2, M <= 4) against the oracle and the MFMA path."""
+    N, K = 272, 3072
+    codes, scales, qw, sc, gg = _oracle_operands(N, K, bits, g, seed=21)
+    for M in (1, 2, 3, 4):
+        A_t = synth.activation(M, K, seed=100 + M, device=DEV)
+        ref = O.rtn_linear(_to_np(A_t), codes, scales, gg)
+        for wn, wk, sk in ((1, 1, 1), (1, 4, 1), (2, 2, 2), (4, 2, 1), (1, 8, 1), (1, 16, 1), (2, 4, 3)):
+            C = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=dict(path=2, waves_n=wn, waves_k=wk, split_k=sk))
+            torch.cuda.synchronize()
+            H.assert_linear_close(_to_np(C), ref, f"dot2 bits={bits} g={g} M={M} cfg={(wn, wk, sk)}")
+    with pytest.raises(rtn.RtnError):
+        rtn.rtn_linear(synth.activation(5, K, seed=1, device=DEV), qw, sc, bits, g, cfg=dict(path=2))
+
+
 @pytest.mark.parametrize("bits,g", [(4, 128), (8, 0)])
 @pytest.mark.parametrize("M", [17, 32, 33, 64, 100, 128])
 def test_linear_larger_batches(rtn, bits, g, M):
