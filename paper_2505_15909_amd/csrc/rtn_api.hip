@@ -80,7 +80,7 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, size_t lds_limit
     p.m_blocks = (int)((M + mrows - 1) / mrows);
     p.prefetch = 1;
     p.split_k = 1;
-    if (rows <= 3) {
+    if (rows <= 2 || (rows == 3 && KC > 16)) {
         const int64_t per_wave = steps <= 6144 ? 1 : (steps <= 24576 ? 2 : 4);
         p.waves_k = round_pow2((KC + per_wave - 1) / per_wave, 1, 16);
         while (p.waves_k > KC) p.waves_k /= 2;
@@ -90,12 +90,18 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, size_t lds_limit
         while (p.waves_k > KC) p.waves_k /= 2;
         p.waves_n = NT >= 384 ? 2 : 1;
     } else if (rows <= 16) {
-        p.waves_n = 4;
-        p.waves_k = (KC <= 16 && rows <= 9) ? 4 : 2;
-        if (KC > 16) {
-            int64_t split = (KC + 7) / 8;                      // about 8 chunks per workgroup
-            while (split > 1 && (split > kMaxSplitK || (size_t)M * N * sizeof(float) * split > kWorkspaceCap)) --split;
+        if (KC > 16) {                                         // long K: about 7-14 chunks per workgroup
+            p.waves_n = 4;
+            p.waves_k = 2;
+            int64_t split = 4;
+            while (split > 1 && (size_t)M * N * sizeof(float) * split > kWorkspaceCap) --split;
             p.split_k = (int)split;
+        } else if (steps > 24576) {                            // the largest matrices: long-lived wavefronts
+            p.waves_n = rows <= 5 ? 2 : 8;
+            p.waves_k = rows <= 5 ? 2 : 1;
+        } else {
+            p.waves_n = 4;
+            p.waves_k = rows <= 9 ? 4 : 2;
         }
     } else {
         // more than 16 rows: wide workgroups share the staged rows; K is split across workgroups
