@@ -116,7 +116,7 @@ rtn_status rtn_linear(const void* dev_A, int64_t M, const void* dev_qweight, con
  * A zeroed struct means "choose automatically", field by field. */
 typedef struct {
     int path;      /* 0 auto, 1 MFMA skinny kernel, 2 vector-ALU dot-product kernel (M <= 4) */
-    int prefetch;  /* k-chunks (4 KiB each) a wavefront keeps in flight: 1 or 2 */
+    int prefetch;  /* k-chunks (4 KiB each) a wavefront keeps in flight: 1, 2 or 4 */
     int waves_n;   /* wavefronts of a workgroup along N (share the staged activations): 1, 2, 4, 8, 16 */
     int waves_k;   /* wavefronts of a workgroup along K (in-workgroup split-K): 1 .. 16; waves_n * waves_k <= 16 */
     int split_k;   /* workgroups along K (global split-K, reduced through the workspace) */

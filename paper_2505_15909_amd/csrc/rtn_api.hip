@@ -140,7 +140,7 @@ rtn_status resolve_plan(const LinearArgs& a, const rtn_linear_cfg* cfg, size_t w
     const int64_t KC = a.K / chunk_k(a.bits);
     if (p.path != 1 && p.path != 2) return RTN_ERR_CONFIG;
     if (p.path == 2 && (a.M > 4 || p.prefetch != 1 || p.m_rows16 != 1)) return RTN_ERR_CONFIG;
-    if (p.prefetch != 1 && p.prefetch != 2) return RTN_ERR_CONFIG;
+    if (p.prefetch != 1 && p.prefetch != 2 && p.prefetch != 4) return RTN_ERR_CONFIG;
     if (p.m_rows16 != 1 && p.m_rows16 != 2 && p.m_rows16 != 4) return RTN_ERR_CONFIG;
     if (p.m_rows16 > 1 && p.prefetch != 1) return RTN_ERR_CONFIG;
     if (!pow2(p.waves_n) || !pow2(p.waves_k) || p.waves_n * p.waves_k > 16) return RTN_ERR_CONFIG;

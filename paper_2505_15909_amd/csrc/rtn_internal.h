@@ -10,7 +10,7 @@ constexpr size_t kMaxLdsBytes = 160 * 1024;   // LDS of one gfx950 compute unit,
 // Resolved launch configuration of the fused dequantise-GEMM.
 struct LinearPlan {
     int path;       // 1 = MFMA skinny kernel, 2 = vector-ALU dot kernel
-    int prefetch;   // k-chunks in flight per wavefront (register buffers): 1 or 2
+    int prefetch;   // k-chunks in flight per wavefront (register buffers): 1, 2 or 4
     int waves_n;    // wavefronts along N per workgroup
     int waves_k;    // wavefronts along K per workgroup
     int split_k;    // workgroups along K

@@ -461,8 +461,10 @@ static hipError_t launch_skinny(const SkinnyParams& sp, int ngc, int nb, bool mu
                               : launch_skinny_ngc<BITS, 1, false, 2>(sp, ngc, grid, block, lds, st);
     if (nb == 1) return multi ? launch_skinny_ngc<BITS, 1, true, 1>(sp, ngc, grid, block, lds, st)
                               : launch_skinny_ngc<BITS, 1, false, 1>(sp, ngc, grid, block, lds, st);
-    return multi ? launch_skinny_ngc<BITS, 2, true, 1>(sp, ngc, grid, block, lds, st)
-                 : launch_skinny_ngc<BITS, 2, false, 1>(sp, ngc, grid, block, lds, st);
+    if (nb == 2) return multi ? launch_skinny_ngc<BITS, 2, true, 1>(sp, ngc, grid, block, lds, st)
+                              : launch_skinny_ngc<BITS, 2, false, 1>(sp, ngc, grid, block, lds, st);
+    return multi ? launch_skinny_ngc<BITS, 4, true, 1>(sp, ngc, grid, block, lds, st)
+                 : launch_skinny_ngc<BITS, 4, false, 1>(sp, ngc, grid, block, lds, st);
 }
 
 hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t st) {
