@@ -9,55 +9,83 @@
 //   amax   exact (max of |fp16| values, held in fp32)
 //   S      fp16_rne( fp32_ieee_div(amax, D) )   -- equal to the single rounding of the exact
 //          quotient for every fp16 amax and D in {7, 127, 7.5, 127.5}
-//   q      clamp( rint( fp32_ieee_div(w, S) ) ) -- w and S have 11-bit significands, so the
-//          exact quotient is either an exact tie (representable, returned exactly by an IEEE
-//          division) or at least 2^-13 away from one; fp32 rounding cannot move it across.
-//          A reciprocal-multiply would not have this property and is not used.
+//   q      clamp( rint( w / S ) ) without a per-element division: with r = fp32_ieee_div(1, S), shared by
+//          the group, and the even constant C = 768 + B (B = 8 or 128, the offset of the stored code),
+//              y = fma(w, r, C)      one fp32 rounding of the exact w r + C, which lies in [512, 2048),
+//                                    where fp32 values are the multiples of 2^-14 (2^-13 from 1024 up,
+//                                    reached only under subnormal S, where |Q| can approach 1.5 D)
+//              z = rint(y)           ties to even
+//              stored code = clamp(z, C + QMIN, C + QMAX) - 768
+//          Why z - C is the round-half-even of the exact quotient Q = w / S.  w and S carry 11-bit
+//          significands, so Q is either exactly a half-integer h or at least 1/4094 > 2^-13 away from every
+//          half-integer (2w - (2i+1)S is a non-zero multiple of the smaller of their quanta).  The exact
+//          product P = w r satisfies |P - Q| <= |Q| 2^-24 < 2^-16 (|Q| < 192 inside a group).
+//          (a) Q = h is a tie: h + C is a grid point and |P + C - (h + C)| < 2^-16 is less than half a
+//              grid step (>= 2^-15), so the fma returns h + C exactly and rint applies ties-to-even to
+//              the true tie; C is even, so the parity of the result is that of the code.
+//          (b) Q is not a tie: for every half-integer h, |P - h| > 2^-13 - 2^-16 > 2^-14, at least half
+//              a grid step, so the fma cannot round onto h + C and, rounding being monotone, y stays
+//              strictly on Q's side of it: rint(y) = rint(Q) + C.
+//          The first rounding (to the 2^-14 grid) and the second (to integers) are both needed: adding a
+//          constant with unit ulp directly would misround true ties by the error of P.
+//          S == 0 (all-zero or underflowed group): r is forced to 0, y = C, the code is 0.
+//          The clamp matters for the Eq. 2 divisor and for subnormal S, whose rounding is coarse.
+//   pack   the integers z are < 1024, so sums  z_a + 16 z_b + 256 z_c + 4096 z_d  (4-bit) and
+//          z_a + 256 z_b (8-bit) are exact in fp32; they are formed by fma, converted once, joined
+//          with a shift-add, and the constant contributed by the 768s is subtracted from the word.
 #include "rtn_device.h"
 #include "rtn_internal.h"
 
 namespace rtn {
 
 template <int BITS>
-__device__ __forceinline__ int quantize_one(float w, float s) {
-    float r = rintf(w / s);                              // v_rndne_f32: ties to even
-    r = fminf(fmaxf(r, (float)Layout<BITS>::QMIN), (float)Layout<BITS>::QMAX);
-    int q = (int)r;
-    return (s == 0.0f) ? 0 : q;                           // all-zero / underflowed scale
+__device__ __forceinline__ float snapped_code(half_t w, float r) {
+    constexpr float C = 768.0f + (BITS == 4 ? 8.0f : 128.0f);
+    const float y = fmaf((float)w, r, C);                // v_fma_mix_f32: the fp16 operand converts exactly
+    return __builtin_amdgcn_fmed3f(rintf(y), C + (float)Layout<BITS>::QMIN, C + (float)Layout<BITS>::QMAX);
 }
+
+__device__ __forceinline__ float group_reciprocal(float s) { return s == 0.0f ? 0.0f : 1.0f / s; }   // IEEE divide
 
 // 8 consecutive-k halves (one 16-byte load) -> 8 codes, offset binary, in layout order.
 // 4-bit: one word.  8-bit: two words.
 template <int BITS>
-__device__ __forceinline__ void quantize_octet(const u32x4_t& raw, float s, uint32_t* out) {
+__device__ __forceinline__ void quantize_octet(const u32x4_t& raw, float r, uint32_t* out) {
     Half8Words h;
     h.v = __builtin_bit_cast(half8_t, raw);
+    float z[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) z[e] = snapped_code<BITS>(h.v[e], r);
     if constexpr (BITS == 4) {
-        constexpr int NIB[8] = {0, 4, 1, 5, 2, 6, 3, 7};
-        uint32_t word = 0;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            int q = quantize_one<4>((float)h.v[e], s);
-            word |= (uint32_t)(q + 8) << (4 * NIB[e]);
-        }
-        out[0] = word;
+        // element e sits in nibble {0,4,1,5,2,6,3,7}[e]: even elements fill the low half-word
+        const float lo = fmaf(z[6], 4096.0f, fmaf(z[4], 256.0f, fmaf(z[2], 16.0f, z[0])));
+        const float hi = fmaf(z[7], 4096.0f, fmaf(z[5], 256.0f, fmaf(z[3], 16.0f, z[1])));
+        out[0] = (((uint32_t)hi << 16) + (uint32_t)lo) - 0x33333300u;      // 768 * 0x1111 in both halves
     } else {
-        uint32_t w0 = 0, w1 = 0;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            w0 |= (uint32_t)(quantize_one<8>((float)h.v[e], s) + 128) << (8 * e);
-            w1 |= (uint32_t)(quantize_one<8>((float)h.v[e + 4], s) + 128) << (8 * e);
-        }
-        out[0] = w0;
-        out[1] = w1;
+        const float a = fmaf(z[1], 256.0f, z[0]), b = fmaf(z[3], 256.0f, z[2]);
+        const float c = fmaf(z[5], 256.0f, z[4]), d = fmaf(z[7], 256.0f, z[6]);
+        out[0] = (((uint32_t)b << 16) + (uint32_t)a) - 0x03030300u;        // 768 * 0x101 in both halves
+        out[1] = (((uint32_t)d << 16) + (uint32_t)c) - 0x03030300u;
     }
 }
 
-__device__ __forceinline__ float octet_amax(const u32x4_t& raw, float m) {
-    half8_t v = __builtin_bit_cast(half8_t, raw);
+// Running maximum of |x| over packed fp16 pairs: max3(m, x, -x) per 32-bit word.  For the finite inputs
+// the library accepts this is the plain maximum; it stays in fp16, where it is exact.
+__device__ __forceinline__ uint32_t pk_amax(uint32_t m, uint32_t x) {
+    uint32_t o;
+    asm("v_pk_maximum3_f16 %0, %1, %2, %2 neg_lo:[0,0,1] neg_hi:[0,0,1]" : "=v"(o) : "v"(m), "v"(x));
+    return o;
+}
+
+__device__ __forceinline__ uint32_t octet_amax(const u32x4_t& raw, uint32_t m) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) m = fmaxf(m, fabsf((float)v[e]));
+    for (int i = 0; i < 4; ++i) m = pk_amax(m, raw[i]);
     return m;
+}
+
+__device__ __forceinline__ float amax_of_pair(uint32_t m) {
+    const half2_t v = __builtin_bit_cast(half2_t, m);
+    return fmaxf((float)v[0], (float)v[1]);
 }
 
 __device__ __forceinline__ float scale_from_amax(float amax, float divisor) {
@@ -90,14 +118,16 @@ __global__ __launch_bounds__(256) void quantize_small_group_kernel(
 #pragma unroll
             for (int t = 0; t < OPT; ++t)
                 raw[tp][t] = *reinterpret_cast<const u32x4_t*>(src + tp * TK + t * 32);
-        float m = 0.0f;
+        uint32_t m2 = 0u;
 #pragma unroll
         for (int tp = 0; tp < TPG; ++tp)
 #pragma unroll
-            for (int t = 0; t < OPT; ++t) m = octet_amax(raw[tp][t], m);
+            for (int t = 0; t < OPT; ++t) m2 = octet_amax(raw[tp][t], m2);
+        float m = amax_of_pair(m2);
         m = fmaxf(m, __shfl_xor(m, 16));
         m = fmaxf(m, __shfl_xor(m, 32));
         const float s = scale_from_amax(m, divisor);
+        const float r = group_reciprocal(s);
         if (kq == 0) scales[(nt * 16 + nl) * G + j] = (half_t)s;
         uint8_t* dst = qweight + ((nt * KT + j * TPG) * 64 + lane) * 16;
 #pragma unroll
@@ -105,7 +135,7 @@ __global__ __launch_bounds__(256) void quantize_small_group_kernel(
             u32x4_t chunk;
             uint32_t words[4];
 #pragma unroll
-            for (int t = 0; t < OPT; ++t) quantize_octet<BITS>(raw[tp][t], s, &words[t * (4 / OPT)]);
+            for (int t = 0; t < OPT; ++t) quantize_octet<BITS>(raw[tp][t], r, &words[t * (4 / OPT)]);
             chunk[0] = words[0]; chunk[1] = words[1]; chunk[2] = words[2]; chunk[3] = words[3];
             *reinterpret_cast<u32x4_t*>(dst + (int64_t)tp * 1024) = chunk;
         }
@@ -132,12 +162,13 @@ __global__ __launch_bounds__(1024) void quantize_large_group_kernel(
     const int64_t nt = u / G, j = u % G;
     const half_t* src = W + (nt * 16 + nl) * K + j * g + kq * 8;
 
-    float m = 0.0f;
+    uint32_t m2 = 0u;
     for (int64_t tp = wave; tp < TPG; tp += nwave) {
 #pragma unroll
         for (int t = 0; t < OPT; ++t)
-            m = octet_amax(*reinterpret_cast<const u32x4_t*>(src + tp * TK + t * 32), m);
+            m2 = octet_amax(*reinterpret_cast<const u32x4_t*>(src + tp * TK + t * 32), m2);
     }
+    float m = amax_of_pair(m2);
     m = fmaxf(m, __shfl_xor(m, 16));
     m = fmaxf(m, __shfl_xor(m, 32));
     if (kq == 0) row_max[wave][nl] = m;
@@ -145,6 +176,7 @@ __global__ __launch_bounds__(1024) void quantize_large_group_kernel(
     m = 0.0f;
     for (int w = 0; w < nwave; ++w) m = fmaxf(m, row_max[w][nl]);
     const float s = scale_from_amax(m, divisor);
+    const float r = group_reciprocal(s);
     if (wave == 0 && kq == 0) scales[(nt * 16 + nl) * G + j] = (half_t)s;
 
     uint8_t* dst = qweight + ((nt * KT + j * TPG) * 64 + lane) * 16;
@@ -154,10 +186,72 @@ __global__ __launch_bounds__(1024) void quantize_large_group_kernel(
 #pragma unroll
         for (int t = 0; t < OPT; ++t) {
             u32x4_t raw = *reinterpret_cast<const u32x4_t*>(src + tp * TK + t * 32);
-            quantize_octet<BITS>(raw, s, &words[t * (4 / OPT)]);
+            quantize_octet<BITS>(raw, r, &words[t * (4 / OPT)]);
         }
         chunk[0] = words[0]; chunk[1] = words[1]; chunk[2] = words[2]; chunk[3] = words[3];
         *reinterpret_cast<u32x4_t*>(dst + tp * 1024) = chunk;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Medium groups (the per-channel case for K up to 14336): as above a workgroup of 16 wavefronts owns a
+// (row-tile, group) unit, but the whole 16 x g block stays in registers between the amax pass and the
+// packing pass (LPL 16-byte loads per lane, 16 KiB x LPL per workgroup), so W is read exactly once.
+// Wavefront w owns tiles w, w + 16, ...; tiles past the end of the group are neither loaded nor stored.
+// ---------------------------------------------------------------------------------------
+template <int BITS, int LPL>
+__global__ __launch_bounds__(1024) void quantize_resident_group_kernel(
+    const half_t* __restrict__ W, uint8_t* __restrict__ qweight, half_t* __restrict__ scales,
+    int64_t N, int64_t K, int64_t g, float divisor) {
+    constexpr int TK = Layout<BITS>::TK;
+    constexpr int OPT = TK / 32;
+    constexpr int TPW = LPL / OPT;                        // tiles per wavefront
+    __shared__ float row_max[16][16];                    // [wave][row]
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nl = lane & 15, kq = lane >> 4;
+    const int64_t G = K / g, KT = K / TK;
+    const int TPG = (int)(g / TK);
+    const int64_t u = blockIdx.x;
+    const int64_t nt = u / G, j = u % G;
+    const half_t* src = W + (nt * 16 + nl) * K + j * g + kq * 8;
+
+    u32x4_t raw[TPW][OPT];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int tp = wave + 16 * i;
+#pragma unroll
+        for (int t = 0; t < OPT; ++t) {
+            raw[i][t] = u32x4_t{0u, 0u, 0u, 0u};
+            if (tp < TPG) raw[i][t] = *reinterpret_cast<const u32x4_t*>(src + (int64_t)tp * TK + t * 32);
+        }
+    }
+    uint32_t m2 = 0u;
+#pragma unroll
+    for (int i = 0; i < TPW; ++i)
+#pragma unroll
+        for (int t = 0; t < OPT; ++t) m2 = octet_amax(raw[i][t], m2);
+    float m = amax_of_pair(m2);
+    m = fmaxf(m, __shfl_xor(m, 16));
+    m = fmaxf(m, __shfl_xor(m, 32));
+    if (kq == 0) row_max[wave][nl] = m;
+    __syncthreads();
+    m = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) m = fmaxf(m, row_max[w][nl]);
+    const float s = scale_from_amax(m, divisor);
+    const float r = group_reciprocal(s);
+    if (wave == 0 && kq == 0) scales[(nt * 16 + nl) * G + j] = (half_t)s;
+
+    uint8_t* dst = qweight + ((nt * KT + j * TPG) * 64 + lane) * 16;
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int tp = wave + 16 * i;
+        u32x4_t chunk;
+        uint32_t words[4];
+#pragma unroll
+        for (int t = 0; t < OPT; ++t) quantize_octet<BITS>(raw[i][t], r, &words[t * (4 / OPT)]);
+        chunk[0] = words[0]; chunk[1] = words[1]; chunk[2] = words[2]; chunk[3] = words[3];
+        if (tp < TPG) *reinterpret_cast<u32x4_t*>(dst + (int64_t)tp * 1024) = chunk;
     }
 }
 
@@ -220,10 +314,15 @@ static hipError_t launch_quantize_bits(const void* W, int64_t N, int64_t K, int6
         if (tpg == 1) hipLaunchKernelGGL((quantize_small_group_kernel<BITS, 1>), grid, block, 0, st, w, q, s, N, K, units, divisor);
         else if (tpg == 2) hipLaunchKernelGGL((quantize_small_group_kernel<BITS, 2>), grid, block, 0, st, w, q, s, N, K, units, divisor);
         else hipLaunchKernelGGL((quantize_small_group_kernel<BITS, 4>), grid, block, 0, st, w, q, s, N, K, units, divisor);
+    } else if (tpg * (TK / 32) <= 16 * 28) {
+        // the unit fits the registers of one 16-wavefront workgroup: 8, 16 or 28 loads per lane
+        const int64_t lpl = (tpg * (TK / 32) + 15) / 16;
+        dim3 grid((unsigned)units), block(1024);
+        if (lpl <= 8) hipLaunchKernelGGL((quantize_resident_group_kernel<BITS, 8>), grid, block, 0, st, w, q, s, N, K, g, divisor);
+        else if (lpl <= 16) hipLaunchKernelGGL((quantize_resident_group_kernel<BITS, 16>), grid, block, 0, st, w, q, s, N, K, g, divisor);
+        else hipLaunchKernelGGL((quantize_resident_group_kernel<BITS, 28>), grid, block, 0, st, w, q, s, N, K, g, divisor);
     } else {
-        // enough wavefronts to cover the group, at most 16
-        int waves = (int)(tpg < 16 ? tpg : 16);
-        dim3 grid((unsigned)units), block(64 * waves);
+        dim3 grid((unsigned)units), block(1024);
         hipLaunchKernelGGL((quantize_large_group_kernel<BITS>), grid, block, 0, st, w, q, s, N, K, g, divisor);
     }
     return hipGetLastError();

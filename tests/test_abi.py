@@ -138,3 +138,99 @@ def test_fp32_arithmetic_of_the_gpu_path_equals_exact_rounding():
         ws = (t.astype(np.float32) * np.float32(sc)).astype(np.float16)
         if np.array_equal(ws.astype(np.float64), t.astype(np.float64) * float(sc)):
             assert np.rint(ws.astype(np.float32) / np.float32(sc)).tolist() == [0, 2, 2, 6, 126]
+
+
+def _fp32_round_on_grid(x, grid_log2):
+    """Round-half-even of the exact rational x onto multiples of 2^grid_log2 (one fp32 rounding inside a binade)."""
+    from fractions import Fraction
+    t = x / Fraction(2) ** grid_log2
+    f = t.numerator // t.denominator
+    rem = t - f
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and f % 2 == 1):
+        f += 1
+    return f * Fraction(2) ** grid_log2
+
+
+def _snapped_code_exact(w16, s16, bits):
+    """The per-element arithmetic of the quantise kernels in exact rationals with explicit fp32 roundings:
+    r = fp32(1 / S); y = fp32(w r + C) for C = 768 + offset; z = rint(y)."""
+    from fractions import Fraction
+    off = 8 if bits == 4 else 128
+    r = Fraction(float(np.float32(1.0) / np.float32(s16))) if float(s16) != 0.0 else Fraction(0)
+    t = Fraction(float(w16)) * r + 768 + off
+    assert 512 <= t < 2048
+    y = _fp32_round_on_grid(t, -14 if t < 1024 else -13)       # fp32 spacing in [512, 1024) and [1024, 2048)
+    z = _fp32_round_on_grid(y, 0)
+    lo, hi = 768 + off - (1 << (bits - 1)), 768 + off + (1 << (bits - 1)) - 1
+    return int(min(max(z, lo), hi)) - 768 - off, y
+
+
+def _snapped_code_fp64(w16, s16, off):
+    """Vectorised version of the same (the fused multiply-add formed in fp64, then rounded to fp32)."""
+    s = s16.astype(np.float32)
+    r = np.where(s == 0, np.float32(0), np.float32(1.0) / np.where(s == 0, np.float32(1), s)).astype(np.float32)
+    y = (w16.astype(np.float64) * r.astype(np.float64) + (768.0 + off)).astype(np.float32)
+    return y, np.rint(y).astype(np.float64) - (768.0 + off)
+
+
+def test_reciprocal_and_snap_arithmetic_rounds_like_the_exact_quotient():
+    """The quantise kernels never divide per element: y = fma(w, 1/S, C) lands on a 2^-14 grid on which true
+    ties are hit exactly, and rint(y) - C is the code.  Checked against exact rational arithmetic: random
+    (w, S) pairs, and constructed exact ties w = (i + 1/2) S with scales that are not powers of two."""
+    from fractions import Fraction
+    rng = np.random.default_rng(1)
+
+    def rne(x):
+        f = x.numerator // x.denominator
+        rem = x - f
+        return f + 1 if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and f % 2 == 1) else f
+
+    # bulk, vectorised, against fp64 division (exact enough away from ties; ties are covered below)
+    for off, lim in ((8, 8.6), (128, 128.6)):
+        w = rng.integers(0, 0x7C00, size=1_000_000).astype(np.uint16).view(np.float16)
+        w = np.where(rng.random(w.size) < 0.5, -w, w).astype(np.float16)
+        s = rng.integers(1, 0x7C00, size=1_000_000).astype(np.uint16).view(np.float16)
+        keep = np.abs(w.astype(np.float64) / s.astype(np.float64)) < lim
+        w, s = w[keep], s[keep]
+        assert w.size > 1000
+        _, q = _snapped_code_fp64(w, s, off)
+        assert np.array_equal(q, np.rint(w.astype(np.float64) / s.astype(np.float64)))
+    # group-shaped samples (|w| <= amax, S = fp16(amax / D)), exact rationals, clamp included
+    for bits in (4, 8):
+        for rule in ("qmax", "eq2"):
+            D = O.scale_divisor(bits, rule)
+            amax = rng.integers(1, 0x7C00, size=300).astype(np.uint16).view(np.float16)
+            amax[:40] = np.arange(1, 41, dtype=np.uint16).view(np.float16)          # subnormal scales
+            for am in amax:
+                sc = O.rtn_scale(np.array([am]), bits, rule)[0]
+                ws = (rng.random(6) * float(am)).astype(np.float16)
+                ws[0] = am
+                for wv in ws:
+                    for sign in (1.0, -1.0):
+                        got, _ = _snapped_code_exact(np.float16(sign * float(wv)), sc, bits)
+                        if float(sc) == 0.0:
+                            want = 0
+                        else:
+                            want = rne(Fraction(sign * float(wv)) / Fraction(float(sc)))
+                            want = min(max(want, -(1 << (bits - 1))), (1 << (bits - 1)) - 1)
+                        assert got == want, (bits, rule, float(am), float(wv), float(sc))
+    # exact ties with non-power-of-two scales
+    checked = 0
+    for bits, imax in ((4, 8), (8, 128)):
+        for i in range(imax):
+            odd = 2 * i + 1
+            for _ in range(30):
+                ms = int(rng.integers(1, max(2, 2047 // odd + 1)))
+                ex = int(rng.integers(-20, 6))
+                sv, wv = ms * 2.0 ** ex, odd * ms * 2.0 ** (ex - 1)
+                if wv > 65504 or float(np.float16(sv)) != sv or float(np.float16(wv)) != wv or sv < 2.0 ** -24:
+                    continue
+                for sign in (1, -1):
+                    got, y = _snapped_code_exact(np.float16(sign * wv), np.float16(sv), bits)
+                    off = 8 if bits == 4 else 128
+                    assert y == Fraction(sign * odd, 2) + 768 + off            # the tie itself, not a neighbour
+                    even = i if i % 2 == 0 else i + 1
+                    want = min(max(sign * even, -(1 << (bits - 1))), (1 << (bits - 1)) - 1)
+                    assert got == want
+                    checked += 1
+    assert checked > 3000

@@ -70,12 +70,31 @@ def test_quantize_adversarial(rtn, bits, flags):
     for r in range(9, 32):                                            # multiples of half a scale step
         s = np.float16(rng.uniform(0.001, 0.1))
         W[r, :g] = (rng.integers(-2 * qmax, 2 * qmax + 1, size=g) * 0.5 * float(s)).astype(np.float16)
+    # subnormal scales of one or a few ulps: the quotient overshoots the code range by up to 1.5x and is clamped
+    for r, a in zip(range(32, 44), (10, 11, 17, 180, 190, 191, 300, 317, 500, 700, 1000, 1023)):
+        W[r, :] = 0.0
+        W[r, :g] = (rng.integers(-a, a + 1, size=g) * 2.0 ** -24).astype(np.float16)
+        W[r, 0] = np.float16(a * 2.0 ** -24)
+        W[r, 1] = np.float16(-a * 2.0 ** -24)
     W_t = torch.from_numpy(W).to(DEV)
     qw, sc, codes, scales = _quantize_both(W_t, bits, g, flags)
     assert np.array_equal(_to_np(sc).view(np.uint16), scales.view(np.uint16))
     assert np.array_equal(_to_np(qw), O.pack_gfx950(codes, bits))
     # per-channel on the same tensor
     qw, sc, codes, scales = _quantize_both(W_t, bits, 0, flags)
+    assert np.array_equal(_to_np(sc).view(np.uint16), scales.view(np.uint16))
+    assert np.array_equal(_to_np(qw), O.pack_gfx950(codes, bits))
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("K,g", [(4096, 0), (5120, 0), (8192, 0), (11264, 0), (14336, 0), (16384, 0), (28672, 0),
+                                 (8192, 4096), (14336, 7168), (32768, 16384)])
+def test_quantize_large_groups_every_kernel(rtn, bits, K, g):
+    """Per-channel and wide groups: the register-resident kernels (8, 16, 28 loads per lane, including groups
+    that do not fill the last wavefront's tiles) and the two-pass kernel beyond them."""
+    N = 48
+    W_t = synth.heavy_tail_weight(N, K, 0.02, seed=K + bits, device=DEV)
+    qw, sc, codes, scales = _quantize_both(W_t, bits, g)
     assert np.array_equal(_to_np(sc).view(np.uint16), scales.view(np.uint16))
     assert np.array_equal(_to_np(qw), O.pack_gfx950(codes, bits))
 
