@@ -115,12 +115,15 @@ rtn_status rtn_linear(const void* dev_A, int64_t M, const void* dev_qweight, con
 /* Explicit kernel configuration for rtn_linear_ex (tuning sweeps and tests of every path).
  * A zeroed struct means "choose automatically", field by field. */
 typedef struct {
-    int path;      /* 0 auto, 1 MFMA skinny kernel, 2 vector-ALU dot-product kernel (M <= 4) */
+    int path;      /* 0 auto, 1 MFMA skinny kernel, 2 vector-ALU dot-product kernel (M <= 4), 3 wide MFMA kernel
+                      (group_size a multiple of 128; uses only split_k, m_rows16 = 2..4 and n_tiles16) */
     int prefetch;  /* k-chunks (4 KiB each) a wavefront keeps in flight: 1, 2 or 4 */
     int waves_n;   /* wavefronts of a workgroup along N (share the staged activations): 1, 2, 4, 8, 16 */
     int waves_k;   /* wavefronts of a workgroup along K (in-workgroup split-K): 1 .. 16; waves_n * waves_k <= 16 */
     int split_k;   /* workgroups along K (global split-K, reduced through the workspace) */
-    int m_rows16;  /* 16-row activation blocks each wavefront multiplies per weight tile: 1, 2 or 4 */
+    int m_rows16;  /* 16-row activation blocks each wavefront multiplies per weight tile: 1, 2 or 4 (path 3: 2, 3, 4) */
+    int n_tiles16; /* path 3: 16-column weight tile-rows per wavefront (share each activation operand): 1, 2 or 4;
+                      m_rows16 * n_tiles16 <= 8 */
 } rtn_linear_cfg;
 
 rtn_status rtn_linear_ex(const void* dev_A, int64_t M, const void* dev_qweight, const void* dev_scales,

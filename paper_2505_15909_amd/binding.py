@@ -26,7 +26,7 @@ class RtnError(RuntimeError):
 
 class rtn_linear_cfg(C.Structure):
     _fields_ = [("path", C.c_int), ("prefetch", C.c_int), ("waves_n", C.c_int),
-                ("waves_k", C.c_int), ("split_k", C.c_int), ("m_rows16", C.c_int)]
+                ("waves_k", C.c_int), ("split_k", C.c_int), ("m_rows16", C.c_int), ("n_tiles16", C.c_int)]
 
 
 class rtn_module(C.Structure):

@@ -69,8 +69,46 @@ int round_pow2(int64_t v, int lo, int hi) {
 // and K is split inside the workgroup (reduced through LDS).  With more than two activation rows the
 // staged slice grows, so workgroups widen along N (sharing it) and, for long K, K is also split across
 // workgroups so that a slice stays a few chunks long; those partials go through the workspace.
-LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, size_t lds_limit) {
+// Plan of the wide MFMA kernel for more than 16 rows (from sweeps over the 8B, 70B and 405B shapes at M = 32,
+// 64, 128): wavefronts with two tile-rows (n_tiles16 = 2) are the more efficient ones and are taken whenever K
+// can be split (32 or more k-steps per workgroup, within the workspace cap) far enough to give about two
+// workgroups per compute unit; otherwise one tile-row per wavefront with up to K/1024 splits.
+void wide_plan(int64_t M, int64_t N, int64_t K, LinearPlan* p) {
+    p->path = 3;
+    p->m_rows16 = M <= 32 ? 2 : (M <= 48 ? 3 : 4);
+    p->m_blocks = (int)((M + 16 * p->m_rows16 - 1) / (16 * p->m_rows16));
+    p->prefetch = 1; p->waves_n = 4; p->waves_k = 1;
+    const int64_t KS = K / 128;
+    int64_t smax = (int64_t)(kWorkspaceCap / ((size_t)M * N * sizeof(float)));
+    if (smax < 1) smax = 1;
+    if (smax > kMaxSplitK) smax = kMaxSplitK;
+    for (int nbw = 2; nbw >= 1; --nbw) {
+        if (p->m_rows16 * nbw > 8) continue;
+        const int64_t wgs = (N + 64 * nbw - 1) / (64 * nbw) * p->m_blocks;
+        int64_t cap = KS / (nbw == 2 ? 32 : 8);
+        if (cap > smax) cap = smax;
+        if (cap < 1) cap = 1;
+        const int64_t want = nbw == 2 ? 448 : 384;
+        int64_t s = (want + wgs - 1) / wgs;
+        if (s <= cap || nbw == 1) {
+            p->n_tiles16 = nbw;
+            p->split_k = (int)(s <= cap ? s : cap);
+            return;
+        }
+    }
+}
+
+// force_path: 0 = choose the path, otherwise the default plan of that path.
+LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_t lds_limit, int force_path = 0) {
     LinearPlan p;
+    p.n_tiles16 = 1;
+    // more than 16 rows: the wide kernel, except at 17-32 rows on matrices so large that the skinny kernel's
+    // pure weight streaming still wins
+    const bool wide_wins = g % 128 == 0 && (M > 32 || (M > 16 && (size_t)N * K * bits / 8 <= ((size_t)64 << 20)));
+    if (force_path == 3 || (force_path == 0 && wide_wins)) {
+        wide_plan(M, N, K, &p);
+        return p;
+    }
     const int64_t NT = N / 16, KC = K / chunk_k(bits);
     const int64_t steps = NT * KC;                             // 4 KiB chunk-steps in the whole matrix
     p.m_rows16 = M <= 16 ? 1 : (M <= 32 ? 2 : 4);              // weights are streamed once per 16/32/64 rows
@@ -125,7 +163,7 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, size_t lds_limit
 
 rtn_status resolve_plan(const LinearArgs& a, const rtn_linear_cfg* cfg, size_t workspace_nbytes, LinearPlan* out) {
     const size_t lds_limit = (size_t)device_max_lds();
-    LinearPlan p = auto_plan(a.M, a.N, a.K, a.bits, lds_limit);
+    LinearPlan p = auto_plan(a.M, a.N, a.K, a.bits, a.g, lds_limit, cfg ? cfg->path : 0);
     if (cfg) {
         if (cfg->path) p.path = cfg->path;
         if (cfg->prefetch) p.prefetch = cfg->prefetch;
@@ -136,9 +174,21 @@ rtn_status resolve_plan(const LinearArgs& a, const rtn_linear_cfg* cfg, size_t w
             p.m_rows16 = cfg->m_rows16;
             p.m_blocks = (int)((a.M + 16 * p.m_rows16 - 1) / (16 * p.m_rows16));
         }
+        if (cfg->n_tiles16) p.n_tiles16 = cfg->n_tiles16;
     }
     const int64_t KC = a.K / chunk_k(a.bits);
-    if (p.path != 1 && p.path != 2) return RTN_ERR_CONFIG;
+    if (p.path < 1 || p.path > 3) return RTN_ERR_CONFIG;
+    if (p.path == 3) {
+        if (!rtn::wide_plan_valid(a, p) || p.split_k > kMaxSplitK) return RTN_ERR_CONFIG;
+        if ((uint64_t)a.N * a.K * a.bits / 8 >= 0x7FFF0000ull || (uint64_t)a.M * a.K * 2 >= 0x7FFF0000ull)
+            return RTN_ERR_SHAPE;                               // 32-bit buffer offsets
+        if (p.split_k > 1) {
+            const size_t need = (size_t)a.M * a.N * sizeof(float) * p.split_k;
+            if (a.workspace == nullptr || workspace_nbytes < need) return RTN_ERR_WORKSPACE;
+        }
+        *out = p;
+        return RTN_OK;
+    }
     if (p.path == 2 && (a.M > 4 || p.prefetch != 1 || p.m_rows16 != 1)) return RTN_ERR_CONFIG;
     if (p.prefetch != 1 && p.prefetch != 2 && p.prefetch != 4) return RTN_ERR_CONFIG;
     if (p.m_rows16 != 1 && p.m_rows16 != 2 && p.m_rows16 != 4) return RTN_ERR_CONFIG;
@@ -247,9 +297,10 @@ rtn_status rtn_linear_query(int64_t M, int64_t N, int64_t K, int bits, int group
     rtn_status st = check_problem(N, K, bits, group_size, &g);
     if (st != RTN_OK) return st;
     if (M <= 0) return RTN_ERR_SHAPE;
-    LinearPlan p = auto_plan(M, N, K, bits, (size_t)device_max_lds());
+    LinearPlan p = auto_plan(M, N, K, bits, g, (size_t)device_max_lds());
     out->path = p.path; out->prefetch = p.prefetch; out->waves_n = p.waves_n;
     out->waves_k = p.waves_k; out->split_k = p.split_k; out->m_rows16 = p.m_rows16;
+    out->n_tiles16 = p.n_tiles16;
     return RTN_OK;
 }
 

@@ -9,13 +9,14 @@ constexpr size_t kMaxLdsBytes = 160 * 1024;   // LDS of one gfx950 compute unit,
 
 // Resolved launch configuration of the fused dequantise-GEMM.
 struct LinearPlan {
-    int path;       // 1 = MFMA skinny kernel, 2 = vector-ALU dot kernel
+    int path;       // 1 = MFMA skinny kernel, 2 = vector-ALU dot kernel, 3 = wide MFMA kernel (larger batches)
     int prefetch;   // k-chunks in flight per wavefront (register buffers): 1, 2 or 4
     int waves_n;    // wavefronts along N per workgroup
     int waves_k;    // wavefronts along K per workgroup
     int split_k;    // workgroups along K
     int m_rows16;   // 16-row activation blocks per wavefront: 1, 2 or 4 (prefetch must be 1 above 1)
     int m_blocks;   // activation blocks of 16 * m_rows16 rows (grid.z)
+    int n_tiles16;  // path 3: 16-column weight tile-rows per wavefront: 1, 2 or 4
 };
 
 struct LinearArgs {
@@ -33,6 +34,11 @@ hipError_t launch_quantize(const void* W, int64_t N, int64_t K, int bits, int64_
 hipError_t launch_unpack(const void* qweight, const void* scales, int64_t N, int64_t K, int bits, int64_t g,
                          bool dequant, void* out, hipStream_t st);
 hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t st);
+// Path 3 (wide MFMA kernel): plan check (group size a multiple of 128, 2-4 row blocks, 1/2/4 tile-rows, at most 8 blocks) and launch.
+bool wide_plan_valid(const LinearArgs& a, const LinearPlan& p);
+hipError_t launch_linear_wide(const LinearArgs& a, const LinearPlan& p, hipStream_t st);
+// Sums split_k fp32 partial outputs [split_k][MN] in a fixed order into fp16 C (MN a multiple of 16).
+hipError_t launch_splitk_reduce(const float* workspace, void* C_fp16, int64_t MN, int split_k, hipStream_t st);
 
 // LDS bytes the skinny kernel needs for a plan (staged activation slice incl. the zero row, or the
 // in-workgroup split-K reduction buffer, whichever is larger).

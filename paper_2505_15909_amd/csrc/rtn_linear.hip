@@ -468,6 +468,7 @@ static hipError_t launch_skinny(const SkinnyParams& sp, int ngc, int nb, bool mu
 }
 
 hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t st) {
+    if (p.path == 3) return launch_linear_wide(a, p, st);
     const int tk = (a.bits == 4) ? 128 : 64;
     const int ck = kChunkTiles * tk;
     SkinnyParams sp;
@@ -517,13 +518,14 @@ hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t s
                           : launch_skinny<8>(sp, ngc, p.prefetch, sgm.multi, p.m_rows16, grid, block, lds, st);
     }
     if (e != hipSuccess) return e;
-    if (p.split_k > 1) {
-        const int64_t MN = a.M * a.N;
-        dim3 rgrid((unsigned)((MN / 4 + 255) / 256)), rblock(256);
-        hipLaunchKernelGGL(splitk_reduce_kernel, rgrid, rblock, 0, st, a.workspace, sp.C, MN, p.split_k);
-        e = hipGetLastError();
-    }
+    if (p.split_k > 1) e = launch_splitk_reduce(a.workspace, sp.C, a.M * a.N, p.split_k, st);
     return e;
+}
+
+hipError_t launch_splitk_reduce(const float* workspace, void* C_fp16, int64_t MN, int split_k, hipStream_t st) {
+    dim3 rgrid((unsigned)((MN / 4 + 255) / 256)), rblock(256);
+    hipLaunchKernelGGL(splitk_reduce_kernel, rgrid, rblock, 0, st, workspace, static_cast<half_t*>(C_fp16), MN, split_k);
+    return hipGetLastError();
 }
 
 }  // namespace rtn

@@ -1,0 +1,289 @@
+// Fused dequantise-GEMM for larger batches (Section 5: the same weight-only quantised linear layer,
+// C = A (q S)^T, when more than a few tokens are processed at once and the matrix cores, not the weight
+// stream, start to bound the time).
+//
+// Wide MFMA kernel.  A workgroup is 4 wavefronts side by side along N; every wavefront owns NBW
+// consecutive 16-row weight tile-rows (16 NBW output columns) and all 16 MB activation rows of the
+// workgroup's row block, i.e. a (16 MB) x (16 NBW) register tile of fp32 accumulators:
+//   - packed weights go from global memory straight into registers in MFMA operand order (that is what
+//     the packed layout is for), three 128-column k-steps deep, and are unpacked once per k-step for all
+//     MB row blocks;
+//   - the activations of a k-step (16 MB rows x 128 columns) are staged through LDS by the whole
+//     workgroup, double buffered, in 16-byte pieces whose position inside a row is XOR-swizzled with
+//     the row number so that both the staging writes and the b128 operand reads are conflict-free
+//     without padding; one operand read feeds NBW MFMAs;
+//   - arithmetic is that of the skinny kernel: exact integer codes into v_mfma_f32_16x16x32_f16, the
+//     fp16 scale applied in fp32 to the partial sum of each group (or of the part of a group that lies
+//     in this workgroup's k-range: scaling is linear, so groups may straddle split-K boundaries).
+// Row blocks of 16 MB rows beyond the first are separate workgroups that re-read the weights; the
+// workgroup index is decoded so that the workgroups sharing a weight range are dispatched back to back on
+// the same XCD and the second reader hits that XCD's L2.
+#include "rtn_device.h"
+#include "rtn_internal.h"
+
+namespace rtn {
+
+namespace {
+
+constexpr int kStepK = 128;                     // columns per k-step
+constexpr int kWideWaves = 4;
+constexpr int kWideThreads = 64 * kWideWaves;
+constexpr uint32_t kOutOfRange = 0x7FFF0000u;   // beyond any resource size used here (< 2 GiB)
+constexpr int kBufferFlags = 0x00020000;        // raw buffer, 32-bit data format
+constexpr int kXcds = 8;
+
+struct WideParams {
+    const half_t* A;
+    const uint8_t* qw;
+    const half_t* scales;
+    half_t* C;
+    float* ws;
+    int M, N, K;
+    int G;              // groups per row
+    int spg;            // k-steps per group (g / 128)
+    int NT;             // N / 16
+    int KL;             // tiles per weight row
+    int KS;             // k-steps per row (K / 128)
+    int XB;             // workgroups along N
+    int ZB;             // row blocks
+    int split_k;
+    int ks_base, ks_rem;   // workgroup sg covers k-steps [sg*ks_base + min(sg, ks_rem), ...)
+    uint32_t spg_inv;      // floor(2^32 / spg) + 1 (0 when spg == 1): k-step -> group by multiply-high
+    uint32_t qw_bytes, sc_bytes, a_bytes;
+};
+
+// G1: one k-step per group (group size 128): every k-step starts its partial sums from zero, which the
+// first MFMA of the step takes as a constant operand instead of a cleared register.
+// At least two wavefronts per SIMD (256 registers each): the MFMAs then keep their accumulators in ordinary
+// vector registers, where the scale multiply-add can read them directly.
+template <int BITS, int MB, int NBW, bool G1>
+__global__ __launch_bounds__(kWideThreads, 2) void wide_mfma_kernel(const WideParams p) {
+    constexpr int TK = Layout<BITS>::TK;
+    constexpr int MPT = Layout<BITS>::MFMA_PER_TILE;
+    constexpr int TPS = kStepK / TK;                      // tiles per k-step and tile-row: 1 / 2
+    constexpr int ROWS = 16 * MB;
+    constexpr int BUF_BYTES = ROWS * kStepK * 2;
+    __shared__ __align__(16) uint8_t lds_a[2 * BUF_BYTES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nl = lane & 15, kq = lane >> 4;
+
+    // workgroup index -> (N block, row block): the ZB row blocks of one N block are kXcds apart
+    const int L = blockIdx.x;
+    const int xcd = L % kXcds, idx = L / kXcds;
+    const int z = idx % p.ZB;
+    const int xb = (idx / p.ZB) * kXcds + xcd;
+    if (xb >= p.XB) return;                               // padding of the last group of 8 (whole workgroup)
+    const int m0 = z * ROWS;
+    const int sg = blockIdx.y;
+    const int ks0 = sg * p.ks_base + min(sg, p.ks_rem);
+    const int T = p.ks_base + (sg < p.ks_rem ? 1 : 0);    // k-steps of this workgroup
+
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.qw), 0, p.qw_bytes, kBufferFlags);
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<half_t*>(p.scales), 0, p.sc_bytes, kBufferFlags);
+    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<half_t*>(p.A), 0, p.a_bytes, kBufferFlags);
+    const uint32_t magic = fp16_magic_vgpr();
+
+    const int nt0 = (xb * kWideWaves + wave) * NBW;       // first tile-row of this wavefront
+    uint32_t w_lane[NBW], s_lane[NBW];
+    bool nt_ok[NBW];
+#pragma unroll
+    for (int r = 0; r < NBW; ++r) {
+        nt_ok[r] = nt0 + r < p.NT;
+        w_lane[r] = (uint32_t)(nt0 + r) * (uint32_t)p.KL * 1024u + lane * 16;
+        s_lane[r] = ((uint32_t)(nt0 + r) * 16 + nl) * (uint32_t)p.G * 2u;
+    }
+
+    // ---- activation staging: thread t moves pieces t, t + 256, ...; piece -> (row, 16-byte column p) ----
+    const int st_p = tid & 15, st_row0 = tid >> 4;        // MB pieces per thread: rows st_row0 + 16 i
+    u32x4_t areg[MB];
+    auto a_load = [&](int t) {                            // k-step t of this workgroup (out of range: zeros)
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            const int row = st_row0 + 16 * i;
+            const bool ok = t < T && m0 + row < p.M;
+            const uint32_t off = ok ? ((uint32_t)(m0 + row) * (uint32_t)p.K + (uint32_t)(ks0 + t) * kStepK + st_p * 8) * 2u : kOutOfRange;
+            areg[i] = __builtin_amdgcn_raw_buffer_load_b128(ra, off, 0, 0);
+        }
+    };
+    auto a_store = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            const int row = st_row0 + 16 * i;             // row & 15 == st_row0 & 15
+            *reinterpret_cast<u32x4_t*>(lds_a + buf * BUF_BYTES + (row * 16 + (st_p ^ (row & 15))) * 16) = areg[i];
+        }
+    };
+
+    // ---- weight / scale ring, three k-steps deep ----
+    u32x4_t wbuf[3][NBW][TPS];
+    uint16_t sbuf[3][NBW];
+    auto w_load = [&](int slot, int t) {
+        const bool in = t < T;
+        const uint32_t ks = (uint32_t)(ks0 + t);
+        const uint32_t j = p.spg_inv == 0 ? ks : __umulhi(ks, p.spg_inv);
+#pragma unroll
+        for (int r = 0; r < NBW; ++r) {
+            const bool ok = in && nt_ok[r];
+            sbuf[slot][r] = __builtin_amdgcn_raw_buffer_load_b16(rs, ok ? s_lane[r] + j * 2u : kOutOfRange, 0, 0);
+#pragma unroll
+            for (int c = 0; c < TPS; ++c)
+                wbuf[slot][r][c] = __builtin_amdgcn_raw_buffer_load_b128(
+                    rw, ok ? w_lane[r] + (ks * TPS + c) * 1024u : kOutOfRange, 0, 2 /* nt */);
+        }
+    };
+
+    float4_t acc[MB][NBW], part[MB][NBW];
+#pragma unroll
+    for (int b = 0; b < MB; ++b)
+#pragma unroll
+        for (int r = 0; r < NBW; ++r) {
+            acc[b][r] = (float4_t){0.f, 0.f, 0.f, 0.f};
+            part[b][r] = (float4_t){0.f, 0.f, 0.f, 0.f};
+        }
+
+    auto scale_row = [&](int slot, int r) {
+        const float sc = (float)__builtin_bit_cast(half_t, sbuf[slot][r]);
+#pragma unroll
+        for (int b = 0; b < MB; ++b) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[b][r][e] = fmaf(sc, part[b][r][e], acc[b][r][e]);
+            if constexpr (!G1) part[b][r] = (float4_t){0.f, 0.f, 0.f, 0.f};
+        }
+    };
+
+    // steps left in the current group when this workgroup starts
+    int left = p.spg - (int)((uint32_t)ks0 - (p.spg_inv == 0 ? (uint32_t)ks0 : __umulhi((uint32_t)ks0, p.spg_inv)) * (uint32_t)p.spg);
+
+    auto step = [&](int slot, int t) {
+        a_store((t + 1) & 1);                             // A(t+1), loaded during the previous step
+        a_load(t + 2);
+        w_load((slot + 2) % 3, t + 2);
+        const uint8_t* abase = lds_a + (t & 1) * BUF_BYTES + (nl * 16) * 16;
+        const bool ends = (--left == 0) || (t == T - 1);  // the group, or this workgroup's share of it, ends
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            half8_t a[MB];
+#pragma unroll
+            for (int b = 0; b < MB; ++b)
+                a[b] = *reinterpret_cast<const half8_t*>(abase + (b * 256 + ((i * 4 + kq) ^ nl)) * 16);
+#pragma unroll
+            for (int r = 0; r < NBW; ++r) {
+                const half8_t bw = unpack_operand<BITS>(wbuf[slot][r][i / MPT], i % MPT, magic);
+#pragma unroll
+                for (int b = 0; b < MB; ++b) {
+                    const float4_t c_in = (G1 && i == 0) ? (float4_t){0.f, 0.f, 0.f, 0.f} : part[b][r];
+                    part[b][r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[b], bw, c_in, 0, 0, 0);
+                }
+                if (i == 3 && ends && r > 0) scale_row(slot, r - 1);     // overlaps the next tile-row's MFMAs
+            }
+        }
+        if (ends) {
+            scale_row(slot, NBW - 1);
+            left = p.spg;
+        }
+        __syncthreads();
+    };
+
+    // ---- prologue ----
+    a_load(0);
+    w_load(0, 0);
+    w_load(1, 1);
+    a_store(0);
+    a_load(1);
+    __syncthreads();
+
+    for (int t = 0; t < T; t += 3) {
+        step(0, t);
+        if (t + 1 < T) step(1, t + 1);
+        if (t + 2 < T) step(2, t + 2);
+    }
+
+    // ---- store: lane holds rows m = 16 b + 4 kq + e, column n = 16 (nt0 + r) + nl ----
+#pragma unroll
+    for (int r = 0; r < NBW; ++r) {
+        if (!nt_ok[r]) continue;
+        const int n = (nt0 + r) * 16 + nl;
+#pragma unroll
+        for (int b = 0; b < MB; ++b) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int m = m0 + b * 16 + kq * 4 + e;
+                if (m < p.M) {
+                    if (p.split_k == 1) p.C[(int64_t)m * p.N + n] = (half_t)acc[b][r][e];
+                    else p.ws[((int64_t)sg * p.M + m) * p.N + n] = acc[b][r][e];
+                }
+            }
+        }
+    }
+}
+
+template <int BITS, int MB, int NBW>
+hipError_t launch_wide_g1(const WideParams& wp, dim3 grid, hipStream_t st) {
+    dim3 block(kWideThreads);
+    if (wp.spg == 1) hipLaunchKernelGGL((wide_mfma_kernel<BITS, MB, NBW, true>), grid, block, 0, st, wp);
+    else hipLaunchKernelGGL((wide_mfma_kernel<BITS, MB, NBW, false>), grid, block, 0, st, wp);
+    return hipGetLastError();
+}
+
+// Register tiles of up to 8 accumulator blocks (MB * NBW <= 8) fit 256 registers without spilling.
+template <int BITS>
+hipError_t launch_wide_bits(const WideParams& wp, int mb, int nbw, dim3 grid, hipStream_t st) {
+    switch (mb * 10 + nbw) {
+        case 21: return launch_wide_g1<BITS, 2, 1>(wp, grid, st);
+        case 22: return launch_wide_g1<BITS, 2, 2>(wp, grid, st);
+        case 24: return launch_wide_g1<BITS, 2, 4>(wp, grid, st);
+        case 31: return launch_wide_g1<BITS, 3, 1>(wp, grid, st);
+        case 32: return launch_wide_g1<BITS, 3, 2>(wp, grid, st);
+        case 41: return launch_wide_g1<BITS, 4, 1>(wp, grid, st);
+        case 42: return launch_wide_g1<BITS, 4, 2>(wp, grid, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+bool wide_plan_valid(const LinearArgs& a, const LinearPlan& p) {
+    if (a.g % kStepK != 0) return false;
+    if (p.m_rows16 < 2 || p.m_rows16 > 4) return false;
+    if (p.n_tiles16 != 1 && p.n_tiles16 != 2 && p.n_tiles16 != 4) return false;
+    if (p.m_rows16 * p.n_tiles16 > 8) return false;       // register tile: at most 8 accumulator blocks
+    if (p.split_k < 1 || p.split_k > a.K / kStepK) return false;
+    return true;
+}
+
+hipError_t launch_linear_wide(const LinearArgs& a, const LinearPlan& p, hipStream_t st) {
+    const int tk = (a.bits == 4) ? 128 : 64;
+    WideParams wp;
+    wp.A = static_cast<const half_t*>(a.A);
+    wp.qw = static_cast<const uint8_t*>(a.qweight);
+    wp.scales = static_cast<const half_t*>(a.scales);
+    wp.C = static_cast<half_t*>(a.C);
+    wp.ws = a.workspace;
+    wp.M = (int)a.M; wp.N = (int)a.N; wp.K = (int)a.K;
+    wp.G = (int)(a.K / a.g);
+    wp.spg = (int)(a.g / kStepK);
+    wp.spg_inv = wp.spg == 1 ? 0u : (uint32_t)(((uint64_t)1 << 32) / (uint32_t)wp.spg) + 1u;
+    wp.NT = (int)(a.N / 16);
+    wp.KL = (int)(a.K / tk);
+    wp.KS = (int)(a.K / kStepK);
+    const int cols_wg = 16 * p.n_tiles16 * kWideWaves;
+    wp.XB = (int)((a.N + cols_wg - 1) / cols_wg);
+    wp.ZB = p.m_blocks;
+    wp.split_k = p.split_k;
+    wp.ks_base = wp.KS / p.split_k;
+    wp.ks_rem = wp.KS % p.split_k;
+    wp.qw_bytes = (uint32_t)((size_t)a.N * a.K * a.bits / 8);
+    wp.sc_bytes = (uint32_t)((size_t)a.N * wp.G * 2);
+    wp.a_bytes = (uint32_t)((size_t)a.M * a.K * 2);
+    const int xb_pad = (wp.XB + kXcds - 1) / kXcds * kXcds;
+    dim3 grid((unsigned)(xb_pad * wp.ZB), (unsigned)p.split_k, 1);
+    hipError_t e = (a.bits == 4) ? launch_wide_bits<4>(wp, p.m_rows16, p.n_tiles16, grid, st)
+                                 : launch_wide_bits<8>(wp, p.m_rows16, p.n_tiles16, grid, st);
+    if (e != hipSuccess) return e;
+    if (p.split_k > 1) e = launch_splitk_reduce(a.workspace, static_cast<half_t*>(a.C), a.M * a.N, p.split_k, st);
+    return e;
+}
+
+}  // namespace rtn

@@ -66,8 +66,14 @@ def test_argument_validation_happens_before_any_launch():
     assert _linear(cfg=C.byref(cfg)) == 7                         # wavefront counts are powers of two
     cfg = rtn.rtn_linear_cfg(waves_n=8, waves_k=4)
     assert _linear(cfg=C.byref(cfg)) == 7                         # at most 16 wavefronts per workgroup
-    cfg = rtn.rtn_linear_cfg(path=3)
+    cfg = rtn.rtn_linear_cfg(path=4)
     assert _linear(cfg=C.byref(cfg)) == 7
+    for bad in (dict(m_rows16=1), dict(m_rows16=5), dict(m_rows16=2, n_tiles16=3), dict(m_rows16=4, n_tiles16=4),
+                dict(m_rows16=2, n_tiles16=1, split_k=1000)):
+        cfg = rtn.rtn_linear_cfg(path=3, **bad)                    # the wide kernel's register-tile limits
+        assert _linear(M=40, cfg=C.byref(cfg)) == 7
+    cfg = rtn.rtn_linear_cfg(path=3, m_rows16=2, n_tiles16=1)
+    assert _linear(M=40, bits=8, g=64, K=512, cfg=C.byref(cfg)) == 7     # its k-steps are 128 columns
     cfg = rtn.rtn_linear_cfg(path=2)
     assert _linear(M=5, cfg=C.byref(cfg)) == 7                    # the vector-ALU path is for M <= 4
     cfg = rtn.rtn_linear_cfg(split_k=2)
@@ -83,6 +89,13 @@ def test_bad_valid_combination_is_not_launched_without_gpu():
     # a per-channel request is g <= 0 or g == K
     q = rtn.rtn_linear_query(1, 4096, 4096, 4, 0)
     assert q["path"] == 1 and q["split_k"] >= 1
+    # more than 16 rows go to the wide kernel (group sizes that are multiples of 128), within its tile limits
+    for M in (17, 32, 33, 64, 100, 128, 1000):
+        q = rtn.rtn_linear_query(M, 4096, 4096, 4, 128)
+        assert q["path"] == 3 and 2 <= q["m_rows16"] <= 4 and q["m_rows16"] * q["n_tiles16"] <= 8
+        assert M * 4096 * 4 * q["split_k"] <= 16 << 20 or q["split_k"] == 1
+    assert rtn.rtn_linear_query(64, 4096, 4096, 8, 64)["path"] == 1
+    assert rtn.rtn_linear_query(32, 16384, 106496, 4, 128)["path"] == 1     # very large matrix at 32 rows: streaming wins
     with pytest.raises(rtn.RtnError):
         rtn.rtn_linear_query(1, 4096, 4000, 4, 128)
 

@@ -183,10 +183,10 @@ def test_linear_larger_batches(rtn, bits, g, M):
     C = rtn.rtn_linear(A_t, qw, sc, bits, g)
     torch.cuda.synchronize()
     H.assert_linear_close(_to_np(C), ref, f"bits={bits} g={g} M={M}")
-    # every activation-block width, wide and K-split workgroups
-    for cfg in (dict(m_rows16=1, waves_n=4, waves_k=2), dict(m_rows16=2, waves_n=8, waves_k=1),
-                dict(m_rows16=2, waves_n=4, waves_k=2, split_k=2), dict(m_rows16=4, waves_n=16, waves_k=1),
-                dict(m_rows16=4, waves_n=8, waves_k=2, split_k=4), dict(m_rows16=4, waves_n=4, waves_k=4)):
+    # the skinny kernel with every activation-block width, wide and K-split workgroups
+    for cfg in (dict(path=1), dict(path=1, m_rows16=1, waves_n=4, waves_k=2), dict(path=1, m_rows16=2, waves_n=8, waves_k=1),
+                dict(path=1, m_rows16=2, waves_n=4, waves_k=2, split_k=2), dict(path=1, m_rows16=4, waves_n=16, waves_k=1),
+                dict(path=1, m_rows16=4, waves_n=8, waves_k=2, split_k=4), dict(path=1, m_rows16=4, waves_n=4, waves_k=4)):
         try:
             C = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=cfg)
         except rtn.RtnError as e:
@@ -194,6 +194,38 @@ def test_linear_larger_batches(rtn, bits, g, M):
             continue
         torch.cuda.synchronize()
         H.assert_linear_close(_to_np(C), ref, f"bits={bits} g={g} M={M} cfg={cfg}")
+
+
+@pytest.mark.parametrize("bits,g", [(4, 128), (4, 256), (4, 512), (4, 0), (8, 128), (8, 256), (8, 0)])
+@pytest.mark.parametrize("M", [5, 17, 33, 48, 64, 100, 130])
+def test_linear_wide_kernel(rtn, bits, g, M):
+    """The wide MFMA kernel (path 3): every register-tile shape, ragged M and N, K split across workgroups
+    inside and across groups, several row blocks."""
+    N, K = 528, 2560                       # 33 tile-rows: the last workgroup is partly out of range; 20 k-steps
+    codes, scales, qw, sc, gg = _oracle_operands(N, K, bits, g, seed=6)
+    A_t = synth.activation(M, K, seed=200 + M, device=DEV)
+    ref = O.rtn_linear(_to_np(A_t), codes, scales, gg)
+    ran = 0
+    for mb in (2, 3, 4):
+        for nbw in (1, 2, 4):
+            for split in (1, 3, 7):
+                cfg = dict(path=3, m_rows16=mb, n_tiles16=nbw, split_k=split)
+                if mb * nbw > 8:            # register tile too large: refused, not launched
+                    with pytest.raises(rtn.RtnError):
+                        rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=cfg)
+                    continue
+                C = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=cfg)
+                torch.cuda.synchronize()
+                H.assert_linear_close(_to_np(C), ref, f"bits={bits} g={g} M={M} cfg={cfg}")
+                ran += 1
+    assert ran == 21
+    C1 = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=dict(path=3, m_rows16=4, n_tiles16=2, split_k=3))
+    C2 = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=dict(path=3, m_rows16=4, n_tiles16=2, split_k=3))
+    assert torch.equal(C1, C2)
+    if bits == 8:                           # group 64 does not fit the kernel's 128-column k-steps
+        _, _, qw64, sc64, _ = _oracle_operands(N, K, 8, 64, seed=6)
+        with pytest.raises(rtn.RtnError):
+            rtn.rtn_linear(A_t, qw64, sc64, 8, 64, cfg=dict(path=3, m_rows16=2, n_tiles16=1))
 
 
 @pytest.mark.parametrize("bits,g", [(4, 128), (8, 64), (8, 0)])
