@@ -116,7 +116,8 @@ rtn_status rtn_linear(const void* dev_A, int64_t M, const void* dev_qweight, con
  * A zeroed struct means "choose automatically", field by field. */
 typedef struct {
     int path;      /* 0 auto, 1 MFMA skinny kernel, 2 vector-ALU dot-product kernel (M <= 4), 3 wide MFMA kernel
-                      (group_size a multiple of 128; uses only split_k, m_rows16 = 2..4 and n_tiles16) */
+                      (group_size a multiple of 128; uses only split_k, m_rows16 = 2..4 and n_tiles16), 4 tile kernel: 128 x 128
+                      output tiles, weights dequantised to fp16 in LDS (group_size a multiple of 128; uses only split_k) */
     int prefetch;  /* k-chunks (4 KiB each) a wavefront keeps in flight: 1, 2 or 4 */
     int waves_n;   /* wavefronts of a workgroup along N (share the staged activations): 1, 2, 4, 8, 16 */
     int waves_k;   /* wavefronts of a workgroup along K (in-workgroup split-K): 1 .. 16; waves_n * waves_k <= 16 */
@@ -141,6 +142,23 @@ rtn_status rtn_unpack(const void* dev_qweight, int64_t N, int64_t K, int bits, v
  * large-input path of Section 5 (dequantise, then a dense 16-bit GEMM). */
 rtn_status rtn_dequantize(const void* dev_qweight, const void* dev_scales, int64_t N, int64_t K, int bits,
                           int group_size, void* dev_W_fp16, void* stream);
+
+/* Dense 16-bit GEMM, the second half of the large-input path of Section 5:
+ *   C[m, n] = fp16( sum_k A[m, k] * W[n, k] ), fp32 accumulation on the matrix cores.
+ *   dev_A fp16 [M, K]; dev_W_fp16 fp16 [N, K] row-major (what rtn_dequantize writes); dev_C fp16 [M, N].
+ * K % 128 == 0, N % 16 == 0.  dev_workspace may be NULL (no split-K); otherwise it is used for split-K partials
+ * when M and N give fewer 128 x 128 output tiles than compute units. */
+rtn_status rtn_gemm_fp16(const void* dev_A, int64_t M, const void* dev_W_fp16, int64_t N, int64_t K, void* dev_C,
+                         void* dev_workspace, size_t workspace_nbytes, void* stream);
+
+/* The dual-path forward of Section 5 for inputs with many rows: dequantise the weights to 16 bit into the
+ * caller's temporary buffer, then run the dense GEMM.  dev_W_tmp must hold rtn_dense_weight_nbytes(N, K) =
+ * 2 N K bytes; its contents afterwards are the dequantised weights.  Same result contract as rtn_linear (each
+ * weight is rounded to fp16 once after scaling, inside the layer's tolerance). */
+size_t rtn_dense_weight_nbytes(int64_t N, int64_t K);
+rtn_status rtn_linear_dense(const void* dev_A, int64_t M, const void* dev_qweight, const void* dev_scales,
+                            int64_t N, int64_t K, int bits, int group_size, void* dev_C, void* dev_W_tmp,
+                            size_t w_tmp_nbytes, void* dev_workspace, size_t workspace_nbytes, void* stream);
 
 /* One linear module of a Transformer layer with its own precision (Section 4: each of the
  * four linear modules of a layer may be kept at 8 bit while the rest is at 4 bit). */

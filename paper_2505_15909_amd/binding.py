@@ -62,6 +62,12 @@ def _load() -> C.CDLL:
     lib.rtn_unpack.argtypes = [vp, i64, i64, ci, vp, vp]
     lib.rtn_dequantize.restype = ci
     lib.rtn_dequantize.argtypes = [vp, vp, i64, i64, ci, ci, vp, vp]
+    lib.rtn_gemm_fp16.restype = ci
+    lib.rtn_gemm_fp16.argtypes = [vp, i64, vp, i64, i64, vp, vp, sz, vp]
+    lib.rtn_dense_weight_nbytes.restype = sz
+    lib.rtn_dense_weight_nbytes.argtypes = [i64, i64]
+    lib.rtn_linear_dense.restype = ci
+    lib.rtn_linear_dense.argtypes = [vp, i64, vp, vp, i64, i64, ci, ci, vp, vp, sz, vp, sz, vp]
     lib.rtn_layer_forward.restype = ci
     lib.rtn_layer_forward.argtypes = [C.POINTER(rtn_module), ci, vp, sz, vp]
     lib.rtn_plan_bits.restype = ci
@@ -74,7 +80,8 @@ def _load() -> C.CDLL:
 _lib = _load()
 EXPORTS = ["rtn_status_str", "rtn_layout_version", "rtn_qweight_nbytes", "rtn_scales_nbytes",
            "rtn_workspace_nbytes", "rtn_quantize", "rtn_linear", "rtn_linear_ex", "rtn_linear_query",
-           "rtn_unpack", "rtn_dequantize", "rtn_layer_forward", "rtn_plan_bits", "rtn_plan_effective_bits"]
+           "rtn_unpack", "rtn_dequantize", "rtn_gemm_fp16", "rtn_dense_weight_nbytes", "rtn_linear_dense",
+           "rtn_layer_forward", "rtn_plan_bits", "rtn_plan_effective_bits"]
 
 
 def _check(status: int, what: str):
@@ -175,6 +182,38 @@ def rtn_dequantize(qweight: torch.Tensor, scales: torch.Tensor, K: int, bits: in
     _check(_lib.rtn_dequantize(qweight.data_ptr(), scales.data_ptr(), N, K, bits, group_size, W.data_ptr(),
                                _stream()), "rtn_dequantize")
     return W
+
+
+def rtn_gemm_fp16(A: torch.Tensor, W: torch.Tensor, out: torch.Tensor = None, workspace: torch.Tensor = None) -> torch.Tensor:
+    """Dense A fp16 [M, K] times W fp16 [N, K] transposed -> C fp16 [M, N]."""
+    _dev_fp16(A, "A")
+    _dev_fp16(W, "W")
+    M, K = A.shape
+    N = W.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=A.device)
+    wp, wn = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) if workspace is not None else (None, 0)
+    _check(_lib.rtn_gemm_fp16(A.data_ptr(), M, W.data_ptr(), N, K, out.data_ptr(), wp, wn, _stream()), "rtn_gemm_fp16")
+    return out
+
+
+def rtn_linear_dense(A: torch.Tensor, qweight: torch.Tensor, scales: torch.Tensor, bits: int, group_size: int,
+                     w_tmp: torch.Tensor, out: torch.Tensor = None, workspace: torch.Tensor = None) -> torch.Tensor:
+    """The dequantise-then-GEMM path: w_tmp is a caller-owned buffer of rtn_dense_weight_nbytes(N, K) bytes."""
+    _dev_fp16(A, "A")
+    M, K = A.shape
+    N = scales.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=A.device)
+    wp, wn = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) if workspace is not None else (None, 0)
+    _check(_lib.rtn_linear_dense(A.data_ptr(), M, qweight.data_ptr(), scales.data_ptr(), N, K, bits, group_size,
+                                 out.data_ptr(), w_tmp.data_ptr(), w_tmp.numel() * w_tmp.element_size(), wp, wn,
+                                 _stream()), "rtn_linear_dense")
+    return out
+
+
+def rtn_dense_weight_nbytes(N: int, K: int) -> int:
+    return _lib.rtn_dense_weight_nbytes(N, K)
 
 
 class LayerPlan:

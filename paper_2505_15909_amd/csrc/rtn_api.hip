@@ -177,9 +177,10 @@ rtn_status resolve_plan(const LinearArgs& a, const rtn_linear_cfg* cfg, size_t w
         if (cfg->n_tiles16) p.n_tiles16 = cfg->n_tiles16;
     }
     const int64_t KC = a.K / chunk_k(a.bits);
-    if (p.path < 1 || p.path > 3) return RTN_ERR_CONFIG;
-    if (p.path == 3) {
-        if (!rtn::wide_plan_valid(a, p) || p.split_k > kMaxSplitK) return RTN_ERR_CONFIG;
+    if (p.path < 1 || p.path > 4) return RTN_ERR_CONFIG;
+    if (p.path >= 3) {
+        const bool ok = p.path == 3 ? rtn::wide_plan_valid(a, p) : rtn::tile_plan_valid(a, p);
+        if (!ok || p.split_k > kMaxSplitK) return RTN_ERR_CONFIG;
         if ((uint64_t)a.N * a.K * a.bits / 8 >= 0x7FFF0000ull || (uint64_t)a.M * a.K * 2 >= 0x7FFF0000ull)
             return RTN_ERR_SHAPE;                               // 32-bit buffer offsets
         if (p.split_k > 1) {
@@ -325,6 +326,43 @@ rtn_status rtn_dequantize(const void* dev_qweight, const void* dev_scales, int64
     hipError_t e = rtn::launch_unpack(dev_qweight, dev_scales, N, K, bits, g, true, dev_W_fp16,
                                       static_cast<hipStream_t>(stream));
     return e == hipSuccess ? RTN_OK : RTN_ERR_HIP;
+}
+
+// Split-K of the dense GEMM: only as far as needed to give every compute unit a workgroup, within the workspace.
+static int dense_split(int64_t M, int64_t N, int64_t K, size_t workspace_nbytes) {
+    const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
+    int split = 1;
+    while (tiles * split < 256 && split * 2 <= kMaxSplitK && K / 128 / (split * 2) >= 8 &&
+           (size_t)M * N * sizeof(float) * (split * 2) <= workspace_nbytes)
+        split *= 2;
+    return split;
+}
+
+rtn_status rtn_gemm_fp16(const void* dev_A, int64_t M, const void* dev_W_fp16, int64_t N, int64_t K, void* dev_C,
+                         void* dev_workspace, size_t workspace_nbytes, void* stream) {
+    if (!dev_A || !dev_W_fp16 || !dev_C) return RTN_ERR_NULL;
+    if (M <= 0 || M > (1 << 20) || N <= 0 || N % 16 != 0 || K <= 0 || K % 128 != 0) return RTN_ERR_SHAPE;
+    if ((uint64_t)K * 2 * 128 >= 0x7FFF0000ull) return RTN_ERR_SHAPE;          // one 128-row slab per buffer resource
+    if (!aligned16(dev_A) || !aligned16(dev_W_fp16) || !aligned16(dev_C) || !aligned16(dev_workspace)) return RTN_ERR_ALIGN;
+    const int split = dev_workspace ? dense_split(M, N, K, workspace_nbytes) : 1;
+    hipError_t e = rtn::launch_gemm_fp16(dev_A, dev_W_fp16, dev_C, static_cast<float*>(dev_workspace), M, N, K, split,
+                                         static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RTN_OK : RTN_ERR_HIP;
+}
+
+size_t rtn_dense_weight_nbytes(int64_t N, int64_t K) {
+    if (N <= 0 || K <= 0) return 0;
+    return (size_t)N * (size_t)K * 2;
+}
+
+rtn_status rtn_linear_dense(const void* dev_A, int64_t M, const void* dev_qweight, const void* dev_scales,
+                            int64_t N, int64_t K, int bits, int group_size, void* dev_C, void* dev_W_tmp,
+                            size_t w_tmp_nbytes, void* dev_workspace, size_t workspace_nbytes, void* stream) {
+    if (!dev_W_tmp) return RTN_ERR_NULL;
+    if (w_tmp_nbytes < rtn_dense_weight_nbytes(N, K)) return RTN_ERR_WORKSPACE;
+    rtn_status st = rtn_dequantize(dev_qweight, dev_scales, N, K, bits, group_size, dev_W_tmp, stream);
+    if (st != RTN_OK) return st;
+    return rtn_gemm_fp16(dev_A, M, dev_W_tmp, N, K, dev_C, dev_workspace, workspace_nbytes, stream);
 }
 
 rtn_status rtn_layer_forward(const rtn_module* mods, int n_mods, void* dev_workspace, size_t workspace_nbytes,

@@ -469,6 +469,7 @@ static hipError_t launch_skinny(const SkinnyParams& sp, int ngc, int nb, bool mu
 
 hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t st) {
     if (p.path == 3) return launch_linear_wide(a, p, st);
+    if (p.path == 4) return launch_linear_tile(a, p, st);
     const int tk = (a.bits == 4) ? 128 : 64;
     const int ck = kChunkTiles * tk;
     SkinnyParams sp;

@@ -122,7 +122,7 @@ __global__ __launch_bounds__(kWideThreads, 2) void wide_mfma_kernel(const WidePa
     auto w_load = [&](int slot, int t) {
         const bool in = t < T;
         const uint32_t ks = (uint32_t)(ks0 + t);
-        const uint32_t j = p.spg_inv == 0 ? ks : __umulhi(ks, p.spg_inv);
+        const uint32_t j = (G1 || p.spg_inv == 0) ? ks : __umulhi(ks, p.spg_inv);
 #pragma unroll
         for (int r = 0; r < NBW; ++r) {
             const bool ok = in && nt_ok[r];
@@ -160,8 +160,10 @@ __global__ __launch_bounds__(kWideThreads, 2) void wide_mfma_kernel(const WidePa
         a_store((t + 1) & 1);                             // A(t+1), loaded during the previous step
         a_load(t + 2);
         w_load((slot + 2) % 3, t + 2);
+        __builtin_amdgcn_sched_barrier(0);                // keep the prefetch ahead of this step's arithmetic
         const uint8_t* abase = lds_a + (t & 1) * BUF_BYTES + (nl * 16) * 16;
-        const bool ends = (--left == 0) || (t == T - 1);  // the group, or this workgroup's share of it, ends
+        // the group, or this workgroup's share of it, ends with this step
+        const bool ends = G1 ? true : ((--left == 0) || (t == T - 1));
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             half8_t a[MB];
@@ -186,18 +188,24 @@ __global__ __launch_bounds__(kWideThreads, 2) void wide_mfma_kernel(const WidePa
         __syncthreads();
     };
 
-    // ---- prologue ----
+    // ---- prologue: the same issue order as in the loop (activations of a step before its weights), so that
+    // the loop's waits are counted waits and not waits for everything ----
     a_load(0);
     w_load(0, 0);
-    w_load(1, 1);
     a_store(0);
     a_load(1);
+    w_load(1, 1);
     __syncthreads();
 
-    for (int t = 0; t < T; t += 3) {
+    int t = 0;
+    for (; t + 3 <= T; t += 3) {          // no control flow between steps: every wait inside is an exact count
+        step(0, t);
+        step(1, t + 1);
+        step(2, t + 2);
+    }
+    if (t < T) {
         step(0, t);
         if (t + 1 < T) step(1, t + 1);
-        if (t + 2 < T) step(2, t + 2);
     }
 
     // ---- store: lane holds rows m = 16 b + 4 kq + e, column n = 16 (nt0 + r) + nl ----

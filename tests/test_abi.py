@@ -19,7 +19,7 @@ FAKE = 0x1000   # a 16-byte aligned non-null "device pointer"; never dereference
 def test_every_declared_symbol_is_exported():
     text = open(os.path.join(ROOT, "include", "rtn.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(rtn_[a-z_]+)\s*\(", text))
+    declared = set(re.findall(r"\b(rtn_[a-z0-9_]+)\s*\(", text))
     assert declared == set(rtn.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
@@ -66,8 +66,17 @@ def test_argument_validation_happens_before_any_launch():
     assert _linear(cfg=C.byref(cfg)) == 7                         # wavefront counts are powers of two
     cfg = rtn.rtn_linear_cfg(waves_n=8, waves_k=4)
     assert _linear(cfg=C.byref(cfg)) == 7                         # at most 16 wavefronts per workgroup
-    cfg = rtn.rtn_linear_cfg(path=4)
+    cfg = rtn.rtn_linear_cfg(path=5)
     assert _linear(cfg=C.byref(cfg)) == 7
+    cfg = rtn.rtn_linear_cfg(path=4, split_k=9)
+    assert _linear(M=200, cfg=C.byref(cfg)) == 7                  # more splits than 128-column k-steps
+    cfg = rtn.rtn_linear_cfg(path=4)
+    assert _linear(M=200, bits=8, g=64, cfg=C.byref(cfg)) == 7    # group 64 is below the tile kernel's k-step
+    assert lib.rtn_gemm_fp16(None, 1, FAKE, 16, 128, FAKE, None, 0, None) == 1
+    assert lib.rtn_gemm_fp16(FAKE, 1, FAKE, 16, 100, FAKE, None, 0, None) == 4
+    assert lib.rtn_gemm_fp16(FAKE, 1, FAKE + 2, 16, 128, FAKE, None, 0, None) == 5
+    assert lib.rtn_linear_dense(FAKE, 1, FAKE, FAKE, 64, 512, 4, 128, FAKE, FAKE, 100, None, 0, None) == 6
+    assert rtn.rtn_dense_weight_nbytes(64, 512) == 64 * 512 * 2
     for bad in (dict(m_rows16=1), dict(m_rows16=5), dict(m_rows16=2, n_tiles16=3), dict(m_rows16=4, n_tiles16=4),
                 dict(m_rows16=2, n_tiles16=1, split_k=1000)):
         cfg = rtn.rtn_linear_cfg(path=3, **bad)                    # the wide kernel's register-tile limits

@@ -228,6 +228,50 @@ def test_linear_wide_kernel(rtn, bits, g, M):
             rtn.rtn_linear(A_t, qw64, sc64, 8, 64, cfg=dict(path=3, m_rows16=2, n_tiles16=1))
 
 
+@pytest.mark.parametrize("bits,g", [(4, 128), (4, 256), (4, 0), (8, 128), (8, 0)])
+@pytest.mark.parametrize("M", [3, 64, 128, 130, 300])
+def test_linear_tile_kernel(rtn, bits, g, M):
+    """The 128 x 128 tile kernel (path 4): ragged M and N (a partly empty last tile in both directions), K split
+    across workgroups, weights dequantised to fp16 on the way into LDS."""
+    N, K = 400, 2560
+    codes, scales, qw, sc, gg = _oracle_operands(N, K, bits, g, seed=8)
+    A_t = synth.activation(M, K, seed=300 + M, device=DEV)
+    ref = O.rtn_linear(_to_np(A_t), codes, scales, gg)
+    for split in (1, 2, 5):
+        cfg = dict(path=4, split_k=split)
+        C = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=cfg)
+        torch.cuda.synchronize()
+        H.assert_linear_close(_to_np(C), ref, f"bits={bits} g={g} M={M} cfg={cfg}")
+    C2 = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=dict(path=4, split_k=5))
+    assert torch.equal(C, C2)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 16, 128), (128, 128, 128), (200, 400, 2560), (1030, 272, 1024)])
+def test_dense_gemm_and_dual_path(rtn, M, N, K):
+    """rtn_gemm_fp16 against an fp64 product of the same fp16 operands, and the dequantise-then-GEMM path of
+    Section 5 against the oracle's linear layer."""
+    W_t = synth.normal_weight(N, K, 0.02, seed=N + K, device=DEV)
+    A_t = synth.activation(M, K, seed=M, device=DEV)
+    ref = _to_np(A_t).astype(np.float64) @ _to_np(W_t).astype(np.float64).T
+    ws = torch.empty(16 << 20, dtype=torch.uint8, device=DEV)
+    for workspace in (None, ws):
+        C = rtn.rtn_gemm_fp16(A_t, W_t, workspace=workspace)
+        torch.cuda.synchronize()
+        H.assert_linear_close(_to_np(C), ref, f"dense M={M} N={N} K={K} ws={workspace is not None}")
+    if K % 512 == 0:
+        for bits, g in ((4, 128), (8, 0)):
+            codes, scales, qw, sc, gg = _oracle_operands(N, K, bits, g, seed=3)
+            want = O.rtn_linear(_to_np(A_t), codes, scales, gg)
+            tmp = torch.empty(rtn.rtn_dense_weight_nbytes(N, K), dtype=torch.uint8, device=DEV)
+            C = rtn.rtn_linear_dense(A_t, qw, sc, bits, g, tmp, workspace=ws)
+            torch.cuda.synchronize()
+            H.assert_linear_close(_to_np(C), want, f"dual path bits={bits} M={M}")
+            deq = O.rtn_dequantize(codes, scales, gg).astype(np.float16)
+            assert np.array_equal(_to_np(tmp).view(np.float16).reshape(N, K).view(np.uint16), deq.view(np.uint16))
+            with pytest.raises(rtn.RtnError):
+                rtn.rtn_linear_dense(A_t, qw, sc, bits, g, tmp[:-16], workspace=ws)
+
+
 @pytest.mark.parametrize("bits,g", [(4, 128), (8, 64), (8, 0)])
 def test_linear_special_cases(rtn, bits, g):
     N, K = 64, 1024
