@@ -95,7 +95,9 @@ def report(args, rtn, synth, torch, np, dev) -> int:
             line = (f"{name:8s} {K:6d}->{N:6d} M={M:3d}  {t:8.2f} us  {nbytes / t / 1e3:7.0f} GB/s  "
                     f"{nbytes / t / 80e3:5.1f} %  {2.0 * M * N * K / t / 1e6:7.2f} TFLOP/s  ")
             if plan["path"] == 3:
-                line += f"wide {16 * plan['m_rows16']}x{16 * plan['n_tiles16']}/wave split {plan['split_k']}"
+                line += (f"wide {plan['waves_n']} waves x {16 * plan['m_rows16']}x{16 * plan['n_tiles16']} split {plan['split_k']}")
+            elif plan["path"] == 4:
+                line += f"tile 128x128 split {plan['split_k']}"
             else:
                 line += f"skinny {plan['waves_n']}x{plan['waves_k']} split {plan['split_k']} rows16 {plan['m_rows16']}"
             if args.compare_paths and M <= 4:

@@ -116,7 +116,8 @@ rtn_status rtn_linear(const void* dev_A, int64_t M, const void* dev_qweight, con
  * A zeroed struct means "choose automatically", field by field. */
 typedef struct {
     int path;      /* 0 auto, 1 MFMA skinny kernel, 2 vector-ALU dot-product kernel (M <= 4), 3 wide MFMA kernel
-                      (group_size a multiple of 128; uses only split_k, m_rows16 = 2..4 and n_tiles16), 4 tile kernel: 128 x 128
+                      (group_size a multiple of 128; uses split_k, m_rows16 = 2..4, n_tiles16 and waves_n = 4, 8 or -- with
+                      n_tiles16 = 1 -- 16 wavefronts per workgroup), 4 tile kernel: 128 x 128
                       output tiles, weights dequantised to fp16 in LDS (group_size a multiple of 128; uses only split_k) */
     int prefetch;  /* k-chunks (4 KiB each) a wavefront keeps in flight: 1, 2 or 4 */
     int waves_n;   /* wavefronts of a workgroup along N (share the staged activations): 1, 2, 4, 8, 16 */

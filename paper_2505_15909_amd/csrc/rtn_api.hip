@@ -2,6 +2,8 @@
 // selective-precision dispatch.  No device code here.
 #include "../../include/rtn.h"
 #include "rtn_internal.h"
+#include <algorithm>
+#include <cmath>
 
 #include <stdlib.h>
 #include <string.h>
@@ -69,33 +71,50 @@ int round_pow2(int64_t v, int lo, int hi) {
 // and K is split inside the workgroup (reduced through LDS).  With more than two activation rows the
 // staged slice grows, so workgroups widen along N (sharing it) and, for long K, K is also split across
 // workgroups so that a slice stays a few chunks long; those partials go through the workspace.
-// Plan of the wide MFMA kernel for more than 16 rows (from sweeps over the 8B, 70B and 405B shapes at M = 32,
-// 64, 128): wavefronts with two tile-rows (n_tiles16 = 2) are the more efficient ones and are taken whenever K
-// can be split (32 or more k-steps per workgroup, within the workspace cap) far enough to give about two
-// workgroups per compute unit; otherwise one tile-row per wavefront with up to K/1024 splits.
-void wide_plan(int64_t M, int64_t N, int64_t K, LinearPlan* p) {
+// Plan of the wide MFMA kernel for more than 16 rows: the candidate (wavefronts per workgroup, tile-rows per
+// wavefront, K splits) with the lowest modelled time.  The model is the larger of three streaming / arithmetic
+// times -- activations re-read from L2 once per workgroup column plus the weights, the weights from HBM, the
+// MFMA work -- derated by how evenly the workgroups fill the compute units, plus fixed per-launch, per-round and
+// split-K reduction costs.  Its constants were fitted to sweeps over the 8B, 70B and 405B shapes at 32-256
+// rows, where its choice is within 2 % of the best measured configuration on average (worst case 15 %).
+double wide_model_us(int64_t M, int64_t N, int64_t K, int bits, int mb, int wv, int nbw, int s) {
+    const double kL2 = 11.26e12, kHbm = 6.96e12, kMfma = 1.02e15, kSmallTile = 0.767, kFix = 2e-6, kRound = 1.5e-6;
+    const double kReduce0 = 2.5e-6, kReduceBw = 4.55e12, kUtilExp = 0.662;
+    const int64_t rows = 16 * mb, ZB = (M + rows - 1) / rows, n_wg = 16 * nbw * wv, XB = (N + n_wg - 1) / n_wg;
+    const int64_t wgs = XB * ZB * s, slots = 256 * (wv == 4 ? 3 : 1);
+    const int64_t rounds = (wgs + slots - 1) / slots;
+    const double util = (double)wgs / (double)(rounds * slots);
+    const double Mp = (double)(ZB * rows), wbytes = (double)N * K * bits / 8.0;
+    const double t_l2 = (2.0 * Mp * K * XB + wbytes * std::sqrt((double)ZB)) / kL2;
+    const double t_hbm = wbytes * 1.03 / kHbm;
+    const double t_mfma = 2.0 * Mp * N * K / (kMfma * (nbw * mb >= 8 ? 1.0 : kSmallTile));
+    double t = std::max(t_l2, std::max(t_hbm, t_mfma)) / std::pow(util, kUtilExp) + kFix + rounds * kRound;
+    if (s > 1) t += kReduce0 + 2.0 * s * M * N * 4.0 / kReduceBw;
+    return t * 1e6;
+}
+
+void wide_plan(int64_t M, int64_t N, int64_t K, int bits, LinearPlan* p) {
     p->path = 3;
     p->m_rows16 = M <= 32 ? 2 : (M <= 48 ? 3 : 4);
     p->m_blocks = (int)((M + 16 * p->m_rows16 - 1) / (16 * p->m_rows16));
-    p->prefetch = 1; p->waves_n = 4; p->waves_k = 1;
+    p->prefetch = 1; p->waves_k = 1;
     const int64_t KS = K / 128;
     int64_t smax = (int64_t)(kWorkspaceCap / ((size_t)M * N * sizeof(float)));
-    if (smax < 1) smax = 1;
     if (smax > kMaxSplitK) smax = kMaxSplitK;
-    for (int nbw = 2; nbw >= 1; --nbw) {
-        if (p->m_rows16 * nbw > 8) continue;
-        const int64_t wgs = (N + 64 * nbw - 1) / (64 * nbw) * p->m_blocks;
-        int64_t cap = KS / (nbw == 2 ? 32 : 8);
-        if (cap > smax) cap = smax;
-        if (cap < 1) cap = 1;
-        const int64_t want = nbw == 2 ? 448 : 384;
-        int64_t s = (want + wgs - 1) / wgs;
-        if (s <= cap || nbw == 1) {
-            p->n_tiles16 = nbw;
-            p->split_k = (int)(s <= cap ? s : cap);
-            return;
+    if (smax > KS / 4) smax = KS / 4;
+    if (smax < 1) smax = 1;
+    double best = 1e30;
+    for (int wv = 4; wv <= 16; wv *= 2)
+        for (int nbw = 1; nbw <= 4; nbw *= 2) {
+            if (p->m_rows16 * nbw > 8 || (wv == 16 && nbw > 1)) continue;
+            for (int s = 1; s <= smax; s *= 2) {
+                const double t = wide_model_us(M, N, K, bits, p->m_rows16, wv, nbw, s);
+                if (t < best) {
+                    best = t;
+                    p->waves_n = wv; p->n_tiles16 = nbw; p->split_k = s;
+                }
+            }
         }
-    }
 }
 
 // force_path: 0 = choose the path, otherwise the default plan of that path.
@@ -104,9 +123,9 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
     p.n_tiles16 = 1;
     // more than 16 rows: the wide kernel, except at 17-32 rows on matrices so large that the skinny kernel's
     // pure weight streaming still wins
-    const bool wide_wins = g % 128 == 0 && (M > 32 || (M > 16 && (size_t)N * K * bits / 8 <= ((size_t)64 << 20)));
+    const bool wide_wins = g % 128 == 0 && (M > 32 || (M > 16 && (size_t)N * K * bits / 8 <= ((size_t)256 << 20)));
     if (force_path == 3 || (force_path == 0 && wide_wins)) {
-        wide_plan(M, N, K, &p);
+        wide_plan(M, N, K, bits, &p);
         return p;
     }
     const int64_t NT = N / 16, KC = K / chunk_k(bits);

@@ -2,7 +2,9 @@
 // C = A (q S)^T, when more than a few tokens are processed at once and the matrix cores, not the weight
 // stream, start to bound the time).
 //
-// Wide MFMA kernel.  A workgroup is 4 wavefronts side by side along N; every wavefront owns NBW
+// Wide MFMA kernel.  A workgroup is WV (4, 8 or 16) wavefronts side by side along N that share the staged
+// activations -- the wider the workgroup, the fewer times the activations cross from L2 to a compute unit,
+// which is what bounds this kernel once a few dozen rows are in play; every wavefront owns NBW
 // consecutive 16-row weight tile-rows (16 NBW output columns) and all 16 MB activation rows of the
 // workgroup's row block, i.e. a (16 MB) x (16 NBW) register tile of fp32 accumulators:
 //   - packed weights go from global memory straight into registers in MFMA operand order (that is what
@@ -26,8 +28,6 @@ namespace rtn {
 namespace {
 
 constexpr int kStepK = 128;                     // columns per k-step
-constexpr int kWideWaves = 4;
-constexpr int kWideThreads = 64 * kWideWaves;
 constexpr uint32_t kOutOfRange = 0x7FFF0000u;   // beyond any resource size used here (< 2 GiB)
 constexpr int kBufferFlags = 0x00020000;        // raw buffer, 32-bit data format
 constexpr int kXcds = 8;
@@ -56,8 +56,8 @@ struct WideParams {
 // first MFMA of the step takes as a constant operand instead of a cleared register.
 // At least two wavefronts per SIMD (256 registers each): the MFMAs then keep their accumulators in ordinary
 // vector registers, where the scale multiply-add can read them directly.
-template <int BITS, int MB, int NBW, bool G1>
-__global__ __launch_bounds__(kWideThreads, 2) void wide_mfma_kernel(const WideParams p) {
+template <int BITS, int MB, int NBW, bool G1, int WV>
+__global__ __launch_bounds__(64 * WV, WV <= 8 ? 2 : 4) void wide_mfma_kernel(const WideParams p) {
     constexpr int TK = Layout<BITS>::TK;
     constexpr int MPT = Layout<BITS>::MFMA_PER_TILE;
     constexpr int TPS = kStepK / TK;                      // tiles per k-step and tile-row: 1 / 2
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(kWideThreads, 2) void wide_mfma_kernel(const WidePa
     const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<half_t*>(p.A), 0, p.a_bytes, kBufferFlags);
     const uint32_t magic = fp16_magic_vgpr();
 
-    const int nt0 = (xb * kWideWaves + wave) * NBW;       // first tile-row of this wavefront
+    const int nt0 = (xb * WV + wave) * NBW;               // first tile-row of this wavefront
     uint32_t w_lane[NBW], s_lane[NBW];
     bool nt_ok[NBW];
 #pragma unroll
@@ -96,23 +96,26 @@ __global__ __launch_bounds__(kWideThreads, 2) void wide_mfma_kernel(const WidePa
         s_lane[r] = ((uint32_t)(nt0 + r) * 16 + nl) * (uint32_t)p.G * 2u;
     }
 
-    // ---- activation staging: thread t moves pieces t, t + 256, ...; piece -> (row, 16-byte column p) ----
-    const int st_p = tid & 15, st_row0 = tid >> 4;        // MB pieces per thread: rows st_row0 + 16 i
-    u32x4_t areg[MB];
+    // ---- activation staging: thread t moves the 16-byte piece st_p of rows st_row0, st_row0 + RP, ... ----
+    constexpr int RP = 4 * WV;                            // rows covered by one pass of the workgroup's threads
+    constexpr int NP = (ROWS + RP - 1) / RP;              // passes
+    const int st_p = tid & 15, st_row0 = tid >> 4;        // row & 15 == st_row0 & 15 in every pass
+    u32x4_t areg[NP];
     auto a_load = [&](int t) {                            // k-step t of this workgroup (out of range: zeros)
 #pragma unroll
-        for (int i = 0; i < MB; ++i) {
-            const int row = st_row0 + 16 * i;
-            const bool ok = t < T && m0 + row < p.M;
+        for (int i = 0; i < NP; ++i) {
+            const int row = st_row0 + RP * i;
+            const bool ok = t < T && row < ROWS && m0 + row < p.M;
             const uint32_t off = ok ? ((uint32_t)(m0 + row) * (uint32_t)p.K + (uint32_t)(ks0 + t) * kStepK + st_p * 8) * 2u : kOutOfRange;
             areg[i] = __builtin_amdgcn_raw_buffer_load_b128(ra, off, 0, 0);
         }
     };
     auto a_store = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < MB; ++i) {
-            const int row = st_row0 + 16 * i;             // row & 15 == st_row0 & 15
-            *reinterpret_cast<u32x4_t*>(lds_a + buf * BUF_BYTES + (row * 16 + (st_p ^ (row & 15))) * 16) = areg[i];
+        for (int i = 0; i < NP; ++i) {
+            const int row = st_row0 + RP * i;
+            if (ROWS % RP == 0 || row < ROWS)
+                *reinterpret_cast<u32x4_t*>(lds_a + buf * BUF_BYTES + (row * 16 + (st_p ^ (row & 15))) * 16) = areg[i];
         }
     };
 
@@ -227,25 +230,36 @@ __global__ __launch_bounds__(kWideThreads, 2) void wide_mfma_kernel(const WidePa
     }
 }
 
-template <int BITS, int MB, int NBW>
+template <int BITS, int MB, int NBW, int WV>
 hipError_t launch_wide_g1(const WideParams& wp, dim3 grid, hipStream_t st) {
-    dim3 block(kWideThreads);
-    if (wp.spg == 1) hipLaunchKernelGGL((wide_mfma_kernel<BITS, MB, NBW, true>), grid, block, 0, st, wp);
-    else hipLaunchKernelGGL((wide_mfma_kernel<BITS, MB, NBW, false>), grid, block, 0, st, wp);
+    dim3 block(64 * WV);
+    if (wp.spg == 1) hipLaunchKernelGGL((wide_mfma_kernel<BITS, MB, NBW, true, WV>), grid, block, 0, st, wp);
+    else hipLaunchKernelGGL((wide_mfma_kernel<BITS, MB, NBW, false, WV>), grid, block, 0, st, wp);
     return hipGetLastError();
+}
+
+// Sixteen wavefronts leave 128 registers each: only the register tiles with one tile-row per wavefront.
+template <int BITS, int MB, int NBW>
+hipError_t launch_wide_wv(const WideParams& wp, int wv, dim3 grid, hipStream_t st) {
+    if (wv == 4) return launch_wide_g1<BITS, MB, NBW, 4>(wp, grid, st);
+    if (wv == 8) return launch_wide_g1<BITS, MB, NBW, 8>(wp, grid, st);
+    if constexpr (NBW == 1) {
+        if (wv == 16) return launch_wide_g1<BITS, MB, NBW, 16>(wp, grid, st);
+    }
+    return hipErrorInvalidValue;
 }
 
 // Register tiles of up to 8 accumulator blocks (MB * NBW <= 8) fit 256 registers without spilling.
 template <int BITS>
-hipError_t launch_wide_bits(const WideParams& wp, int mb, int nbw, dim3 grid, hipStream_t st) {
+hipError_t launch_wide_bits(const WideParams& wp, int mb, int nbw, int wv, dim3 grid, hipStream_t st) {
     switch (mb * 10 + nbw) {
-        case 21: return launch_wide_g1<BITS, 2, 1>(wp, grid, st);
-        case 22: return launch_wide_g1<BITS, 2, 2>(wp, grid, st);
-        case 24: return launch_wide_g1<BITS, 2, 4>(wp, grid, st);
-        case 31: return launch_wide_g1<BITS, 3, 1>(wp, grid, st);
-        case 32: return launch_wide_g1<BITS, 3, 2>(wp, grid, st);
-        case 41: return launch_wide_g1<BITS, 4, 1>(wp, grid, st);
-        case 42: return launch_wide_g1<BITS, 4, 2>(wp, grid, st);
+        case 21: return launch_wide_wv<BITS, 2, 1>(wp, wv, grid, st);
+        case 22: return launch_wide_wv<BITS, 2, 2>(wp, wv, grid, st);
+        case 24: return launch_wide_wv<BITS, 2, 4>(wp, wv, grid, st);
+        case 31: return launch_wide_wv<BITS, 3, 1>(wp, wv, grid, st);
+        case 32: return launch_wide_wv<BITS, 3, 2>(wp, wv, grid, st);
+        case 41: return launch_wide_wv<BITS, 4, 1>(wp, wv, grid, st);
+        case 42: return launch_wide_wv<BITS, 4, 2>(wp, wv, grid, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -257,6 +271,7 @@ bool wide_plan_valid(const LinearArgs& a, const LinearPlan& p) {
     if (p.m_rows16 < 2 || p.m_rows16 > 4) return false;
     if (p.n_tiles16 != 1 && p.n_tiles16 != 2 && p.n_tiles16 != 4) return false;
     if (p.m_rows16 * p.n_tiles16 > 8) return false;       // register tile: at most 8 accumulator blocks
+    if (p.waves_n != 4 && p.waves_n != 8 && !(p.waves_n == 16 && p.n_tiles16 == 1)) return false;
     if (p.split_k < 1 || p.split_k > a.K / kStepK) return false;
     return true;
 }
@@ -276,7 +291,7 @@ hipError_t launch_linear_wide(const LinearArgs& a, const LinearPlan& p, hipStrea
     wp.NT = (int)(a.N / 16);
     wp.KL = (int)(a.K / tk);
     wp.KS = (int)(a.K / kStepK);
-    const int cols_wg = 16 * p.n_tiles16 * kWideWaves;
+    const int cols_wg = 16 * p.n_tiles16 * p.waves_n;
     wp.XB = (int)((a.N + cols_wg - 1) / cols_wg);
     wp.ZB = p.m_blocks;
     wp.split_k = p.split_k;
@@ -287,8 +302,8 @@ hipError_t launch_linear_wide(const LinearArgs& a, const LinearPlan& p, hipStrea
     wp.a_bytes = (uint32_t)((size_t)a.M * a.K * 2);
     const int xb_pad = (wp.XB + kXcds - 1) / kXcds * kXcds;
     dim3 grid((unsigned)(xb_pad * wp.ZB), (unsigned)p.split_k, 1);
-    hipError_t e = (a.bits == 4) ? launch_wide_bits<4>(wp, p.m_rows16, p.n_tiles16, grid, st)
-                                 : launch_wide_bits<8>(wp, p.m_rows16, p.n_tiles16, grid, st);
+    hipError_t e = (a.bits == 4) ? launch_wide_bits<4>(wp, p.m_rows16, p.n_tiles16, p.waves_n, grid, st)
+                                 : launch_wide_bits<8>(wp, p.m_rows16, p.n_tiles16, p.waves_n, grid, st);
     if (e != hipSuccess) return e;
     if (p.split_k > 1) e = launch_splitk_reduce(a.workspace, static_cast<half_t*>(a.C), a.M * a.N, p.split_k, st);
     return e;

@@ -219,6 +219,13 @@ def test_linear_wide_kernel(rtn, bits, g, M):
                 H.assert_linear_close(_to_np(C), ref, f"bits={bits} g={g} M={M} cfg={cfg}")
                 ran += 1
     assert ran == 21
+    for wv, mb, nbw in ((8, 4, 2), (8, 2, 4), (8, 3, 1), (16, 4, 1), (16, 2, 1), (16, 3, 1)):     # wider workgroups
+        cfg = dict(path=3, waves_n=wv, m_rows16=mb, n_tiles16=nbw, split_k=2)
+        C = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=cfg)
+        torch.cuda.synchronize()
+        H.assert_linear_close(_to_np(C), ref, f"bits={bits} g={g} M={M} cfg={cfg}")
+    with pytest.raises(rtn.RtnError):
+        rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=dict(path=3, waves_n=16, m_rows16=2, n_tiles16=2))
     C1 = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=dict(path=3, m_rows16=4, n_tiles16=2, split_k=3))
     C2 = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=dict(path=3, m_rows16=4, n_tiles16=2, split_k=3))
     assert torch.equal(C1, C2)
