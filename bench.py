@@ -34,33 +34,42 @@ BATCHES = (1, 2, 4, 8, 16)
 BITS, GROUP = 4, 128
 CACHE_BYTES = 256e6
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# very command, scaled by a copy kernel of known size (FETCH_SIZE x 1.998, WRITE_SIZE x 1.000).
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 29068733   # profiles/skinny_mfma_llama8b_w4a16_hbm_traffic.txt
+# very command, scaled by a copy kernel of known size (FETCH_SIZE x 1.997, WRITE_SIZE x 1.000).
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 29045465   # profiles/skinny_mfma_llama8b_w4a16_hbm_traffic.txt
 
 
-def _time_linear(rtn, torch, np, A, qws, sc, bits, g, cfg, ws, reps=3):
-    """Microseconds per rtn_linear launch: HIP-graph replay of launches that rotate over distinct weight copies."""
+def _time_linear(rtn, torch, np, A, qws, sc, bits, g, cfg, ws, reps=3, graph=True):
+    """Microseconds per rtn_linear launch: launches rotate over distinct weight copies, replayed as a HIP graph
+    (or issued directly, graph=False: for counter collection)."""
     M, K = A.shape
     N = sc.shape[0]
     out = torch.empty((M, N), dtype=torch.float16, device=A.device)
     for q in qws[:2]:
         rtn.rtn_linear(A, q, sc, bits, g, out=out, workspace=ws, cfg=cfg)
     torch.cuda.synchronize()
-    graph = torch.cuda.CUDAGraph()
-    st = torch.cuda.Stream()
-    with torch.cuda.stream(st):
-        with torch.cuda.graph(graph, stream=st):
-            for _ in range(reps):
-                for q in qws:
-                    rtn.rtn_linear(A, q, sc, bits, g, out=out, workspace=ws, cfg=cfg)
+
+    def issue():
+        for _ in range(reps):
+            for q in qws:
+                rtn.rtn_linear(A, q, sc, bits, g, out=out, workspace=ws, cfg=cfg)
+
+    if graph:
+        cg = torch.cuda.CUDAGraph()
+        st = torch.cuda.Stream()
+        with torch.cuda.stream(st):
+            with torch.cuda.graph(cg, stream=st):
+                issue()
+        run = cg.replay
+    else:
+        run = issue
     n = reps * len(qws)
-    graph.replay()
+    run()
     torch.cuda.synchronize()
     ts = []
-    for _ in range(5):
+    for _ in range(5 if graph else 1):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        graph.replay()
+        run()
         e1.record()
         torch.cuda.synchronize()
         ts.append(e0.elapsed_time(e1) * 1e3 / n)
@@ -89,7 +98,7 @@ def report(args, rtn, synth, torch, np, dev) -> int:
         qws = [qw] + [qw.clone() for _ in range(L - 1)]
         for M in Ms:
             A = synth.activation(M, K, 100 + M, dev)
-            t = _time_linear(rtn, torch, np, A, qws, sc, bits, g, None, ws)
+            t = _time_linear(rtn, torch, np, A, qws, sc, bits, g, None, ws, graph=not args.no_graph)
             tot[M] += t
             plan = rtn.rtn_linear_query(M, N, K, bits, g)
             line = (f"{name:8s} {K:6d}->{N:6d} M={M:3d}  {t:8.2f} us  {nbytes / t / 1e3:7.0f} GB/s  "
@@ -113,6 +122,78 @@ def report(args, rtn, synth, torch, np, dev) -> int:
     return 0
 
 
+def report_quantize(args, rtn, synth, torch, np, dev) -> int:
+    """rtn_quantize throughput per matrix: bytes = fp16 read + packed codes and scales written."""
+    shapes = {"8b": synth.LLAMA_8B, "70b": synth.LLAMA_70B, "405b": synth.LLAMA_405B}[args.report_quantize]
+    print(f"# rtn_quantize on {args.report_quantize} shapes; bytes = 2 B read + packed codes + scales written per weight; "
+          f"HIP events around 10 back-to-back calls")
+    for bits, g in ((4, 128), (4, 0), (8, 128), (8, 0)):
+        for idx, (name, (K, N)) in enumerate(shapes.items()):
+            W = synth.normal_weight(N, K, 0.02, idx, dev)
+            q, s = rtn.rtn_quantize(W, bits, g)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ts = []
+            for _ in range(3):
+                e0.record()
+                for _ in range(10):
+                    rtn.rtn_quantize(W, bits, g, out=(q, s))
+                e1.record()
+                torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1) * 1e2)
+            t = float(np.median(ts))
+            nbytes = W.numel() * 2 + q.numel() + s.numel() * 2
+            print(f"int{bits} {'g=128' if g else 'per-channel':11s} {name:8s} {K:6d}->{N:6d}  {t:8.1f} us  {nbytes / t / 1e3:6.0f} GB/s  "
+                  f"{nbytes / t / 80e3:5.1f} % of 8 TB/s", flush=True)
+            del W, q, s
+    return 0
+
+
+def report_crossover(args, rtn, synth, torch, np, dev) -> int:
+    """Fused kernels against dequantise + dense GEMM (the dual path of Section 5) over M, on one model's shapes."""
+    shapes = {"8b": synth.LLAMA_8B, "70b": synth.LLAMA_70B, "405b": synth.LLAMA_405B}[args.report_crossover]
+    bits = args.bits
+    g = 128 if bits == 4 else 0
+    Ms = [int(x) for x in args.batches.split(",")]
+    ws = torch.empty(16 << 20, dtype=torch.uint8, device=dev)
+    print(f"# {args.report_crossover} shapes, int{bits}; us per call (HIP events, 6 back-to-back calls, best of 3; one weight copy, "
+          f"so matrices under 256 MB are cache-resident): fused = rtn_linear; dual = rtn_linear_dense (dequantise to fp16 + "
+          f"own dense GEMM); gemm = the dense GEMM alone on already dequantised weights")
+
+    def timeit(fn, n=6):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ts = []
+        for _ in range(3):
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e3 / n)
+        return min(ts)
+
+    for idx, (name, (K, N)) in enumerate(shapes.items()):
+        W = synth.normal_weight(N, K, 0.02, idx, dev)
+        qw, sc = rtn.rtn_quantize(W, bits, g)
+        del W
+        tmp = torch.empty(rtn.rtn_dense_weight_nbytes(N, K), dtype=torch.uint8, device=dev)
+        Wd = tmp.view(torch.float16).view(N, K)
+        for M in Ms:
+            A = synth.activation(M, K, 100 + M, dev)
+            out = torch.empty((M, N), dtype=torch.float16, device=dev)
+            fl = 2.0 * M * N * K
+            tf = timeit(lambda: rtn.rtn_linear(A, qw, sc, bits, g, out=out, workspace=ws))
+            td = timeit(lambda: rtn.rtn_linear_dense(A, qw, sc, bits, g, tmp, out=out, workspace=ws))
+            tg = timeit(lambda: rtn.rtn_gemm_fp16(A, Wd, out=out, workspace=ws))
+            path = rtn.rtn_linear_query(M, N, K, bits, g)["path"]
+            print(f"{name:8s} {K:6d}->{N:6d} M={M:5d}  fused(path {path}) {tf:9.1f} us {fl / tf / 1e6:6.0f} TFLOP/s | dual {td:9.1f} us "
+                  f"{fl / td / 1e6:6.0f} TFLOP/s | gemm {tg:9.1f} us {fl / tg / 1e6:6.0f} TFLOP/s | fused/dual {tf / td:5.2f}", flush=True)
+        del qw, tmp, Wd
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -122,6 +203,10 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--report", choices=["8b", "70b", "405b"], default=None,
                     help="instead of the JSON line, print a per-matrix, per-M table for that model's shapes")
+    ap.add_argument("--report-quantize", choices=["8b", "70b", "405b"], default=None,
+                    help="instead of the JSON line, print rtn_quantize throughput per matrix and (bits, group) setting")
+    ap.add_argument("--report-crossover", choices=["8b", "70b", "405b"], default=None,
+                    help="instead of the JSON line, print fused kernels vs dequantise + dense GEMM over --batches")
     ap.add_argument("--bits", type=int, default=4, help="--report only: 4 (group 128) or 8 (per-channel)")
     ap.add_argument("--batches", type=str, default="1,2,4,8,16", help="--report only")
     ap.add_argument("--compare-paths", action="store_true",
@@ -141,6 +226,10 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.report:
         return report(args, rtn, synth, torch, np, dev)
+    if args.report_quantize:
+        return report_quantize(args, rtn, synth, torch, np, dev)
+    if args.report_crossover:
+        return report_crossover(args, rtn, synth, torch, np, dev)
     modules = list(synth.LLAMA_8B.items())
 
     # ---- set-up: synthetic fp16 weights, load-time quantise (timed separately) ---------------

@@ -137,10 +137,15 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
     p.m_blocks = (int)((M + mrows - 1) / mrows);
     p.prefetch = 1;
     p.split_k = 1;
-    if (rows <= 2 || (rows == 3 && KC > 16)) {
+    if (rows <= 2 || (rows == 3 && KC >= 16)) {
         const int64_t per_wave = steps <= 6144 ? 1 : (steps <= 24576 ? 2 : 4);
-        p.waves_k = round_pow2((KC + per_wave - 1) / per_wave, 1, 16);
-        while (p.waves_k > KC) p.waves_k /= 2;
+        const int64_t even = (KC + per_wave - 1) / per_wave;   // wavefronts that each get exactly per_wave chunks
+        if (even <= 16 && KC % even == 0) {
+            p.waves_k = (int)even;                             // e.g. K = 14336: 28 chunks = 14 wavefronts x 2
+        } else {
+            p.waves_k = round_pow2(even, 1, 16);
+            while (p.waves_k > KC) p.waves_k /= 2;
+        }
         p.waves_n = (steps > 24576 && p.waves_k < 8) ? 8 / p.waves_k : 1;    // eight wavefronts only for the largest
     } else if (steps <= 6144) {
         p.waves_k = round_pow2(KC, 1, 8);
@@ -213,7 +218,7 @@ rtn_status resolve_plan(const LinearArgs& a, const rtn_linear_cfg* cfg, size_t w
     if (p.prefetch != 1 && p.prefetch != 2 && p.prefetch != 4) return RTN_ERR_CONFIG;
     if (p.m_rows16 != 1 && p.m_rows16 != 2 && p.m_rows16 != 4) return RTN_ERR_CONFIG;
     if (p.m_rows16 > 1 && p.prefetch != 1) return RTN_ERR_CONFIG;
-    if (!pow2(p.waves_n) || !pow2(p.waves_k) || p.waves_n * p.waves_k > 16) return RTN_ERR_CONFIG;
+    if (!pow2(p.waves_n) || p.waves_k < 1 || p.waves_n * p.waves_k > 16) return RTN_ERR_CONFIG;
     if (p.split_k < 1 || p.split_k > kMaxSplitK || p.split_k > KC) return RTN_ERR_CONFIG;
     if (!rtn::linear_plan_fits(a, p, lds_limit)) return RTN_ERR_CONFIG;
     if ((uint64_t)a.N * a.K * a.bits / 8 >= 0x7FFF0000ull || (uint64_t)a.M * a.K * 2 >= 0x7FFF0000ull)

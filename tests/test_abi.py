@@ -63,7 +63,7 @@ def test_argument_validation_happens_before_any_launch():
     cfg = rtn.rtn_linear_cfg(path=1, prefetch=3)
     assert _linear(cfg=C.byref(cfg)) == 7
     cfg = rtn.rtn_linear_cfg(waves_n=3)
-    assert _linear(cfg=C.byref(cfg)) == 7                         # wavefront counts are powers of two
+    assert _linear(cfg=C.byref(cfg)) == 7                         # wavefronts along N: a power of two
     cfg = rtn.rtn_linear_cfg(waves_n=8, waves_k=4)
     assert _linear(cfg=C.byref(cfg)) == 7                         # at most 16 wavefronts per workgroup
     cfg = rtn.rtn_linear_cfg(path=5)
