@@ -106,7 +106,7 @@ def report(args, rtn, synth, torch, np, dev) -> int:
             if plan["path"] == 3:
                 line += (f"wide {plan['waves_n']} waves x {16 * plan['m_rows16']}x{16 * plan['n_tiles16']} split {plan['split_k']}")
             elif plan["path"] == 4:
-                line += f"tile 128x128 split {plan['split_k']}"
+                line += f"tile kernel (128 or 256 rows x 256 columns per workgroup) split {plan['split_k']}"
             else:
                 line += f"skinny {plan['waves_n']}x{plan['waves_k']} split {plan['split_k']} rows16 {plan['m_rows16']}"
             if args.compare_paths and M <= 4:

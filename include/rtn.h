@@ -117,8 +117,9 @@ rtn_status rtn_linear(const void* dev_A, int64_t M, const void* dev_qweight, con
 typedef struct {
     int path;      /* 0 auto, 1 MFMA skinny kernel, 2 vector-ALU dot-product kernel (M <= 4), 3 wide MFMA kernel
                       (group_size a multiple of 128; uses split_k, m_rows16 = 2..4, n_tiles16 and waves_n = 4, 8 or -- with
-                      n_tiles16 = 1 -- 16 wavefronts per workgroup), 4 tile kernel: 128 x 128
-                      output tiles, weights dequantised to fp16 in LDS (group_size a multiple of 128; uses only split_k) */
+                      n_tiles16 = 1 -- 16 wavefronts per workgroup), 4 tile kernel: 128 x 256 or
+                      256 x 256 output tiles, weights dequantised to fp16 in LDS (group_size a multiple of 128; uses split_k and
+                      m_rows16 = 4 or 8 for the tile height, 0 = chosen from M) */
     int prefetch;  /* k-chunks (4 KiB each) a wavefront keeps in flight: 1, 2 or 4 */
     int waves_n;   /* wavefronts of a workgroup along N (share the staged activations): 1, 2, 4, 8, 16 (a power of two) */
     int waves_k;   /* wavefronts of a workgroup along K (in-workgroup split-K): 1 .. 16; waves_n * waves_k <= 16 */

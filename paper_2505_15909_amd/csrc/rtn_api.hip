@@ -124,6 +124,16 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
     // more than 16 rows: the wide kernel, except at 17-32 rows on matrices so large that the skinny kernel's
     // pure weight streaming still wins
     const bool wide_wins = g % 128 == 0 && (M > 32 || (M > 16 && (size_t)N * K * bits / 8 <= ((size_t)256 << 20)));
+    // a hundred rows and more, and at least one 128 x 256 output tile per compute unit without splitting K: the
+    // tile kernel (measured against the wide kernel on the 8B and 405B shapes at M = 128 ... 4096)
+    const bool tile_wins = g % 128 == 0 && M >= 128 && ((N + 255) / 256) * ((M + 127) / 128) >= 256;
+    if (force_path == 4 || (force_path == 0 && tile_wins)) {
+        p.path = 4;
+        p.prefetch = 1; p.waves_n = 8; p.waves_k = 1; p.split_k = 1;
+        p.m_rows16 = 0;                                        // tile height: chosen at launch
+        p.m_blocks = (int)((M + 127) / 128);
+        return p;
+    }
     if (force_path == 3 || (force_path == 0 && wide_wins)) {
         wide_plan(M, N, K, bits, &p);
         return p;
@@ -199,7 +209,9 @@ rtn_status resolve_plan(const LinearArgs& a, const rtn_linear_cfg* cfg, size_t w
             p.m_blocks = (int)((a.M + 16 * p.m_rows16 - 1) / (16 * p.m_rows16));
         }
         if (cfg->n_tiles16) p.n_tiles16 = cfg->n_tiles16;
+        if (p.path == 4 && !cfg->m_rows16) p.m_rows16 = 0;      // tile height: chosen at launch
     }
+    if (p.path == 4 && !cfg) p.m_rows16 = 0;
     const int64_t KC = a.K / chunk_k(a.bits);
     if (p.path < 1 || p.path > 4) return RTN_ERR_CONFIG;
     if (p.path >= 3) {

@@ -4,19 +4,22 @@
 //   - packed 4-bit / 8-bit codes: dequantised on the way into LDS (fused path for a hundred rows and more),
 //   - dense fp16 weights [N, K]: the 16-bit GEMM of the dequantise-then-GEMM path.
 //
-// A workgroup of 4 wavefronts (2 x 2) computes a 128 x 128 tile of C; a wavefront owns 64 x 64 of it as 4 x 4
-// v_mfma_f32_16x16x32_f16 blocks (64 fp32 accumulator registers).  K advances in steps of 128 columns: the
-// 128 x 128 activation tile and the 128 x 128 weight tile of a step are staged in LDS (32 KiB each), in 16-byte
-// pieces XOR-swizzled with the row number (conflict-free b128 reads and writes without padding); every
-// operand read feeds four MFMAs.  Global loads of step t+1 are issued before the arithmetic of step t and held
-// in registers; two barriers per step swap the tiles.
+// A workgroup of 8 wavefronts (2 along M x 4 along N) computes a TM x 256 tile of C, TM = 128 or 256; a
+// wavefront owns (TM / 2) x 64 of it as MBW x 4 v_mfma_f32_16x16x32_f16 blocks (MBW = 4 or 8: 64 or 128 fp32
+// accumulator registers).  What bounds a GEMM of this kind on this chip is the traffic from L2 to the compute
+// units (about 11 TB/s in aggregate): a TM x 256 x 64 step moves (TM + 256) x 128 bytes of fp16 operands for
+// 2 x TM x 256 x 64 flops, 85 flop/B at TM = 128 and 128 flop/B at TM = 256 (packed int4 weights: 175 and
+// 210 flop/B), against 64 flop/B for 128 x 128 tiles.
+// K advances in steps of 64 columns through two LDS stages (one barrier per step); a row of a staged tile is
+// 128 bytes = eight 16-byte pieces, stored at piece ^ ((row >> 1) & 7) so that both the staging writes and the
+// b128 operand reads of 16 consecutive rows touch all 64 banks exactly once.  Global loads run two steps
+// (activations, dense weights) or one 128-column chunk (packed weights) ahead of their LDS stores, in registers.
 //
 // Fused dequantisation: a packed tile is unpacked once per workgroup (not once per wavefront), multiplied by
 // its group's scale in fp16 (one rounding per weight, relative error 2^-11, far inside the layer's tolerance)
 // and written to LDS as ordinary fp16, so the inner loop is that of the dense GEMM and carries no
-// per-accumulator scale arithmetic.  The vector ALU and the matrix cores of a SIMD do not overlap much on this
-// chip (measured), so vector instructions per MFMA are what this layout minimises: about two, against four in
-// the register-blocked wide kernel.
+// per-accumulator scale arithmetic.  The vector ALU and the matrix cores of a SIMD overlap little on this chip
+// (measured), so vector instructions per MFMA are what this layout minimises.
 #include "rtn_device.h"
 #include "rtn_internal.h"
 
@@ -24,8 +27,10 @@ namespace rtn {
 
 namespace {
 
-constexpr int kTile = 128;                      // rows and columns of the workgroup tile, and columns per k-step
-constexpr int kThreads = 256;
+constexpr int kTN = 256;                        // columns of C per workgroup
+constexpr int kBK = 64;                         // columns of K per step
+constexpr int kChunkK = 128;                    // packed weights are fetched in 128-column chunks (two steps)
+constexpr int kThreads = 512;
 constexpr uint32_t kOutOfRange = 0x7FFF0000u;
 constexpr int kBufferFlags = 0x00020000;
 constexpr int kXcds = 8;
@@ -38,25 +43,32 @@ struct TileParams {
     float* ws;
     int M, N, K;
     int G;                  // groups per row (packed sources)
-    int spg;                // k-steps per group
-    uint32_t spg_inv;
+    int cpg;                // 128-column chunks per group
+    uint32_t cpg_inv;       // floor(2^32 / cpg) + 1 (0 when cpg == 1)
     int KL;                 // packed tiles per weight row
     int XB, ZB;             // tiles along N, along M
     int split_k;
-    int ks_base, ks_rem;
+    int kc_base, kc_rem;    // workgroup sg covers 128-column chunks [sg*kc_base + min(sg, kc_rem), ...)
     uint32_t b_bytes, sc_bytes;   // packed sources only
 };
 
-// BSRC: 0 = dense fp16 weights, 4 / 8 = packed codes.
-template <int BSRC>
+__device__ __forceinline__ uint32_t swizzled(int row, int piece) {      // byte offset inside a staged tile
+    return (uint32_t)(row * 128 + ((piece ^ ((row >> 1) & 7)) * 16));
+}
+
+// BSRC: 0 = dense fp16 weights, 4 / 8 = packed codes.  MBW: 16-row blocks per wavefront along M (4 or 8).
+// PD: prefetch distance of the global loads in steps (activations, dense weights) or chunks (packed weights):
+// 2 with the 64-register accumulator tile, 1 with the 128-register one (256 registers per wavefront in all).
+template <int BSRC, int MBW, int PD = (MBW == 4 ? 2 : 1)>
 __global__ __launch_bounds__(kThreads, 2) void tile_gemm_kernel(const TileParams p) {
-    __shared__ __align__(16) uint8_t lds_a[kTile * kTile * 2];
-    __shared__ __align__(16) uint8_t lds_b[kTile * kTile * 2];
+    constexpr int TM = 32 * MBW;
+    constexpr int A_BYTES = TM * 128, B_BYTES = kTN * 128, STAGE = A_BYTES + B_BYTES;
+    extern __shared__ __align__(16) uint8_t lds[];           // two stages: [A tile][B tile]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave >> 2, wn = wave & 3;
     const int nl = lane & 15, kq = lane >> 4;
 
     // workgroup index -> (N tile, M tile): the ZB row tiles that share a weight tile are dispatched back to
@@ -66,14 +78,15 @@ __global__ __launch_bounds__(kThreads, 2) void tile_gemm_kernel(const TileParams
     const int zb = idx % p.ZB;
     const int xb = (idx / p.ZB) * kXcds + xcd;
     if (xb >= p.XB) return;
-    const int m0 = zb * kTile, n0 = xb * kTile;
+    const int m0 = zb * TM, n0 = xb * kTN;
     const int sg = blockIdx.y;
-    const int ks0 = sg * p.ks_base + min(sg, p.ks_rem);
-    const int T = p.ks_base + (sg < p.ks_rem ? 1 : 0);
+    const int kc0 = sg * p.kc_base + min(sg, p.kc_rem);      // first 128-column chunk
+    const int T = 2 * (p.kc_base + (sg < p.kc_rem ? 1 : 0)); // 64-column steps of this workgroup
+    const int ks0 = 2 * kc0;
 
     // Row-major fp16 operands are addressed through a resource that starts at this workgroup's first row and
     // ends after its last valid one (rows past M or N read as zeros; no 32-bit limit on the whole matrix).
-    const int a_rows = min(kTile, p.M - m0), b_rows = min(kTile, p.N - n0);
+    const int a_rows = min(TM, p.M - m0), b_rows = min(kTN, p.N - n0);
     const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<half_t*>(p.A) + (int64_t)m0 * p.K, 0, (uint32_t)a_rows * (uint32_t)p.K * 2u, kBufferFlags);
     const __amdgpu_buffer_rsrc_t rb = BSRC == 0
@@ -83,135 +96,163 @@ __global__ __launch_bounds__(kThreads, 2) void tile_gemm_kernel(const TileParams
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<half_t*>(p.scales), 0, p.sc_bytes, kBufferFlags);
     const uint32_t magic = fp16_magic_vgpr();
 
-    // ---- staging of row-major fp16 tiles (A always, B when dense): thread -> piece st_p of rows st_r + 16 i ----
-    const int st_p = tid & 15, st_r = tid >> 4;
-    const uint32_t st_slot = (uint32_t)(st_r * 16 + (st_p ^ st_r)) * 16;      // + i * 16 rows * 256 bytes
-    u32x4_t areg[8];
-    auto a_load = [&](int t) {
+    // ---- staging of row-major fp16 tiles (A always, B when dense): thread -> piece st_p of rows st_r + 64 i ----
+    const int st_p = tid & 7, st_r = tid >> 3;               // ((st_r + 64 i) >> 1) & 7 does not depend on i
+    const uint32_t st_off = swizzled(st_r, st_p);            // + i * 64 rows * 128 bytes
+    constexpr int NA = TM / 64;                              // pieces per thread per step
+    u32x4_t areg[PD][NA];
+    auto a_load = [&](int set, int t) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int row = st_r + 16 * i;
+        for (int i = 0; i < NA; ++i) {
+            const int row = st_r + 64 * i;
             const bool ok = t < T && row < a_rows;
-            const uint32_t off = ok ? ((uint32_t)row * (uint32_t)p.K + (uint32_t)(ks0 + t) * kTile + st_p * 8) * 2u : kOutOfRange;
-            areg[i] = __builtin_amdgcn_raw_buffer_load_b128(ra, off, 0, 0);
+            const uint32_t off = ok ? ((uint32_t)row * (uint32_t)p.K + (uint32_t)(ks0 + t) * kBK + st_p * 8) * 2u : kOutOfRange;
+            areg[set][i] = __builtin_amdgcn_raw_buffer_load_b128(ra, off, 0, 0);
         }
     };
-    auto a_store = [&]() {
+    auto a_store = [&](int set, int stage) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4_t*>(lds_a + st_slot + i * 4096) = areg[i];
+        for (int i = 0; i < NA; ++i) *reinterpret_cast<u32x4_t*>(lds + stage * STAGE + st_off + i * 8192) = areg[set][i];
     };
 
     // ---- weights ----
-    constexpr int NBREG = BSRC == 0 ? 8 : (BSRC == 4 ? 2 : 4);            // 16-byte loads per thread per step
-    u32x4_t breg[NBREG];
-    uint16_t sreg[BSRC == 0 ? 1 : 2];
-    auto b_load = [&](int t) {
-        const bool in = t < T;
-        const uint32_t ks = (uint32_t)(ks0 + t);
-        if constexpr (BSRC == 0) {
+    // dense: four pieces per thread per step, two steps ahead (set = step & 1)
+    // packed: wavefront w dequantises tile-rows 2w and 2w+1 of the 16 in the weight tile; a 128-column chunk
+    // (one int4 tile or two int8 tiles per tile-row, plus its scale) is fetched two chunks ahead (set = chunk & 1)
+    constexpr int TPC = BSRC == 8 ? 2 : 1;                   // packed tiles per chunk and tile-row
+    constexpr int NBR = BSRC == 0 ? 4 : 2 * TPC;
+    u32x4_t breg[PD][NBR];
+    uint16_t sreg[PD][2];
+    auto b_load_dense = [&](int set, int t) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int row = st_r + 16 * i;
-                const bool ok = in && row < b_rows;
-                const uint32_t off = ok ? ((uint32_t)row * (uint32_t)p.K + ks * kTile + st_p * 8) * 2u : kOutOfRange;
-                breg[i] = __builtin_amdgcn_raw_buffer_load_b128(rb, off, 0, 0);
-            }
-        } else {
-            // wavefront w dequantises tile-rows 2w and 2w+1 of the 8 in the weight tile
-            const uint32_t j = p.spg_inv == 0 ? ks : __umulhi(ks, p.spg_inv);
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const int nt = n0 / 16 + 2 * wave + c;
-                const bool ok = in && nt * 16 < p.N;
-                sreg[c] = __builtin_amdgcn_raw_buffer_load_b16(rs, ok ? ((uint32_t)(nt * 16 + nl) * (uint32_t)p.G + j) * 2u : kOutOfRange, 0, 0);
-                constexpr int TPS = BSRC == 4 ? 1 : 2;                    // packed tiles per step and tile-row
-#pragma unroll
-                for (int kt = 0; kt < TPS; ++kt)
-                    breg[c * TPS + kt] = __builtin_amdgcn_raw_buffer_load_b128(
-                        rb, ok ? ((uint32_t)nt * (uint32_t)p.KL + ks * TPS + kt) * 1024u + lane * 16 : kOutOfRange, 0, 2 /* nt */);
-            }
+        for (int i = 0; i < 4; ++i) {
+            const int row = st_r + 64 * i;
+            const bool ok = t < T && row < b_rows;
+            const uint32_t off = ok ? ((uint32_t)row * (uint32_t)p.K + (uint32_t)(ks0 + t) * kBK + st_p * 8) * 2u : kOutOfRange;
+            breg[set][i] = __builtin_amdgcn_raw_buffer_load_b128(rb, off, 0, 0);
         }
     };
-    auto b_store = [&]() {
-        if constexpr (BSRC == 0) {
+    auto b_load_packed = [&](int set, int c) {               // chunk c of this workgroup
+        const bool in = 2 * c < T;
+        const uint32_t kc = (uint32_t)(kc0 + c);
+        const uint32_t j = p.cpg_inv == 0 ? kc : __umulhi(kc, p.cpg_inv);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4_t*>(lds_b + st_slot + i * 4096) = breg[i];
-        } else {
-            constexpr int TPS = BSRC == 4 ? 1 : 2;
-            constexpr int MPT = Layout<BSRC>::MFMA_PER_TILE;
+        for (int q = 0; q < 2; ++q) {
+            const int nt = n0 / 16 + 2 * wave + q;
+            const bool ok = in && nt * 16 < p.N;
+            sreg[set][q] = __builtin_amdgcn_raw_buffer_load_b16(rs, ok ? ((uint32_t)(nt * 16 + nl) * (uint32_t)p.G + j) * 2u : kOutOfRange, 0, 0);
 #pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const half_t s = __builtin_bit_cast(half_t, sreg[c]);
-                const half2_t s2 = {s, s};
-                uint8_t* row = lds_b + (uint32_t)((2 * wave + c) * 16 + nl) * 256;
+            for (int kt = 0; kt < TPC; ++kt)
+                breg[set][q * TPC + kt] = __builtin_amdgcn_raw_buffer_load_b128(
+                    rb, ok ? ((uint32_t)nt * (uint32_t)p.KL + kc * TPC + kt) * 1024u + lane * 16 : kOutOfRange, 0, 2 /* nt */);
+        }
+    };
+    auto b_store_dense = [&](int set, int stage) {
 #pragma unroll
-                for (int kt = 0; kt < TPS; ++kt) {
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4_t*>(lds + stage * STAGE + A_BYTES + st_off + i * 8192) = breg[set][i];
+    };
+    auto b_store_packed = [&](int set, int half, int stage) {          // half = which 64 columns of the chunk
 #pragma unroll
-                    for (int o = 0; o < MPT; ++o) {
-                        Half8Words h;
-                        h.v = unpack_operand<BSRC>(breg[c * TPS + kt], o, magic);       // exact integers
+        for (int q = 0; q < 2; ++q) {
+            const half_t s = __builtin_bit_cast(half_t, sreg[set][q]);
+            const half2_t s2 = {s, s};
+            const int row = (2 * wave + q) * 16 + nl;
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) h.h2[q] = h.h2[q] * s2;             // fp16(q * S)
-                        const int piece = (kt * MPT + o) * 4 + kq;                      // 8 columns each
-                        *reinterpret_cast<half8_t*>(row + ((piece ^ nl) * 16)) = h.v;
-                    }
-                }
+            for (int o = 0; o < 2; ++o) {                                // two 32-column MFMA operands per half
+                Half8Words h;
+                if constexpr (BSRC == 4) h.v = unpack_word4(breg[set][q][2 * half + o], magic);
+                else h.v = unpack_words8(breg[set][q * 2 + half][2 * o], breg[set][q * 2 + half][2 * o + 1]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) h.h2[e] = h.h2[e] * s2;     // fp16(q * S)
+                *reinterpret_cast<half8_t*>(lds + stage * STAGE + A_BYTES + swizzled(row, o * 4 + kq)) = h.v;
             }
         }
     };
 
-    float4_t acc[4][4];
+    float4_t acc[MBW][4];
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
+    for (int b = 0; b < MBW; ++b)
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc[b][r] = (float4_t){0.f, 0.f, 0.f, 0.f};
 
-    const uint8_t* a_rd = lds_a + (uint32_t)((wm * 64 + nl) * 256);
-    const uint8_t* b_rd = lds_b + (uint32_t)((wn * 64 + nl) * 256);
-    auto compute = [&]() {
+    // operand rows of this lane: A rows wm*TM/2 + 16 b + nl, B rows wn*64 + 16 r + nl; ((row >> 1) & 7) == nl >> 1
+    const uint32_t a_rd = (uint32_t)((wm * (TM / 2) + nl) * 128);
+    const uint32_t b_rd = (uint32_t)(A_BYTES + (wn * 64 + nl) * 128);
+    auto compute = [&](int stage) {
+        const uint8_t* base = lds + stage * STAGE;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t po = (uint32_t)(((i * 4 + kq) ^ nl) * 16);
-            half8_t a[4], bq[4];
+        for (int i = 0; i < 2; ++i) {
+            const uint32_t po = (uint32_t)(((i * 4 + kq) ^ (nl >> 1)) * 16);
+            half8_t a[MBW], bq[4];
 #pragma unroll
-            for (int b = 0; b < 4; ++b) a[b] = *reinterpret_cast<const half8_t*>(a_rd + b * 4096 + po);
+            for (int r = 0; r < 4; ++r) bq[r] = *reinterpret_cast<const half8_t*>(base + b_rd + r * 2048 + po);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) bq[r] = *reinterpret_cast<const half8_t*>(b_rd + r * 4096 + po);
+            for (int b = 0; b < MBW; ++b) a[b] = *reinterpret_cast<const half8_t*>(base + a_rd + b * 2048 + po);
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
+            for (int b = 0; b < MBW; ++b)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[b][r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[b], bq[r], acc[b][r], 0, 0, 0);
+            if constexpr (MBW == 8) __builtin_amdgcn_sched_barrier(0);   // one slice's operands live at a time: 256 registers
         }
     };
 
-    // ---- main loop: registers hold step t+1 while LDS holds step t ----
-    a_load(0);
-    b_load(0);
-    a_store();
-    b_store();
-    a_load(1);
-    b_load(1);
-    __syncthreads();
-    for (int t = 0; t < T; ++t) {
-        compute();
-        __syncthreads();                  // everyone is done reading step t
-        a_store();
-        b_store();
-        a_load(t + 2);                    // out of range past the end: zeros, no traffic
-        b_load(t + 2);
+    // One step: arithmetic on stage (t & 1) while the next step's tiles go from registers into the other stage
+    // and the loads of step t+1+PD (chunk c+PD) are issued.  u = t & 3 is a literal at every call site.
+    auto step = [&](int u, int t) {
+        const int stage = u & 1;
+        const int set = PD == 2 ? (u & 1) : 0;               // register set that holds step t+1
+        compute(stage);
+        a_store(set, stage ^ 1);
+        if constexpr (BSRC == 0) {
+            b_store_dense(set, stage ^ 1);
+            a_load(set, t + 1 + PD);
+            b_load_dense(set, t + 1 + PD);
+        } else {
+            const int cset = PD == 2 ? (((u + 1) >> 1) & 1) : 0;    // set of chunk (t+1) >> 1
+            b_store_packed(cset, (u + 1) & 1, stage ^ 1);           // its half (t+1) & 1
+            a_load(set, t + 1 + PD);
+            if ((u & 1) == 0) b_load_packed(cset, (t >> 1) + PD);   // the chunk just finished leaves its registers
+        }
         __syncthreads();
+    };
+
+    // ---- prologue: step 0 into stage 0; registers then hold the next PD steps / chunks, issued in the loop's
+    // order so that its waits are exact counts ----
+    a_load(0, 0);
+    if constexpr (BSRC == 0) b_load_dense(0, 0); else b_load_packed(0, 0);
+    a_store(0, 0);
+    if constexpr (BSRC == 0) b_store_dense(0, 0); else b_store_packed(0, 0, 0);
+    a_load(0, 1);
+    if constexpr (BSRC == 0) b_load_dense(0, 1);
+    if constexpr (PD == 2) {
+        if constexpr (BSRC != 0) b_load_packed(1, 1);
+        a_load(1, 2);
+        if constexpr (BSRC == 0) b_load_dense(1, 2);
+    }
+    __syncthreads();
+
+    int t = 0;
+    for (; t + 4 <= T; t += 4) {          // no control flow between steps: every wait inside is an exact count
+        step(0, t);
+        step(1, t + 1);
+        step(2, t + 2);
+        step(3, t + 3);
+    }
+    if (t < T) {                          // T is even
+        step(0, t);
+        step(1, t + 1);
     }
 
-    // ---- store: lane holds rows 16 b + 4 kq + e, column 16 r + nl of its 64 x 64 tile ----
+    // ---- store: lane holds rows 16 b + 4 kq + e, column 16 r + nl of its wavefront tile ----
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int n = n0 + wn * 64 + r * 16 + nl;
         if (n >= p.N) continue;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
+        for (int b = 0; b < MBW; ++b) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int m = m0 + wm * 64 + b * 16 + kq * 4 + e;
+                const int m = m0 + wm * (TM / 2) + b * 16 + kq * 4 + e;
                 if (m < p.M) {
                     if (p.split_k == 1) p.C[(int64_t)m * p.N + n] = (half_t)acc[b][r][e];
                     else p.ws[((int64_t)sg * p.M + m) * p.N + n] = acc[b][r][e];
@@ -221,13 +262,33 @@ __global__ __launch_bounds__(kThreads, 2) void tile_gemm_kernel(const TileParams
     }
 }
 
-hipError_t launch_tile(const TileParams& tp, int bsrc, hipStream_t st) {
-    const int xb_pad = (tp.XB + kXcds - 1) / kXcds * kXcds;
-    dim3 grid((unsigned)(xb_pad * tp.ZB), (unsigned)tp.split_k, 1), block(kThreads);
-    if (bsrc == 0) hipLaunchKernelGGL((tile_gemm_kernel<0>), grid, block, 0, st, tp);
-    else if (bsrc == 4) hipLaunchKernelGGL((tile_gemm_kernel<4>), grid, block, 0, st, tp);
-    else hipLaunchKernelGGL((tile_gemm_kernel<8>), grid, block, 0, st, tp);
+template <int BSRC, int MBW>
+hipError_t launch_tile_inst(const TileParams& tp, dim3 grid, hipStream_t st) {
+    constexpr size_t lds = 2 * (size_t)(32 * MBW + kTN) * 128;
+    static bool attr_done = false;
+    if (!attr_done) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(tile_gemm_kernel<BSRC, MBW>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((tile_gemm_kernel<BSRC, MBW>), grid, dim3(kThreads), lds, st, tp);
     return hipGetLastError();
+}
+
+// rows16: 16-row blocks per wavefront (4 or 8), 0 = choose.
+hipError_t launch_tile(TileParams& tp, int bsrc, int64_t M, int rows16, hipStream_t st) {
+    // 256-row tiles only when there are several rounds of them for every compute unit: they halve the unpack and
+    // operand traffic per flop (a few per cent at thousands of rows) but quarter the number of workgroups
+    const int64_t xb = (tp.N + kTN - 1) / kTN;
+    const bool tall = rows16 ? rows16 == 8 : (M > 128 && xb * ((M + 255) / 256) * tp.split_k >= 1024);
+    const int tm = tall ? 256 : 128;
+    tp.XB = (int)xb;
+    tp.ZB = (int)((M + tm - 1) / tm);
+    const int xb_pad = (tp.XB + kXcds - 1) / kXcds * kXcds;
+    dim3 grid((unsigned)(xb_pad * tp.ZB), (unsigned)tp.split_k, 1);
+    if (bsrc == 0) return tall ? launch_tile_inst<0, 8>(tp, grid, st) : launch_tile_inst<0, 4>(tp, grid, st);
+    if (bsrc == 4) return tall ? launch_tile_inst<4, 8>(tp, grid, st) : launch_tile_inst<4, 4>(tp, grid, st);
+    return tall ? launch_tile_inst<8, 8>(tp, grid, st) : launch_tile_inst<8, 4>(tp, grid, st);
 }
 
 void fill_common(TileParams& tp, const void* A, void* C, float* ws, int64_t M, int64_t N, int64_t K, int split_k) {
@@ -235,19 +296,17 @@ void fill_common(TileParams& tp, const void* A, void* C, float* ws, int64_t M, i
     tp.C = static_cast<half_t*>(C);
     tp.ws = ws;
     tp.M = (int)M; tp.N = (int)N; tp.K = (int)K;
-    tp.XB = (int)((N + kTile - 1) / kTile);
-    tp.ZB = (int)((M + kTile - 1) / kTile);
     tp.split_k = split_k;
-    const int KS = (int)(K / kTile);
-    tp.ks_base = KS / split_k;
-    tp.ks_rem = KS % split_k;
+    const int KC = (int)(K / kChunkK);
+    tp.kc_base = KC / split_k;
+    tp.kc_rem = KC % split_k;
 }
 
 }  // namespace
 
 bool tile_plan_valid(const LinearArgs& a, const LinearPlan& p) {
-    if (a.g % kTile != 0 || a.K % kTile != 0) return false;
-    return p.split_k >= 1 && p.split_k <= a.K / kTile;
+    if (a.g % kChunkK != 0 || a.K % kChunkK != 0) return false;
+    return p.split_k >= 1 && p.split_k <= a.K / kChunkK;
 }
 
 hipError_t launch_linear_tile(const LinearArgs& a, const LinearPlan& p, hipStream_t st) {
@@ -256,12 +315,12 @@ hipError_t launch_linear_tile(const LinearArgs& a, const LinearPlan& p, hipStrea
     tp.B = a.qweight;
     tp.scales = static_cast<const half_t*>(a.scales);
     tp.G = (int)(a.K / a.g);
-    tp.spg = (int)(a.g / kTile);
-    tp.spg_inv = tp.spg == 1 ? 0u : (uint32_t)(((uint64_t)1 << 32) / (uint32_t)tp.spg) + 1u;
+    tp.cpg = (int)(a.g / kChunkK);
+    tp.cpg_inv = tp.cpg == 1 ? 0u : (uint32_t)(((uint64_t)1 << 32) / (uint32_t)tp.cpg) + 1u;
     tp.KL = (int)(a.K / (a.bits == 4 ? 128 : 64));
     tp.b_bytes = (uint32_t)((size_t)a.N * a.K * a.bits / 8);
     tp.sc_bytes = (uint32_t)((size_t)a.N * tp.G * 2);
-    hipError_t e = launch_tile(tp, a.bits, st);
+    hipError_t e = launch_tile(tp, a.bits, a.M, p.m_rows16 == 4 || p.m_rows16 == 8 ? p.m_rows16 : 0, st);
     if (e != hipSuccess) return e;
     if (p.split_k > 1) e = launch_splitk_reduce(a.workspace, a.C, a.M * a.N, p.split_k, st);
     return e;
@@ -273,10 +332,10 @@ hipError_t launch_gemm_fp16(const void* A, const void* W, void* C, float* worksp
     fill_common(tp, A, C, workspace, M, N, K, split_k);
     tp.B = W;
     tp.scales = static_cast<const half_t*>(W);           // unused by the dense source; any valid pointer
-    tp.G = 1; tp.spg = 1; tp.spg_inv = 0; tp.KL = 0;
+    tp.G = 1; tp.cpg = 1; tp.cpg_inv = 0; tp.KL = 0;
     tp.b_bytes = 0;
     tp.sc_bytes = 16;
-    hipError_t e = launch_tile(tp, 0, st);
+    hipError_t e = launch_tile(tp, 0, M, 0, st);
     if (e != hipSuccess) return e;
     if (split_k > 1) e = launch_splitk_reduce(workspace, C, M * N, split_k, st);
     return e;

@@ -238,22 +238,24 @@ def test_linear_wide_kernel(rtn, bits, g, M):
 @pytest.mark.parametrize("bits,g", [(4, 128), (4, 256), (4, 0), (8, 128), (8, 0)])
 @pytest.mark.parametrize("M", [3, 64, 128, 130, 300])
 def test_linear_tile_kernel(rtn, bits, g, M):
-    """The 128 x 128 tile kernel (path 4): ragged M and N (a partly empty last tile in both directions), K split
-    across workgroups, weights dequantised to fp16 on the way into LDS."""
+    """The tile kernel (path 4): both tile heights, ragged M and N (a partly empty last tile in both directions), K
+    split across workgroups (an odd number of chunks per workgroup included), weights dequantised to fp16 on the way
+    into LDS."""
     N, K = 400, 2560
     codes, scales, qw, sc, gg = _oracle_operands(N, K, bits, g, seed=8)
     A_t = synth.activation(M, K, seed=300 + M, device=DEV)
     ref = O.rtn_linear(_to_np(A_t), codes, scales, gg)
     for split in (1, 2, 5):
-        cfg = dict(path=4, split_k=split)
-        C = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=cfg)
-        torch.cuda.synchronize()
-        H.assert_linear_close(_to_np(C), ref, f"bits={bits} g={g} M={M} cfg={cfg}")
+        for rows16 in (0, 4, 8):            # tile height: chosen from M, 128 rows, 256 rows
+            cfg = dict(path=4, split_k=split, m_rows16=rows16)
+            C = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=cfg)
+            torch.cuda.synchronize()
+            H.assert_linear_close(_to_np(C), ref, f"bits={bits} g={g} M={M} cfg={cfg}")
     C2 = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=dict(path=4, split_k=5))
     assert torch.equal(C, C2)
 
 
-@pytest.mark.parametrize("M,N,K", [(1, 16, 128), (128, 128, 128), (200, 400, 2560), (1030, 272, 1024)])
+@pytest.mark.parametrize("M,N,K", [(1, 16, 128), (128, 128, 128), (200, 400, 2560), (1030, 272, 1024), (520, 4112, 384)])
 def test_dense_gemm_and_dual_path(rtn, M, N, K):
     """rtn_gemm_fp16 against an fp64 product of the same fp16 operands, and the dequantise-then-GEMM path of
     Section 5 against the oracle's linear layer."""
