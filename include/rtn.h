@@ -94,6 +94,19 @@ size_t rtn_workspace_nbytes(int64_t M, int64_t N, int64_t K, int bits, int group
 rtn_status rtn_quantize(const void* dev_W, int64_t N, int64_t K, int bits, int group_size, int flags,
                         void* dev_qweight, void* dev_scales, void* stream);
 
+/* Load-time pipeline (Sections 1 and 5: a model is quantised on the fly while it is loaded, shard by shard, so the
+ * 16-bit model never has to fit the GPU): RTN-quantise a weight tensor that lives in HOST memory.  Shards of
+ * rows_per_shard rows (a multiple of 16) are copied into two device staging buffers on `copy_stream` while the previous
+ * shard is quantised on `stream`; results are identical to rtn_quantize on the whole tensor.
+ *   host_W        in   fp16 [N, K] in host memory; pinned (hipHostMalloc / torch pin_memory) for the copies to overlap
+ *   dev_staging   scratch, >= rtn_quantize_host_staging_nbytes(K, rows_per_shard) = 2 shards of fp16 rows
+ *   stream, copy_stream   two different streams; the call returns after enqueueing, the packed tensor is complete when
+ *                 `stream` reaches the point after the call.  Creates and destroys five events per call (no device memory). */
+size_t rtn_quantize_host_staging_nbytes(int64_t K, int64_t rows_per_shard);
+rtn_status rtn_quantize_from_host(const void* host_W, int64_t N, int64_t K, int bits, int group_size, int flags,
+                                  void* dev_qweight, void* dev_scales, void* dev_staging, size_t staging_nbytes,
+                                  int64_t rows_per_shard, void* stream, void* copy_stream);
+
 /* Fused dequantise-GEMM of the weight-only quantised linear layer (Sections 2.3 and 5:
  * 16-bit activations times 4- or 8-bit weights, W4A16 / W8A16, for the small batches of
  * token generation):  C[m, n] = fp16( sum_k A[m, k] * q[n, k] * S[n, k / g] ), products and

@@ -62,6 +62,10 @@ def _load() -> C.CDLL:
     lib.rtn_unpack.argtypes = [vp, i64, i64, ci, vp, vp]
     lib.rtn_dequantize.restype = ci
     lib.rtn_dequantize.argtypes = [vp, vp, i64, i64, ci, ci, vp, vp]
+    lib.rtn_quantize_host_staging_nbytes.restype = sz
+    lib.rtn_quantize_host_staging_nbytes.argtypes = [i64, i64]
+    lib.rtn_quantize_from_host.restype = ci
+    lib.rtn_quantize_from_host.argtypes = [vp, i64, i64, ci, ci, ci, vp, vp, vp, sz, i64, vp, vp]
     lib.rtn_gemm_fp16.restype = ci
     lib.rtn_gemm_fp16.argtypes = [vp, i64, vp, i64, i64, vp, vp, sz, vp]
     lib.rtn_dense_weight_nbytes.restype = sz
@@ -79,7 +83,7 @@ def _load() -> C.CDLL:
 
 _lib = _load()
 EXPORTS = ["rtn_status_str", "rtn_layout_version", "rtn_qweight_nbytes", "rtn_scales_nbytes",
-           "rtn_workspace_nbytes", "rtn_quantize", "rtn_linear", "rtn_linear_ex", "rtn_linear_query",
+           "rtn_workspace_nbytes", "rtn_quantize", "rtn_quantize_host_staging_nbytes", "rtn_quantize_from_host", "rtn_linear", "rtn_linear_ex", "rtn_linear_query",
            "rtn_unpack", "rtn_dequantize", "rtn_gemm_fp16", "rtn_dense_weight_nbytes", "rtn_linear_dense",
            "rtn_layer_forward", "rtn_plan_bits", "rtn_plan_effective_bits"]
 
@@ -182,6 +186,30 @@ def rtn_dequantize(qweight: torch.Tensor, scales: torch.Tensor, K: int, bits: in
     _check(_lib.rtn_dequantize(qweight.data_ptr(), scales.data_ptr(), N, K, bits, group_size, W.data_ptr(),
                                _stream()), "rtn_dequantize")
     return W
+
+
+def rtn_quantize_from_host(W_host: torch.Tensor, bits: int, group_size: int, rows_per_shard: int, copy_stream,
+                           flags: int = RTN_SCALE_QMAX, staging: torch.Tensor = None, out=None, device="cuda:0"):
+    """W_host: fp16 [N, K] in (pinned) host memory -> (qweight, scales) on the GPU, quantised shard by shard with the
+    host-to-device copies on `copy_stream` (a torch.cuda.Stream other than the current one) overlapping the kernels."""
+    if W_host.is_cuda or W_host.dtype != torch.float16 or not W_host.is_contiguous() or W_host.dim() != 2:
+        raise ValueError("W_host must be a contiguous fp16 host matrix")
+    N, K = W_host.shape
+    g = K if group_size <= 0 else group_size
+    need = _lib.rtn_quantize_host_staging_nbytes(K, rows_per_shard)
+    if staging is None:
+        staging = torch.empty(max(need, 16), dtype=torch.uint8, device=device)
+    if out is None:
+        nb = _lib.rtn_qweight_nbytes(N, K, bits)
+        ns = _lib.rtn_scales_nbytes(N, K, g)
+        qweight = torch.empty(max(nb, 16), dtype=torch.uint8, device=device)[:nb]
+        scales = torch.empty((N, max(K // max(g, 1), 1)), dtype=torch.float16, device=device) if ns else torch.empty((N, 1), dtype=torch.float16, device=device)
+    else:
+        qweight, scales = out
+    _check(_lib.rtn_quantize_from_host(W_host.data_ptr(), N, K, bits, group_size, flags, qweight.data_ptr(),
+                                       scales.data_ptr(), staging.data_ptr(), staging.numel(), rows_per_shard,
+                                       _stream(), copy_stream.cuda_stream), "rtn_quantize_from_host")
+    return qweight, scales
 
 
 def rtn_gemm_fp16(A: torch.Tensor, W: torch.Tensor, out: torch.Tensor = None, workspace: torch.Tensor = None) -> torch.Tensor:

@@ -364,6 +364,64 @@ rtn_status rtn_dequantize(const void* dev_qweight, const void* dev_scales, int64
     return e == hipSuccess ? RTN_OK : RTN_ERR_HIP;
 }
 
+size_t rtn_quantize_host_staging_nbytes(int64_t K, int64_t rows_per_shard) {
+    if (K <= 0 || rows_per_shard <= 0 || rows_per_shard % 16 != 0) return 0;
+    return 2 * (size_t)rows_per_shard * (size_t)K * 2;
+}
+
+rtn_status rtn_quantize_from_host(const void* host_W, int64_t N, int64_t K, int bits, int group_size, int flags,
+                                  void* dev_qweight, void* dev_scales, void* dev_staging, size_t staging_nbytes,
+                                  int64_t rows_per_shard, void* stream, void* copy_stream) {
+    if (!host_W || !dev_qweight || !dev_scales || !dev_staging) return RTN_ERR_NULL;
+    int64_t g;
+    rtn_status st = check_problem(N, K, bits, group_size, &g);
+    if (st != RTN_OK) return st;
+    if (flags != RTN_SCALE_QMAX && flags != RTN_SCALE_EQ2) return RTN_ERR_CONFIG;
+    if (rows_per_shard <= 0 || rows_per_shard % 16 != 0) return RTN_ERR_SHAPE;
+    if (!aligned16(dev_qweight) || !aligned16(dev_scales) || !aligned16(dev_staging)) return RTN_ERR_ALIGN;
+    if (staging_nbytes < rtn_quantize_host_staging_nbytes(K, rows_per_shard)) return RTN_ERR_WORKSPACE;
+    if (stream == copy_stream) return RTN_ERR_CONFIG;          // the overlap needs two streams
+    hipStream_t qs = static_cast<hipStream_t>(stream), cs = static_cast<hipStream_t>(copy_stream);
+    const float qmax = (float)((1 << (bits - 1)) - 1);
+    const float divisor = (flags == RTN_SCALE_EQ2) ? qmax + 0.5f : qmax;
+    const size_t shard_bytes = (size_t)rows_per_shard * K * 2;
+    hipEvent_t copied[2], consumed[2], start;
+    bool ok = hipEventCreateWithFlags(&start, hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; i < 2 && ok; ++i) {
+        ok = hipEventCreateWithFlags(&copied[i], hipEventDisableTiming) == hipSuccess &&
+             hipEventCreateWithFlags(&consumed[i], hipEventDisableTiming) == hipSuccess;
+    }
+    if (!ok) return RTN_ERR_HIP;
+    // the copy stream starts after whatever the caller queued on `stream` before this call (the staging buffer
+    // may still be in use there)
+    ok = hipEventRecord(start, qs) == hipSuccess && hipStreamWaitEvent(cs, start, 0) == hipSuccess;
+    int64_t shard = 0;
+    for (int64_t r0 = 0; r0 < N && ok; r0 += rows_per_shard, ++shard) {
+        const int b = (int)(shard & 1);
+        const int64_t rows = (N - r0 < rows_per_shard) ? N - r0 : rows_per_shard;
+        uint8_t* stage = static_cast<uint8_t*>(dev_staging) + (size_t)b * shard_bytes;
+        // copy shard -> staging buffer b, once the quantise pass that last read buffer b is done
+        if (shard >= 2) ok = ok && hipStreamWaitEvent(cs, consumed[b], 0) == hipSuccess;
+        ok = ok && hipMemcpyAsync(stage, static_cast<const uint8_t*>(host_W) + (size_t)r0 * K * 2, (size_t)rows * K * 2,
+                                  hipMemcpyHostToDevice, cs) == hipSuccess;
+        ok = ok && hipEventRecord(copied[b], cs) == hipSuccess;
+        // quantise it on `stream` into its slice of the packed tensor (tile-rows and scale rows are contiguous)
+        ok = ok && hipStreamWaitEvent(qs, copied[b], 0) == hipSuccess;
+        if (ok) {
+            uint8_t* qdst = static_cast<uint8_t*>(dev_qweight) + (size_t)r0 * K * bits / 8;
+            uint8_t* sdst = static_cast<uint8_t*>(dev_scales) + (size_t)r0 * (K / g) * 2;
+            ok = rtn::launch_quantize(stage, rows, K, bits, g, divisor, qdst, sdst, qs) == hipSuccess;
+        }
+        ok = ok && hipEventRecord(consumed[b], qs) == hipSuccess;
+    }
+    (void)hipEventDestroy(start);
+    for (int i = 0; i < 2; ++i) {
+        (void)hipEventDestroy(copied[i]);                       // destruction is deferred until the events complete
+        (void)hipEventDestroy(consumed[i]);
+    }
+    return ok ? RTN_OK : RTN_ERR_HIP;
+}
+
 // Split-K of the dense GEMM: only as far as needed to give every compute unit a workgroup, within the workspace.
 static int dense_split(int64_t M, int64_t N, int64_t K, size_t workspace_nbytes) {
     const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);

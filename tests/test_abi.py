@@ -77,6 +77,13 @@ def test_argument_validation_happens_before_any_launch():
     assert lib.rtn_gemm_fp16(FAKE, 1, FAKE + 2, 16, 128, FAKE, None, 0, None) == 5
     assert lib.rtn_linear_dense(FAKE, 1, FAKE, FAKE, 64, 512, 4, 128, FAKE, FAKE, 100, None, 0, None) == 6
     assert rtn.rtn_dense_weight_nbytes(64, 512) == 64 * 512 * 2
+    qh = lib.rtn_quantize_from_host
+    assert lib.rtn_quantize_host_staging_nbytes(512, 32) == 2 * 32 * 512 * 2 and lib.rtn_quantize_host_staging_nbytes(512, 20) == 0
+    assert qh(None, 64, 512, 4, 128, 0, FAKE, FAKE, FAKE, 1 << 20, 32, None, FAKE) == 1
+    assert qh(FAKE, 64, 512, 4, 128, 0, FAKE, FAKE, FAKE, 1 << 20, 20, None, FAKE) == 4        # shard rows: a multiple of 16
+    assert qh(FAKE, 64, 512, 4, 128, 0, FAKE, FAKE, FAKE, 1000, 32, None, FAKE) == 6            # staging too small
+    assert qh(FAKE, 64, 512, 4, 128, 0, FAKE, FAKE, FAKE, 1 << 20, 32, FAKE, FAKE) == 7         # needs two streams
+    assert qh(FAKE, 64, 512, 4, 100, 0, FAKE, FAKE, FAKE, 1 << 20, 32, None, FAKE) == 3
     for bad in (dict(m_rows16=1), dict(m_rows16=5), dict(m_rows16=2, n_tiles16=3), dict(m_rows16=4, n_tiles16=4),
                 dict(m_rows16=2, n_tiles16=1, split_k=1000)):
         cfg = rtn.rtn_linear_cfg(path=3, **bad)                    # the wide kernel's register-tile limits

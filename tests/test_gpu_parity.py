@@ -99,6 +99,24 @@ def test_quantize_large_groups_every_kernel(rtn, bits, K, g):
     assert np.array_equal(_to_np(qw), O.pack_gfx950(codes, bits))
 
 
+@pytest.mark.parametrize("bits,g", [(4, 128), (8, 0)])
+@pytest.mark.parametrize("rows_per_shard", [16, 48, 112, 4096])
+def test_quantize_from_host_matches_device_quantize(rtn, bits, g, rows_per_shard):
+    """The load-time pipeline (host tensor -> staged shards -> quantise) gives the bits of a single rtn_quantize call,
+    for shard sizes that divide N, that do not, and that exceed it; twice in a row on the same staging buffer."""
+    N, K = 272, 2048
+    W_host = synth.heavy_tail_weight(N, K, 0.02, seed=21, device="cpu").pin_memory()
+    q_ref, s_ref = rtn.rtn_quantize(W_host.to(DEV), bits, g)
+    cs = torch.cuda.Stream()
+    staging = torch.empty(rtn._lib.rtn_quantize_host_staging_nbytes(K, rows_per_shard), dtype=torch.uint8, device=DEV)
+    for _ in range(2):
+        q, s = rtn.rtn_quantize_from_host(W_host, bits, g, rows_per_shard, cs, staging=staging, device=DEV)
+        torch.cuda.synchronize()
+        assert torch.equal(q, q_ref) and torch.equal(s.view(torch.int16), s_ref.view(torch.int16))
+    codes, scales = O.rtn_quantize(W_host.numpy(), bits, K if g == 0 else g)
+    assert np.array_equal(_to_np(q), O.pack_gfx950(codes, bits))
+
+
 def test_quantize_is_deterministic_and_dequantize_matches(rtn):
     N, K = 256, 2048
     W_t = synth.heavy_tail_weight(N, K, 0.02, seed=5, device=DEV)
