@@ -21,8 +21,9 @@
  *     A are [M, K] row-major, outputs C are [M, N] row-major, all IEEE binary16.
  *     N % 16 == 0.  K % 512 == 0 for 4-bit, K % 256 == 0 for 8-bit (one k-chunk of the
  *     GEMM kernels).  group_size g: g == K (or g <= 0) means one scale per output channel;
- *     otherwise g must be 128, 256, 512 or a multiple of 512 dividing K for 4-bit and 64,
- *     128, 256 or a multiple of 256 dividing K for 8-bit.
+ *     otherwise g must be 32, 64, 128, 256, 512 or a multiple of 512 dividing K for 4-bit and 32, 64,
+ *     128, 256 or a multiple of 256 dividing K for 8-bit (the paper uses 128 and per-channel; the
+ *     smaller groups of Section 2.2's discussion run on the skinny kernel at every M).
  *   - Scales are fp16 [N, K/g] row-major (group j of row n covers columns j*g .. j*g+g-1):
  *     the sub-channel grouping of Section 2.2.
  *

@@ -30,8 +30,8 @@ rtn_status check_problem(int64_t N, int64_t K, int bits, int group_size, int64_t
     int64_t g = (group_size <= 0) ? K : group_size;
     if (g > K || K % g != 0) return RTN_ERR_GROUP;
     const int ck = chunk_k(bits), tk = tile_k(bits);
-    if (g < ck) {
-        if (g != tk && g != 2 * tk && g != 4 * tk) return RTN_ERR_GROUP;
+    if (g < ck) {                                   // 32, 64, ... up to a k-chunk: a power-of-two number of groups per chunk
+        if (g != 32 && g != 64 && g != tk && g != 2 * tk && g != 4 * tk) return RTN_ERR_GROUP;
     } else if (g % ck != 0) {
         return RTN_ERR_GROUP;
     }
@@ -55,7 +55,7 @@ int device_max_lds() {
             hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && v > 0)
             cached = v < (int)rtn::kMaxLdsBytes ? v : (int)rtn::kMaxLdsBytes;
         else
-            cached = 64 * 1024;
+            cached = (int)rtn::kMaxLdsBytes;   // no device to ask (host-only planning): the gfx950 figure
     }
     return cached;
 }
@@ -226,7 +226,7 @@ rtn_status resolve_plan(const LinearArgs& a, const rtn_linear_cfg* cfg, size_t w
         *out = p;
         return RTN_OK;
     }
-    if (p.path == 2 && (a.M > 4 || p.prefetch != 1 || p.m_rows16 != 1)) return RTN_ERR_CONFIG;
+    if (p.path == 2 && (a.M > 4 || p.prefetch != 1 || p.m_rows16 != 1 || a.g < tile_k(a.bits))) return RTN_ERR_CONFIG;
     if (p.prefetch != 1 && p.prefetch != 2 && p.prefetch != 4) return RTN_ERR_CONFIG;
     if (p.m_rows16 != 1 && p.m_rows16 != 2 && p.m_rows16 != 4) return RTN_ERR_CONFIG;
     if (p.m_rows16 > 1 && p.prefetch != 1) return RTN_ERR_CONFIG;

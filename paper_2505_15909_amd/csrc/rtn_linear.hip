@@ -77,10 +77,14 @@ struct Geom {
     static constexpr int NM = kChunkTiles * MPT;          // MFMAs per chunk: 16 / 8
 };
 
+// The fp16 scales of one k-chunk of one weight row: NGC = groups per chunk = 1, 2, 4, 8 or 16 consecutive values.
+struct ScaleOct { u32x4_t v[2]; };
 template <int NGC> struct ScaleVec;
 template <> struct ScaleVec<1> { typedef uint16_t raw_t; };
 template <> struct ScaleVec<2> { typedef uint32_t raw_t; };
 template <> struct ScaleVec<4> { typedef u32x2_t raw_t; };
+template <> struct ScaleVec<8> { typedef u32x4_t raw_t; };
+template <> struct ScaleVec<16> { typedef ScaleOct raw_t; };
 
 template <int NGC>
 __device__ __forceinline__ float scale_at(const typename ScaleVec<NGC>::raw_t& raw, int i) {
@@ -90,7 +94,9 @@ __device__ __forceinline__ float scale_at(const typename ScaleVec<NGC>::raw_t& r
         half2_t h = __builtin_bit_cast(half2_t, raw);
         return (float)h[i];
     } else {
-        const uint32_t word = raw[i >> 1];     // by value: bit_cast of a vector-element lvalue reads element 0
+        uint32_t word;                         // by value: bit_cast of a vector-element lvalue reads element 0
+        if constexpr (NGC == 16) word = raw.v[i >> 3][(i >> 1) & 3];
+        else word = raw[i >> 1];
         half2_t h = __builtin_bit_cast(half2_t, word);
         return (float)h[i & 1];
     }
@@ -100,7 +106,14 @@ template <int NGC>
 __device__ __forceinline__ typename ScaleVec<NGC>::raw_t load_scales(__amdgpu_buffer_rsrc_t r, uint32_t off) {
     if constexpr (NGC == 1) return __builtin_amdgcn_raw_buffer_load_b16(r, off, 0, 0);
     else if constexpr (NGC == 2) return __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0);
-    else return __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0);
+    else if constexpr (NGC == 4) return __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0);
+    else if constexpr (NGC == 8) return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+    else {
+        ScaleOct o;                            // out-of-range offsets stay out of range: the resource is < 2 GiB
+        o.v[0] = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+        o.v[1] = __builtin_amdgcn_raw_buffer_load_b128(r, off + 16, 0, 0);
+        return o;
+    }
 }
 
 // MULTI = false: the workgroup's whole activation slice is staged once, before the main loop.
@@ -414,21 +427,23 @@ static void allow_large_lds(K kernel) {
     }
 }
 
+template <int BITS, int NGC, int NB, bool MULTI, int MB>
+static void launch_skinny_inst(const SkinnyParams& sp, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
+    if constexpr (NGC <= Geom<BITS>::NM) {     // at most one group per MFMA (32 columns)
+        allow_large_lds(skinny_mfma_kernel<BITS, NGC, NB, MULTI, MB>);
+        hipLaunchKernelGGL((skinny_mfma_kernel<BITS, NGC, NB, MULTI, MB>), grid, block, lds, st, sp);
+    }
+}
+
 template <int BITS, int NB, bool MULTI, int MB>
 static hipError_t launch_skinny_ngc(const SkinnyParams& sp, int ngc, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
     switch (ngc) {
-        case 1:
-            allow_large_lds(skinny_mfma_kernel<BITS, 1, NB, MULTI, MB>);
-            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 1, NB, MULTI, MB>), grid, block, lds, st, sp);
-            break;
-        case 2:
-            allow_large_lds(skinny_mfma_kernel<BITS, 2, NB, MULTI, MB>);
-            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 2, NB, MULTI, MB>), grid, block, lds, st, sp);
-            break;
-        default:
-            allow_large_lds(skinny_mfma_kernel<BITS, 4, NB, MULTI, MB>);
-            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, 4, NB, MULTI, MB>), grid, block, lds, st, sp);
-            break;
+        case 1: launch_skinny_inst<BITS, 1, NB, MULTI, MB>(sp, grid, block, lds, st); break;
+        case 2: launch_skinny_inst<BITS, 2, NB, MULTI, MB>(sp, grid, block, lds, st); break;
+        case 4: launch_skinny_inst<BITS, 4, NB, MULTI, MB>(sp, grid, block, lds, st); break;
+        case 8: launch_skinny_inst<BITS, 8, NB, MULTI, MB>(sp, grid, block, lds, st); break;
+        case 16: launch_skinny_inst<BITS, 16, NB, MULTI, MB>(sp, grid, block, lds, st); break;
+        default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }

@@ -93,24 +93,28 @@ __device__ __forceinline__ float scale_from_amax(float amax, float divisor) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Small groups (g = TPG tiles, TPG in {1, 2, 4}): one wavefront owns a (row-tile, group)
-// unit, keeps its 16 x g block in registers, reduces amax across the four lanes that share a
-// row, and quantises from registers: W is read exactly once.
+// Small groups: one wavefront owns a 16-row block of TPG tiles (TPG in {1, 2, 4}) that holds SUB groups per
+// row (SUB = 1: g = TPG tiles; SUB = 2 or 4 with TPG = 1: g = half or a quarter of a tile, down to 32 columns),
+// keeps it in registers, reduces amax across the four lanes that share a row, and quantises from registers: W is
+// read exactly once.
 // ---------------------------------------------------------------------------------------
-template <int BITS, int TPG>
+template <int BITS, int TPG, int SUB>
 __global__ __launch_bounds__(256) void quantize_small_group_kernel(
     const half_t* __restrict__ W, uint8_t* __restrict__ qweight, half_t* __restrict__ scales,
     int64_t N, int64_t K, int64_t units, float divisor) {
     constexpr int TK = Layout<BITS>::TK;
     constexpr int OPT = TK / 32;                          // octets (16-byte loads) per lane per tile
+    constexpr int OPS = OPT / SUB;                        // octets per lane per sub-group (SUB > 1 only with TPG == 1)
+    static_assert(SUB == 1 || (TPG == 1 && OPT % SUB == 0), "sub-tile groups need one tile per unit");
     const int lane = threadIdx.x & 63;
     const int nl = lane & 15, kq = lane >> 4;
-    const int64_t G = K / (TPG * TK);                     // groups per row
+    const int64_t U = K / (TPG * TK);                     // units per row
+    const int64_t G = U * SUB;                            // groups per row
     const int64_t KT = K / TK;
     const int64_t wave0 = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     const int64_t nwaves = (int64_t)gridDim.x * (blockDim.x >> 6);
     for (int64_t u = wave0; u < units; u += nwaves) {
-        const int64_t nt = u / G, j = u % G;
+        const int64_t nt = u / U, j = u % U;
         const half_t* src = W + (nt * 16 + nl) * K + j * (TPG * TK) + kq * 8;
         u32x4_t raw[TPG][OPT];
 #pragma unroll
@@ -118,24 +122,33 @@ __global__ __launch_bounds__(256) void quantize_small_group_kernel(
 #pragma unroll
             for (int t = 0; t < OPT; ++t)
                 raw[tp][t] = *reinterpret_cast<const u32x4_t*>(src + tp * TK + t * 32);
-        uint32_t m2 = 0u;
+        float r[SUB];
 #pragma unroll
-        for (int tp = 0; tp < TPG; ++tp)
+        for (int sg = 0; sg < SUB; ++sg) {
+            uint32_t m2 = 0u;
+            if constexpr (SUB == 1) {
 #pragma unroll
-            for (int t = 0; t < OPT; ++t) m2 = octet_amax(raw[tp][t], m2);
-        float m = amax_of_pair(m2);
-        m = fmaxf(m, __shfl_xor(m, 16));
-        m = fmaxf(m, __shfl_xor(m, 32));
-        const float s = scale_from_amax(m, divisor);
-        const float r = group_reciprocal(s);
-        if (kq == 0) scales[(nt * 16 + nl) * G + j] = (half_t)s;
+                for (int tp = 0; tp < TPG; ++tp)
+#pragma unroll
+                    for (int t = 0; t < OPT; ++t) m2 = octet_amax(raw[tp][t], m2);
+            } else {
+#pragma unroll
+                for (int t = 0; t < OPS; ++t) m2 = octet_amax(raw[0][sg * OPS + t], m2);
+            }
+            float m = amax_of_pair(m2);
+            m = fmaxf(m, __shfl_xor(m, 16));
+            m = fmaxf(m, __shfl_xor(m, 32));
+            const float s = scale_from_amax(m, divisor);
+            r[sg] = group_reciprocal(s);
+            if (kq == 0) scales[(nt * 16 + nl) * G + j * SUB + sg] = (half_t)s;
+        }
         uint8_t* dst = qweight + ((nt * KT + j * TPG) * 64 + lane) * 16;
 #pragma unroll
         for (int tp = 0; tp < TPG; ++tp) {
             u32x4_t chunk;
             uint32_t words[4];
 #pragma unroll
-            for (int t = 0; t < OPT; ++t) quantize_octet<BITS>(raw[tp][t], r, &words[t * (4 / OPT)]);
+            for (int t = 0; t < OPT; ++t) quantize_octet<BITS>(raw[tp][t], r[SUB == 1 ? 0 : t / OPS], &words[t * (4 / OPT)]);
             chunk[0] = words[0]; chunk[1] = words[1]; chunk[2] = words[2]; chunk[3] = words[3];
             *reinterpret_cast<u32x4_t*>(dst + (int64_t)tp * 1024) = chunk;
         }
@@ -307,13 +320,22 @@ static hipError_t launch_quantize_bits(const void* W, int64_t N, int64_t K, int6
     half_t* s = static_cast<half_t*>(scales);
     const int64_t tpg = g / TK;
     const int64_t units = (N / 16) * (K / g);
-    if (tpg == 1 || tpg == 2 || tpg == 4) {
+    if (g < TK) {                                             // 2 or 4 groups per tile (g = 32 or 64)
+        const int sub = (int)(TK / g);
+        const int64_t tiles = (N / 16) * (K / TK);
+        int64_t blocks = (tiles + 3) / 4;
+        if (blocks > 256 * 64) blocks = 256 * 64;
+        dim3 grid((unsigned)blocks), block(256);
+        if (sub == 2) hipLaunchKernelGGL((quantize_small_group_kernel<BITS, 1, 2>), grid, block, 0, st, w, q, s, N, K, tiles, divisor);
+        else if constexpr (BITS == 4) hipLaunchKernelGGL((quantize_small_group_kernel<BITS, 1, 4>), grid, block, 0, st, w, q, s, N, K, tiles, divisor);
+        else return hipErrorInvalidValue;
+    } else if (tpg == 1 || tpg == 2 || tpg == 4) {
         int64_t blocks = (units + 3) / 4;
         if (blocks > 256 * 64) blocks = 256 * 64;             // grid-stride beyond this
         dim3 grid((unsigned)blocks), block(256);
-        if (tpg == 1) hipLaunchKernelGGL((quantize_small_group_kernel<BITS, 1>), grid, block, 0, st, w, q, s, N, K, units, divisor);
-        else if (tpg == 2) hipLaunchKernelGGL((quantize_small_group_kernel<BITS, 2>), grid, block, 0, st, w, q, s, N, K, units, divisor);
-        else hipLaunchKernelGGL((quantize_small_group_kernel<BITS, 4>), grid, block, 0, st, w, q, s, N, K, units, divisor);
+        if (tpg == 1) hipLaunchKernelGGL((quantize_small_group_kernel<BITS, 1, 1>), grid, block, 0, st, w, q, s, N, K, units, divisor);
+        else if (tpg == 2) hipLaunchKernelGGL((quantize_small_group_kernel<BITS, 2, 1>), grid, block, 0, st, w, q, s, N, K, units, divisor);
+        else hipLaunchKernelGGL((quantize_small_group_kernel<BITS, 4, 1>), grid, block, 0, st, w, q, s, N, K, units, divisor);
     } else if (tpg * (TK / 32) <= 16 * 28) {
         // the unit fits the registers of one 16-wavefront workgroup: 8, 16 or 28 loads per lane
         const int64_t lpl = (tpg * (TK / 32) + 15) / 16;

@@ -51,7 +51,7 @@ def _linear(A=FAKE, M=1, q=FAKE, s=FAKE, N=64, K=512, bits=4, g=128, Cp=FAKE, ws
 def test_argument_validation_happens_before_any_launch():
     assert _quant(W=None) == 1 and _quant(q=None) == 1 and _quant(s=None) == 1
     assert _quant(bits=3) == 2 and _quant(bits=16) == 2
-    assert _quant(g=96) == 3 and _quant(g=32) == 3 and _quant(g=1024) == 3      # 1024 > K
+    assert _quant(g=96) == 3 and _quant(g=16) == 3 and _quant(g=1024) == 3      # 1024 > K
     assert _quant(N=60) == 4 and _quant(K=640) == 4 and _quant(N=0) == 4
     assert _quant(W=FAKE + 8) == 5 and _quant(q=FAKE + 2) == 5
     assert _quant(flags=7) == 7
@@ -72,6 +72,8 @@ def test_argument_validation_happens_before_any_launch():
     assert _linear(M=200, cfg=C.byref(cfg)) == 7                  # more splits than 128-column k-steps
     cfg = rtn.rtn_linear_cfg(path=4)
     assert _linear(M=200, bits=8, g=64, cfg=C.byref(cfg)) == 7    # group 64 is below the tile kernel's k-step
+    cfg = rtn.rtn_linear_cfg(path=2)
+    assert _linear(M=2, bits=4, g=64, cfg=C.byref(cfg)) == 7      # the vector-ALU variant needs whole-tile groups
     assert lib.rtn_gemm_fp16(None, 1, FAKE, 16, 128, FAKE, None, 0, None) == 1
     assert lib.rtn_gemm_fp16(FAKE, 1, FAKE, 16, 100, FAKE, None, 0, None) == 4
     assert lib.rtn_gemm_fp16(FAKE, 1, FAKE + 2, 16, 128, FAKE, None, 0, None) == 5
@@ -262,4 +264,31 @@ def test_reciprocal_and_snap_arithmetic_rounds_like_the_exact_quotient():
                     want = min(max(sign * even, -(1 << (bits - 1))), (1 << (bits - 1)) - 1)
                     assert got == want
                     checked += 1
+    assert checked > 3000
+
+
+def test_every_automatic_plan_is_a_valid_configuration():
+    """Host logic: for a spread of shapes (the paper's Llama shapes and random ones), every batch size and both
+    precisions, the plan rtn_linear would choose passes the library's own validation when handed back explicitly,
+    fits the 16 MiB workspace the size helper promises, and (no GPU here) only then fails at the launch itself."""
+    rng = np.random.default_rng(7)
+    shapes = [(4096, 6144), (4096, 4096), (4096, 28672), (14336, 4096), (8192, 10240), (8192, 57344), (28672, 8192),
+              (16384, 18432), (16384, 106496), (53248, 16384)]
+    for _ in range(40):
+        shapes.append((int(rng.integers(1, 40)) * 512, int(rng.integers(1, 600)) * 16))
+    Ms = [1, 2, 3, 4, 5, 8, 15, 16, 17, 31, 32, 33, 48, 49, 64, 65, 100, 128, 129, 256, 1000, 4096]
+    checked = 0
+    for K, N in shapes:
+        for bits, g in ((4, 32), (4, 64), (4, 128), (4, 0), (8, 32), (8, 64), (8, 128), (8, 0)):
+            if g and K % g:
+                continue
+            for M in Ms:
+                q = rtn.rtn_linear_query(M, N, K, bits, g)
+                assert q["path"] in (1, 3, 4), q
+                need = M * N * 4 * q["split_k"] if q["split_k"] > 1 else 0
+                assert need <= rtn._lib.rtn_workspace_nbytes(M, N, K, bits, g), (M, N, K, bits, g, q)
+                cfg = rtn.rtn_linear_cfg(**q)
+                st = lib.rtn_linear_ex(FAKE, M, FAKE, FAKE, N, K, bits, g, FAKE, FAKE, 16 << 20, None, C.byref(cfg))
+                assert st == 8, (st, M, N, K, bits, g, q)      # accepted by validation; the launch fails without a GPU
+                checked += 1
     assert checked > 3000

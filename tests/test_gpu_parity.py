@@ -36,8 +36,8 @@ def _quantize_both(W_t, bits, g, flags=0):
 # ----------------------------------------------------------------------------------------
 # quantise + pack
 # ----------------------------------------------------------------------------------------
-@pytest.mark.parametrize("bits,g", [(4, 128), (4, 256), (4, 512), (4, 1024), (4, 0), (8, 64), (8, 128),
-                                     (8, 256), (8, 512), (8, 0)])
+@pytest.mark.parametrize("bits,g", [(4, 32), (4, 64), (4, 128), (4, 256), (4, 512), (4, 1024), (4, 0), (8, 32), (8, 64),
+                                     (8, 128), (8, 256), (8, 512), (8, 0)])
 @pytest.mark.parametrize("N,K", [(80, 2048), (16, 512), (272, 3072)])
 def test_quantize_bit_exact_small(rtn, bits, g, N, K):
     if g > K or (g > 0 and K % g):
@@ -49,11 +49,11 @@ def test_quantize_bit_exact_small(rtn, bits, g, N, K):
     assert np.array_equal(_to_np(rtn.rtn_unpack(qw, N, K, bits)), codes)
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits,g", [(4, 128), (8, 64), (4, 32), (4, 64), (8, 32)])
 @pytest.mark.parametrize("flags", [0, 1])
-def test_quantize_adversarial(rtn, bits, flags):
+def test_quantize_adversarial(rtn, bits, g, flags):
     """Exact ties, all-zero groups, fp16 subnormals, +-65504, -0.0, one huge outlier per group."""
-    N, K, g = 64, 1024, 128 if bits == 4 else 64
+    N, K = 64, 1024
     rng = np.random.default_rng(11)
     W = (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
     qmax = (1 << (bits - 1)) - 1
@@ -149,7 +149,8 @@ CFGS = [dict(prefetch=nb, waves_n=wn, waves_k=wk, split_k=sk)
                                (1, 1, 16, 1), (2, 16, 1, 1), (1, 2, 8, 1), (2, 8, 2, 1), (1, 1, 3, 1), (1, 2, 7, 1), (2, 1, 5, 2)]]
 
 
-@pytest.mark.parametrize("bits,g", [(4, 128), (4, 256), (4, 512), (4, 0), (8, 64), (8, 128), (8, 256), (8, 0)])
+@pytest.mark.parametrize("bits,g", [(4, 32), (4, 64), (4, 128), (4, 256), (4, 512), (4, 0), (8, 32), (8, 64), (8, 128),
+                                     (8, 256), (8, 0)])
 def test_linear_all_configs_small(rtn, bits, g):
     N, K = 272, 3072            # 17 tile rows (ragged against every WN*R), 6 / 12 chunks
     codes, scales, qw, sc, gg = _oracle_operands(N, K, bits, g, seed=3)
