@@ -329,22 +329,37 @@ def main() -> int:
                 with torch.cuda.graph(g, stream=stream):
                     step_direct()
                 graphs.append(g)
+            # and one graph that holds a whole rotation (n_copies consecutive steps): replaying it issues n_copies
+            # steps with one submission, which takes the per-submission gap out of long runs
+            pass_no[0] = 0
+            rotation = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(rotation, stream=stream):
+                for _ in range(n_copies):
+                    step_direct()
     step_no = [0]
 
-    def step():
-        if graphs:
-            graphs[step_no[0] % n_copies].replay()
-        else:
-            step_direct()
-        step_no[0] += 1
+    def run_steps(n):
+        """Exactly n steps, in rotation order: whole rotations through the rotation graph, the rest step by step."""
+        done = 0
+        while done < n:
+            phase = step_no[0] % n_copies
+            if graphs and phase == 0 and n - done >= n_copies:
+                rotation.replay()
+                k = n_copies
+            elif graphs:
+                graphs[phase].replay()
+                k = 1
+            else:
+                step_direct()
+                k = 1
+            step_no[0] += k
+            done += k
 
     with torch.cuda.stream(stream):
-        for _ in range(args.warmup):
-            step()
+        run_steps(args.warmup)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step()
+        run_steps(args.steps)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
