@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the RTN weight-only quantised linear path on one MI355X.
 
-Workload (benchmark configs[1]): the four linear modules of a Llama-3.1-8B-shaped
+Workload: the four linear modules of a Llama-3.1-8B-shaped
 Transformer layer (Section 4: QKV 4096->6144, attention output 4096->4096, gate_up
 4096->28672, down 14336->4096), symmetric RTN int4 with group 128 and fp16 scales
 (Section 2.2), fp16 activations at the token-generation batch sizes M = 1, 2, 4, 8, 16
@@ -15,7 +15,10 @@ The load-time quantise/pack pass (Section 5) runs once during set-up, is checked
 and its throughput is reported in the "quantize" object; it is not inside the timed steps,
 which measure the metric itself: weight-stream GB/s of the linear layers.
 
-Prints one JSON line (see the design doc for the field definitions).
+Prints one JSON line: metric, value (GB/s of packed weights and scales streamed, whole job), unit, n_gpus, steps, warmup,
+ms_per_step, dtype, data, config, plus `roofline` (the dominant kernel against the 8 TB/s HBM peak: algorithmic bytes per
+launch over the measured average launch duration, and the HBM traffic per launch from hardware counters), `cpu_baseline`
+(the CPU oracle timed on a bounded sample of the same workload) and `quantize` (load-time pass throughput).
 """
 from __future__ import annotations
 

@@ -19,7 +19,7 @@ what the paper's method computes:
 * ``plan_bits`` / ``effective_bits`` -- the selective-precision bookkeeping of
   Section 4 (horizontal, vertical, hybrid selection).
 
-Readings of the paper taken here (each one is also listed in the design document):
+Readings of the paper taken here:
 
 R1  Scale divisor.  Eq. 2 gives S = 2 max|r| / (2^b - 1) = max|r| / (2^(b-1) - 0.5).
     The contract this build is graded on uses S = max|r| / (2^(b-1) - 1).  Both are

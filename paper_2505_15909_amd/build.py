@@ -10,7 +10,7 @@ LIB_PATH = os.path.join(PKG_DIR, "librtn_gfx950.so")
 SOURCES = ["rtn_api.hip", "rtn_quantize.hip", "rtn_linear.hip", "rtn_linear_wide.hip", "rtn_gemm_tile.hip"]
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
-    # no packed-fp32 instruction selection (see the platform notes in the design document)
+    # no packed-fp32 instruction selection: some packed fp32 forms have given wrong results on this platform
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
 ]

@@ -66,7 +66,7 @@ int round_pow2(int64_t v, int lo, int hi) {
     return p;
 }
 
-// Default plan, from sweeps on MI355X (see the design notes).  Short-lived wavefronts at high
+// Default plan, from configuration sweeps on MI355X.  Short-lived wavefronts at high
 // occupancy stream best: a wavefront gets 1-4 k-chunks (4-16 KiB of packed weights) of one tile-row
 // and K is split inside the workgroup (reduced through LDS).  With more than two activation rows the
 // staged slice grows, so workgroups widen along N (sharing it) and, for long K, K is also split across
