@@ -377,6 +377,34 @@ def test_full_size_quantize_and_linear(rtn, case):
             print(f"{name} {mod} M={M} ok", flush=True)
 
 
+@pytest.mark.parametrize("M", [512, 1500])
+def test_full_size_large_batch_fused_and_dual_path(rtn, M):
+    """Prefill-sized inputs on the full 8B-shaped gate_up and down matrices (Section 5): the fused path (tile kernel
+    where it has a full round of output tiles, wide kernel otherwise) and the dequantise-then-GEMM path, both against
+    the oracle on a stripe of 16-row tiles."""
+    ws = torch.empty(16 << 20, dtype=torch.uint8, device=DEV)
+    for idx, mod in enumerate(("gate_up", "down")):
+        K, N = synth.LLAMA_8B[mod]
+        W_t = synth.normal_weight(N, K, 0.02, seed=idx, device=DEV)
+        qw, sc = rtn.rtn_quantize(W_t, 4, 128)
+        tiles = H.pick_row_tiles(N, 12, seed=idx)
+        rows = H.tile_rows(tiles, N)
+        codes, scales = O.rtn_quantize(_to_np(W_t[torch.from_numpy(rows).to(DEV)]), 4, 128)
+        del W_t
+        A_t = synth.activation(M, K, seed=400 + M, device=DEV)
+        ref = O.rtn_linear(_to_np(A_t), codes, scales, 128)
+        sel = torch.from_numpy(rows).to(DEV)
+        C = rtn.rtn_linear(A_t, qw, sc, 4, 128, workspace=ws)
+        torch.cuda.synchronize()
+        H.assert_linear_close(_to_np(C[:, sel]), ref, f"{mod} M={M} fused path {rtn.rtn_linear_query(M, N, K, 4, 128)['path']}")
+        tmp = torch.empty(rtn.rtn_dense_weight_nbytes(N, K), dtype=torch.uint8, device=DEV)
+        C2 = rtn.rtn_linear_dense(A_t, qw, sc, 4, 128, tmp, workspace=ws)
+        torch.cuda.synchronize()
+        H.assert_linear_close(_to_np(C2[:, sel]), ref, f"{mod} M={M} dual path")
+        del tmp
+        print(f"{mod} M={M} fused and dual ok", flush=True)
+
+
 def test_full_size_405b_selective_layer(rtn):
     """The 405B-shaped selective-precision decoder layer at full width (qkv and gate_up int4 g128, o and
     down int8 per-channel), quantised on the GPU and run through rtn_layer_forward at M = 1, 16, 128;
