@@ -103,6 +103,7 @@ def report(args, rtn, synth, torch, np, dev) -> int:
             A = synth.activation(M, K, 100 + M, dev)
             t = _time_linear(rtn, torch, np, A, qws, sc, bits, g, None, ws, graph=not args.no_graph)
             tot[M] += t
+            t_hot = _time_linear(rtn, torch, np, A, qws[:1], sc, bits, g, None, ws, reps=12) if args.hot else None
             plan = rtn.rtn_linear_query(M, N, K, bits, g)
             line = (f"{name:8s} {K:6d}->{N:6d} M={M:3d}  {t:8.2f} us  {nbytes / t / 1e3:7.0f} GB/s  "
                     f"{nbytes / t / 80e3:5.1f} %  {2.0 * M * N * K / t / 1e6:7.2f} TFLOP/s  ")
@@ -112,6 +113,8 @@ def report(args, rtn, synth, torch, np, dev) -> int:
                 line += f"tile kernel (128 or 256 rows x 256 columns per workgroup) split {plan['split_k']}"
             else:
                 line += f"skinny {plan['waves_n']}x{plan['waves_k']} split {plan['split_k']} rows16 {plan['m_rows16']}"
+            if t_hot is not None:
+                line += f"  | one buffer (cache-hot) {t_hot:7.2f} us"
             if args.compare_paths and M <= 4:
                 c2 = dict(path=2, waves_n=plan["waves_n"], waves_k=plan["waves_k"], split_k=plan["split_k"])
                 try:
@@ -121,7 +124,8 @@ def report(args, rtn, synth, torch, np, dev) -> int:
             print(line, flush=True)
         del qws, qw
     for M in Ms:
-        print(f"layer set M={M:3d}: {tot[M]:8.2f} us  {totb / tot[M] / 1e3:7.0f} GB/s  {totb / tot[M] / 80e3:5.1f} % of 8 TB/s")
+        print(f"layer set M={M:3d}: {tot[M]:8.2f} us  {totb / tot[M] / 1e3:7.0f} GB/s  {totb / tot[M] / 80e3:5.1f} % of 8 TB/s"
+              f"  ({totb / tot[M] / 70.5e3:5.1f} % of the 7.05 TB/s a plain read kernel reaches on this chip)")
     return 0
 
 
@@ -259,6 +263,8 @@ def main() -> int:
                     help="instead of the JSON line, print fused kernels vs dequantise + dense GEMM over --batches")
     ap.add_argument("--bits", type=int, default=4, help="--report only: 4 (group 128) or 8 (per-channel)")
     ap.add_argument("--batches", type=str, default="1,2,4,8,16", help="--report only")
+    ap.add_argument("--hot", action="store_true",
+                    help="--report only: also time launches on a single weight copy (cache-resident when it fits the 256 MB Infinity Cache)")
     ap.add_argument("--compare-paths", action="store_true",
                     help="--report only: also time the vector-ALU v_dot2 variant (M <= 4) in the same workgroup shape")
     args = ap.parse_args()
