@@ -300,6 +300,49 @@ def test_dense_gemm_and_dual_path(rtn, M, N, K):
                 rtn.rtn_linear_dense(A_t, qw, sc, bits, g, tmp[:-16], workspace=ws)
 
 
+def test_linear_seeded_random_shapes_and_plans(rtn):
+    """A seeded sweep of small random problems -- odd numbers of tile-rows and k-chunks, ragged M, every group size,
+    the automatic plan and random explicit plans of every path -- against the oracle.  Plans the library refuses
+    (status 7) are skipped; every accepted one must be right."""
+    rng = np.random.default_rng(2024)
+    ran = {1: 0, 2: 0, 3: 0, 4: 0}
+    for case in range(48):
+        bits = int(rng.choice([4, 8]))
+        ck = 512 if bits == 4 else 256
+        K = int(rng.integers(1, 9)) * ck
+        N = int(rng.integers(1, 40)) * 16
+        gs = [g for g in (32, 64, 128, 256, 512, 1024, 0) if g == 0 or (K % g == 0 and (g < ck or g % ck == 0))]
+        g = int(rng.choice(gs))
+        M = int(rng.choice([1, 2, 3, 4, 5, 9, 16, 17, 31, 40, 64, 70, 129, 200]))
+        codes, scales, qw, sc, gg = _oracle_operands(N, K, bits, g, seed=case)
+        A_t = synth.activation(M, K, seed=500 + case, device=DEV)
+        ref = O.rtn_linear(_to_np(A_t), codes, scales, gg)
+        cfgs = [None]
+        for _ in range(3):
+            path = int(rng.choice([1, 1, 2, 3, 4]))
+            if path == 1:
+                cfgs.append(dict(path=1, prefetch=int(rng.choice([1, 2, 4])), waves_n=int(rng.choice([1, 2, 4, 8])),
+                                 waves_k=int(rng.integers(1, 9)), split_k=int(rng.integers(1, 4)),
+                                 m_rows16=int(rng.choice([1, 2, 4]))))
+            elif path == 2:
+                cfgs.append(dict(path=2, waves_n=int(rng.choice([1, 2, 4])), waves_k=int(rng.integers(1, 5))))
+            elif path == 3:
+                cfgs.append(dict(path=3, waves_n=int(rng.choice([4, 8, 16])), m_rows16=int(rng.choice([2, 3, 4])),
+                                 n_tiles16=int(rng.choice([1, 2, 4])), split_k=int(rng.integers(1, 5))))
+            else:
+                cfgs.append(dict(path=4, m_rows16=int(rng.choice([0, 4, 8])), split_k=int(rng.integers(1, 4))))
+        for cfg in cfgs:
+            try:
+                C = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=cfg)
+            except rtn.RtnError as e:
+                assert cfg is not None and e.status in (6, 7), (case, cfg, e.status)
+                continue
+            torch.cuda.synchronize()
+            H.assert_linear_close(_to_np(C), ref, f"case {case}: bits={bits} g={g} M={M} N={N} K={K} cfg={cfg}")
+            ran[cfg["path"] if cfg else rtn.rtn_linear_query(M, N, K, bits, g)["path"]] += 1
+    assert ran[1] >= 40 and ran[3] >= 8 and ran[4] >= 8 and ran[2] >= 1, ran
+
+
 @pytest.mark.parametrize("bits,g", [(4, 128), (8, 64), (8, 0)])
 def test_linear_special_cases(rtn, bits, g):
     N, K = 64, 1024
