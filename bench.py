@@ -246,6 +246,62 @@ def report_crossover(args, rtn, synth, torch, np, dev) -> int:
     return 0
 
 
+def report_grouped(args, rtn, synth, torch, np, dev) -> int:
+    """Expert-like independent modules: rtn_layer_forward (one launch per module) against rtn_grouped_forward."""
+    bits = args.bits
+    g = 128 if bits == 4 else 0
+    Ms = [int(x) for x in args.batches.split(",") if int(x) <= 16]
+    configs = [("experts 7168/2048 (8 active)", 7168, 2048, 8), ("experts 6144/16384 (8 active)", 6144, 16384, 8),
+               ("experts 2048/1024 (8 active)", 2048, 1024, 8)]
+    print(f"# int{bits}; us per call over all active experts (HIP-graph replay, calls rotate over >= 600 MB of distinct expert "
+          f"weights); serial = rtn_layer_forward, grouped = rtn_grouped_forward; every expert gets M rows of its own")
+    for label, hidden, inter, active in configs:
+        for mod, (K, N) in (("gate_up", (hidden, 2 * inter)), ("down", (inter, hidden))):
+            W = synth.normal_weight(N, K, 0.02, 1, dev)
+            qw, sc = rtn.rtn_quantize(W, bits, g)
+            del W
+            nbytes = qw.numel() + sc.numel() * 2
+            calls = max(1, int(np.ceil(600e6 / (nbytes * active))))
+            pool = [qw] + [qw.clone() for _ in range(calls * active - 1)]
+            for M in Ms:
+                plans = []
+                for c in range(calls):
+                    mods = [dict(A=synth.activation(M, K, 100 + e, dev), qweight=pool[c * active + e], scales=sc, bits=bits,
+                                 group_size=g, C=torch.empty((M, N), dtype=torch.float16, device=dev)) for e in range(active)]
+                    plans.append(rtn.LayerPlan(mods))
+                res = []
+                for grouped in (False, True):
+                    def issue():
+                        for _ in range(3):
+                            for pl in plans:
+                                pl.run_grouped() if grouped else pl.run()
+                    issue()
+                    torch.cuda.synchronize()
+                    cg = torch.cuda.CUDAGraph()
+                    st = torch.cuda.Stream()
+                    with torch.cuda.stream(st):
+                        with torch.cuda.graph(cg, stream=st):
+                            issue()
+                    cg.replay()
+                    torch.cuda.synchronize()
+                    ts = []
+                    for _ in range(5):
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record()
+                        cg.replay()
+                        e1.record()
+                        torch.cuda.synchronize()
+                        ts.append(e0.elapsed_time(e1) * 1e3 / (3 * calls))
+                    res.append(float(np.median(ts)))
+                tot = nbytes * active
+                print(f"{label:30s} {mod:8s} {K:6d}->{N:6d} M={M:2d}  serial {res[0]:8.2f} us {tot / res[0] / 1e3:6.0f} GB/s | grouped "
+                      f"{res[1]:8.2f} us {tot / res[1] / 1e3:6.0f} GB/s ({tot / res[1] / 80e3:4.1f} % of 8 TB/s) | grouped/serial {res[1] / res[0]:5.2f}",
+                      flush=True)
+                del plans
+            del pool, qw
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -261,6 +317,8 @@ def main() -> int:
                     help="instead of the JSON line, time the load-time pipeline from pinned host memory per matrix")
     ap.add_argument("--report-crossover", choices=["8b", "70b", "405b"], default=None,
                     help="instead of the JSON line, print fused kernels vs dequantise + dense GEMM over --batches")
+    ap.add_argument("--report-grouped", action="store_true",
+                    help="instead of the JSON line, time expert-like independent modules serially and through the grouped call")
     ap.add_argument("--bits", type=int, default=4, help="--report only: 4 (group 128) or 8 (per-channel)")
     ap.add_argument("--batches", type=str, default="1,2,4,8,16", help="--report only")
     ap.add_argument("--hot", action="store_true",
@@ -288,6 +346,8 @@ def main() -> int:
         return report_crossover(args, rtn, synth, torch, np, dev)
     if args.report_load:
         return report_load(args, rtn, synth, torch, np, dev)
+    if args.report_grouped:
+        return report_grouped(args, rtn, synth, torch, np, dev)
     modules = list(synth.LLAMA_8B.items())
 
     # ---- set-up: synthetic fp16 weights, load-time quantise (timed separately) ---------------

@@ -197,6 +197,20 @@ typedef struct {
 rtn_status rtn_layer_forward(const rtn_module* mods, int n_mods, void* dev_workspace,
                              size_t workspace_nbytes, void* stream);
 
+/* Grouped call for modules that do not depend on one another: the experts of a
+ * mixture-of-experts layer, each with its own weight matrix, its own rows of activations
+ * and -- the per-expert precision that Section 6 (Discussion) proposes, with the Mixtral
+ * 8x22B remark of the Limitations section -- its own bits; or projections that read the
+ * same input.  Same arguments and validation as
+ * rtn_layer_forward, but nothing is launched unless every module passes, the launch order
+ * is unspecified, and modules with M <= 16 and the same (bits, group size) class are merged,
+ * up to 16 at a time, into single grids whose workgroups each serve one module, so that one
+ * launch streams all their weights.  No dev_C may overlap any module's dev_A.  Results are
+ * those of rtn_linear with the plan rtn_grouped_forward picks (planned for the summed size),
+ * which may differ from the single call's in summation order only. */
+rtn_status rtn_grouped_forward(const rtn_module* mods, int n_mods, void* dev_workspace,
+                               size_t workspace_nbytes, void* stream);
+
 /* Hybrid selection rule of Section 4.3: bits of module `module_id` (1 = QKV projection,
  * 2 = attention output projection, 3 and 4 = feed-forward, numbering of Section 4.2) of
  * 0-based `layer` when X layers chosen by `policy` (first / last / middle, Section 4.1)

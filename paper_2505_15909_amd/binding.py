@@ -74,6 +74,8 @@ def _load() -> C.CDLL:
     lib.rtn_linear_dense.argtypes = [vp, i64, vp, vp, i64, i64, ci, ci, vp, vp, sz, vp, sz, vp]
     lib.rtn_layer_forward.restype = ci
     lib.rtn_layer_forward.argtypes = [C.POINTER(rtn_module), ci, vp, sz, vp]
+    lib.rtn_grouped_forward.restype = ci
+    lib.rtn_grouped_forward.argtypes = [C.POINTER(rtn_module), ci, vp, sz, vp]
     lib.rtn_plan_bits.restype = ci
     lib.rtn_plan_bits.argtypes = [ci, ci, ci, ci, ci, C.c_uint]
     lib.rtn_plan_effective_bits.restype = C.c_double
@@ -85,7 +87,7 @@ _lib = _load()
 EXPORTS = ["rtn_status_str", "rtn_layout_version", "rtn_qweight_nbytes", "rtn_scales_nbytes",
            "rtn_workspace_nbytes", "rtn_quantize", "rtn_quantize_host_staging_nbytes", "rtn_quantize_from_host", "rtn_linear", "rtn_linear_ex", "rtn_linear_query",
            "rtn_unpack", "rtn_dequantize", "rtn_gemm_fp16", "rtn_dense_weight_nbytes", "rtn_linear_dense",
-           "rtn_layer_forward", "rtn_plan_bits", "rtn_plan_effective_bits"]
+           "rtn_layer_forward", "rtn_grouped_forward", "rtn_plan_bits", "rtn_plan_effective_bits"]
 
 
 def _check(status: int, what: str):
@@ -267,9 +269,18 @@ class LayerPlan:
         _check(_lib.rtn_layer_forward(self.arr, self.n, self.workspace.data_ptr(), self.workspace.numel(),
                                       _stream()), "rtn_layer_forward")
 
+    def run_grouped(self):
+        """The modules as independent problems (rtn_grouped_forward): no C may be another module's A."""
+        _check(_lib.rtn_grouped_forward(self.arr, self.n, self.workspace.data_ptr(), self.workspace.numel(),
+                                        _stream()), "rtn_grouped_forward")
+
 
 def rtn_layer_forward(modules, workspace: torch.Tensor = None):
     LayerPlan(modules, workspace).run()
+
+
+def rtn_grouped_forward(modules, workspace: torch.Tensor = None):
+    LayerPlan(modules, workspace).run_grouped()
 
 
 def rtn_plan_bits(layer, n_layers, module_id, policy, X, modules=(1, 2, 3, 4)) -> int:

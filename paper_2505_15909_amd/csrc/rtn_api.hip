@@ -2,6 +2,7 @@
 // selective-precision dispatch.  No device code here.
 #include "../../include/rtn.h"
 #include "rtn_internal.h"
+#include <vector>
 #include <algorithm>
 #include <cmath>
 
@@ -118,7 +119,8 @@ void wide_plan(int64_t M, int64_t N, int64_t K, int bits, LinearPlan* p) {
 }
 
 // force_path: 0 = choose the path, otherwise the default plan of that path.
-LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_t lds_limit, int force_path = 0) {
+LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_t lds_limit, int force_path = 0,
+                     int64_t steps_hint = 0) {
     LinearPlan p;
     p.n_tiles16 = 1;
     // more than 16 rows: the wide kernel, except at 17-32 rows on matrices so large that the skinny kernel's
@@ -139,7 +141,8 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
         return p;
     }
     const int64_t NT = N / 16, KC = K / chunk_k(bits);
-    const int64_t steps = NT * KC;                             // 4 KiB chunk-steps in the whole matrix
+    // 4 KiB chunk-steps in the whole matrix, or in everything that shares the launch (grouped call)
+    const int64_t steps = NT * KC > steps_hint ? NT * KC : steps_hint;
     p.m_rows16 = M <= 16 ? 1 : (M <= 32 ? 2 : 4);              // weights are streamed once per 16/32/64 rows
     const int mrows = 16 * p.m_rows16;
     const int rows = (int)(M < mrows ? M + 1 : mrows);
@@ -471,6 +474,45 @@ rtn_status rtn_layer_forward(const rtn_module* mods, int n_mods, void* dev_works
         if (st != RTN_OK) return st;
     }
     return RTN_OK;
+}
+
+rtn_status rtn_grouped_forward(const rtn_module* mods, int n_mods, void* dev_workspace, size_t workspace_nbytes,
+                               void* stream) {
+    if (!mods) return RTN_ERR_NULL;
+    if (n_mods <= 0) return RTN_ERR_SHAPE;
+    if (!aligned16(dev_workspace)) return RTN_ERR_ALIGN;
+    const size_t lds_limit = (size_t)device_max_lds();
+    std::vector<LinearArgs> args((size_t)n_mods);
+    std::vector<LinearPlan> plans((size_t)n_mods);
+    int64_t steps_total = 0;                                   // of the modules the skinny kernel will serve
+    for (int i = 0; i < n_mods; ++i) {
+        const rtn_module& m = mods[i];
+        if (!m.dev_A || !m.dev_qweight || !m.dev_scales || !m.dev_C) return RTN_ERR_NULL;
+        int64_t g;
+        rtn_status st = check_problem(m.N, m.K, m.bits, m.group_size, &g);
+        if (st != RTN_OK) return st;
+        if (m.M <= 0 || m.M > (1 << 20)) return RTN_ERR_SHAPE;
+        if (!aligned16(m.dev_A) || !aligned16(m.dev_qweight) || !aligned16(m.dev_scales) || !aligned16(m.dev_C))
+            return RTN_ERR_ALIGN;
+        LinearArgs& a = args[i];
+        a.A = m.dev_A; a.qweight = m.dev_qweight; a.scales = m.dev_scales; a.C = m.dev_C;
+        a.workspace = static_cast<float*>(dev_workspace);
+        a.M = m.M; a.N = m.N; a.K = m.K; a.g = g; a.bits = m.bits;
+        if (m.M <= 16) steps_total += (m.N / 16) * (m.K / chunk_k(m.bits));
+    }
+    for (int i = 0; i < n_mods; ++i) {
+        const LinearArgs& a = args[i];
+        // planned as one slice of a launch that streams all the small-batch modules together
+        const LinearPlan h = auto_plan(a.M, a.N, a.K, a.bits, a.g, lds_limit, 0, a.M <= 16 ? steps_total : 0);
+        rtn_linear_cfg cfg;
+        cfg.path = h.path; cfg.prefetch = h.prefetch; cfg.waves_n = h.waves_n; cfg.waves_k = h.waves_k;
+        cfg.split_k = h.split_k; cfg.m_rows16 = h.m_rows16; cfg.n_tiles16 = h.n_tiles16;
+        rtn_status st = resolve_plan(a, &cfg, workspace_nbytes, &plans[i]);
+        if (st == RTN_ERR_CONFIG) st = resolve_plan(a, nullptr, workspace_nbytes, &plans[i]);   // the module's own plan
+        if (st != RTN_OK) return st;
+    }
+    hipError_t e = rtn::launch_linear_grouped(args.data(), plans.data(), n_mods, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RTN_OK : RTN_ERR_HIP;
 }
 
 static int layer_selected(int layer, int n_layers, int policy, int X) {

@@ -35,6 +35,8 @@ hipError_t launch_quantize(const void* W, int64_t N, int64_t K, int bits, int64_
 hipError_t launch_unpack(const void* qweight, const void* scales, int64_t N, int64_t K, int bits, int64_t g,
                          bool dequant, void* out, hipStream_t st);
 hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t st);
+// n independent problems with resolved plans: compatible skinny-kernel launches are merged into grouped launches.
+hipError_t launch_linear_grouped(const LinearArgs* args, const LinearPlan* plans, int n, hipStream_t st);
 // Path 3 (wide MFMA kernel): plan check (group size a multiple of 128, 2-4 row blocks, 1/2/4 tile-rows, at most 8 blocks) and launch.
 bool wide_plan_valid(const LinearArgs& a, const LinearPlan& p);
 hipError_t launch_linear_wide(const LinearArgs& a, const LinearPlan& p, hipStream_t st);

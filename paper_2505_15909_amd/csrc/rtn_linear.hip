@@ -34,6 +34,7 @@
 // exactly one scale per group (that of its own weight row).
 #include "rtn_device.h"
 #include "rtn_internal.h"
+#include <vector>
 
 namespace rtn {
 
@@ -124,8 +125,10 @@ __device__ __forceinline__ typename ScaleVec<NGC>::raw_t load_scales(__amdgpu_bu
 // (v_dot2_f32_f16, 4 per weight word and batch row; lane l accumulates row l % 16 over its own k-slots
 // and the four k-slot lanes of a row are summed by two cross-lane adds at the end) instead of the matrix
 // cores -- the wavefront-reduction GEMV the skinny MFMA path is measured against.
-template <int BITS, int NGC, int NB, bool MULTI, int MB, bool DOT = false>
-__global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p) {
+// The body takes the workgroup's coordinates as arguments so that one launch can also serve several independent
+// problems (grouped launch below).
+template <int BITS, int NGC, int NB, bool MULTI, int MB, bool DOT>
+__device__ __forceinline__ void skinny_body(const SkinnyParams& p, const int bx, const int by, const int bz) {
     typedef Geom<BITS> GM;
     typedef typename ScaleVec<NGC>::raw_t sraw_t;
     extern __shared__ __align__(16) uint8_t lds_bytes[];
@@ -138,13 +141,13 @@ __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p)
     const int nthreads = blockDim.x;
 
     constexpr int MROWS = 16 * MB;                                      // batch rows per workgroup
-    const int m0 = blockIdx.z * MROWS;
+    const int m0 = bz * MROWS;
     const int Mb = min(MROWS, p.M - m0);
-    const int sg = blockIdx.y;
+    const int sg = by;
     const int cb0 = sg * p.kc_base + min(sg, p.kc_rem);               // chunk range of this workgroup
     const int cb1 = cb0 + p.kc_base + (sg < p.kc_rem ? 1 : 0);
     const int cw0 = min(cb0 + wk * p.per, cb1), cw1 = min(cw0 + p.per, cb1);   // ... and of this wavefront
-    const int nt = blockIdx.x * p.WN + wn;
+    const int nt = bx * p.WN + wn;
     const bool nt_ok = nt < p.NT;
 
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.qw), 0, p.qw_bytes, kBufferFlags);
@@ -340,6 +343,29 @@ __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p)
     }
 }
 
+template <int BITS, int NGC, int NB, bool MULTI, int MB, bool DOT = false>
+__global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p) {
+    skinny_body<BITS, NGC, NB, MULTI, MB, DOT>(p, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+// Grouped launch: up to kMaxGroup independent problems of the same precision, group size and workgroup shape
+// and activation staging mode (e.g. the experts of a mixture-of-experts layer, or modules that do not feed one another) in one grid.
+// Workgroup b belongs to the problem g with first_block[g] <= b < first_block[g + 1].
+constexpr int kMaxGroup = 16;
+struct GroupedParams {
+    int n;
+    int first_block[kMaxGroup + 1];
+    SkinnyParams p[kMaxGroup];
+};
+
+template <int BITS, int NGC, bool MULTI>
+__global__ __launch_bounds__(1024) void skinny_grouped_kernel(const GroupedParams gp) {
+    const int b = blockIdx.x;
+    int g = 0;
+    for (int i = 1; i < gp.n; ++i) g = (b >= gp.first_block[i]) ? i : g;     // uniform
+    skinny_body<BITS, NGC, 1, MULTI, 1, false>(gp.p[g], b - gp.first_block[g], 0, 0);
+}
+
 // Sums the split-K partials in a fixed order and rounds once to fp16.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ ws, half_t* __restrict__ C,
                                                             int64_t MN, int split_k) {
@@ -482,12 +508,20 @@ static hipError_t launch_skinny(const SkinnyParams& sp, int ngc, int nb, bool mu
                  : launch_skinny_ngc<BITS, 4, false, 1>(sp, ngc, grid, block, lds, st);
 }
 
-hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t st) {
-    if (p.path == 3) return launch_linear_wide(a, p, st);
-    if (p.path == 4) return launch_linear_tile(a, p, st);
+// Everything a skinny-kernel launch needs, derived from the problem and its plan.
+struct SkinnyLaunch {
+    SkinnyParams sp;
+    dim3 grid, block;
+    size_t lds;
+    int ngc;
+    bool multi;
+};
+
+static SkinnyLaunch prepare_skinny(const LinearArgs& a, const LinearPlan& p) {
     const int tk = (a.bits == 4) ? 128 : 64;
     const int ck = kChunkTiles * tk;
-    SkinnyParams sp;
+    SkinnyLaunch L;
+    SkinnyParams& sp = L.sp;
     sp.A = static_cast<const half_t*>(a.A);
     sp.qw = static_cast<const uint8_t*>(a.qweight);
     sp.scales = static_cast<const half_t*>(a.scales);
@@ -518,24 +552,102 @@ hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t s
     sp.srp = p.waves_k * sgm.sc * (ck / 8);
     sp.srp_inv = (uint32_t)(((uint64_t)1 << 32) / (uint32_t)sp.srp) + 1u;
     sp.lds_stride = p.waves_k * sgm.sc * ck + kLdsPadHalves;
-    const int nthreads = 64 * p.waves_n * p.waves_k;
     sp.qw_bytes = (uint32_t)((size_t)a.N * a.K * a.bits / 8);
     sp.sc_bytes = (uint32_t)((size_t)a.N * sp.G * 2);
     sp.a_bytes = (uint32_t)((size_t)a.M * a.K * 2);
-    const int ngc = (a.g >= ck) ? 1 : (int)(ck / a.g);
-    dim3 grid((unsigned)((sp.NT + p.waves_n - 1) / p.waves_n), (unsigned)p.split_k, (unsigned)p.m_blocks);
-    dim3 block((unsigned)nthreads);
-    const size_t lds = sgm.lds;
+    L.ngc = (a.g >= ck) ? 1 : (int)(ck / a.g);
+    L.grid = dim3((unsigned)((sp.NT + p.waves_n - 1) / p.waves_n), (unsigned)p.split_k, (unsigned)p.m_blocks);
+    L.block = dim3((unsigned)(64 * p.waves_n * p.waves_k));
+    L.lds = sgm.lds;
+    L.multi = sgm.multi;
+    return L;
+}
+
+hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t st) {
+    if (p.path == 3) return launch_linear_wide(a, p, st);
+    if (p.path == 4) return launch_linear_tile(a, p, st);
+    const SkinnyLaunch L = prepare_skinny(a, p);
     hipError_t e;
     if (p.path == 2) {
-        e = (a.bits == 4) ? launch_dot<4>(sp, ngc, grid, block, lds, st) : launch_dot<8>(sp, ngc, grid, block, lds, st);
+        e = (a.bits == 4) ? launch_dot<4>(L.sp, L.ngc, L.grid, L.block, L.lds, st) : launch_dot<8>(L.sp, L.ngc, L.grid, L.block, L.lds, st);
     } else {
-        e = (a.bits == 4) ? launch_skinny<4>(sp, ngc, p.prefetch, sgm.multi, p.m_rows16, grid, block, lds, st)
-                          : launch_skinny<8>(sp, ngc, p.prefetch, sgm.multi, p.m_rows16, grid, block, lds, st);
+        e = (a.bits == 4) ? launch_skinny<4>(L.sp, L.ngc, p.prefetch, L.multi, p.m_rows16, L.grid, L.block, L.lds, st)
+                          : launch_skinny<8>(L.sp, L.ngc, p.prefetch, L.multi, p.m_rows16, L.grid, L.block, L.lds, st);
     }
     if (e != hipSuccess) return e;
-    if (p.split_k > 1) e = launch_splitk_reduce(a.workspace, sp.C, a.M * a.N, p.split_k, st);
+    if (p.split_k > 1) e = launch_splitk_reduce(a.workspace, L.sp.C, a.M * a.N, p.split_k, st);
     return e;
+}
+
+template <int BITS, int NGC>
+static void launch_grouped_inst(const GroupedParams& gp, bool multi, unsigned blocks, unsigned threads, size_t lds,
+                                hipStream_t st) {
+    if constexpr (NGC <= Geom<BITS>::NM) {
+        if (multi) {
+            allow_large_lds(skinny_grouped_kernel<BITS, NGC, true>);
+            hipLaunchKernelGGL((skinny_grouped_kernel<BITS, NGC, true>), dim3(blocks), dim3(threads), lds, st, gp);
+        } else {
+            allow_large_lds(skinny_grouped_kernel<BITS, NGC, false>);
+            hipLaunchKernelGGL((skinny_grouped_kernel<BITS, NGC, false>), dim3(blocks), dim3(threads), lds, st, gp);
+        }
+    }
+}
+
+template <int BITS>
+static hipError_t launch_grouped_bits(const GroupedParams& gp, int ngc, bool multi, unsigned blocks, unsigned threads,
+                                      size_t lds, hipStream_t st) {
+    switch (ngc) {
+        case 1: launch_grouped_inst<BITS, 1>(gp, multi, blocks, threads, lds, st); break;
+        case 2: launch_grouped_inst<BITS, 2>(gp, multi, blocks, threads, lds, st); break;
+        case 4: launch_grouped_inst<BITS, 4>(gp, multi, blocks, threads, lds, st); break;
+        case 8: launch_grouped_inst<BITS, 8>(gp, multi, blocks, threads, lds, st); break;
+        case 16: launch_grouped_inst<BITS, 16>(gp, multi, blocks, threads, lds, st); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// Independent problems: those whose plan is a plain skinny launch (no K split across workgroups, one row block,
+// default prefetch) are bucketed by (bits, groups per chunk, workgroup size, staging mode) and every bucket goes
+// out as grouped launches of up to kMaxGroup problems; the rest are launched one by one.
+hipError_t launch_linear_grouped(const LinearArgs* args, const LinearPlan* plans, int n, hipStream_t st) {
+    std::vector<char> done((size_t)n, 0);
+    std::vector<SkinnyLaunch> prep((size_t)n);
+    std::vector<char> eligible((size_t)n, 0);
+    for (int i = 0; i < n; ++i) {
+        const LinearPlan& p = plans[i];
+        if (p.path != 1 || p.split_k != 1 || p.m_blocks != 1 || p.prefetch != 1 || p.m_rows16 != 1) continue;
+        prep[i] = prepare_skinny(args[i], p);
+        eligible[i] = 1;
+    }
+    for (int i = 0; i < n; ++i) {
+        if (done[i]) continue;
+        if (!eligible[i]) {
+            hipError_t e = launch_linear(args[i], plans[i], st);
+            if (e != hipSuccess) return e;
+            done[i] = 1;
+            continue;
+        }
+        GroupedParams gp;
+        gp.n = 0;
+        gp.first_block[0] = 0;
+        size_t lds = 0;
+        for (int j = i; j < n && gp.n < kMaxGroup; ++j) {
+            if (done[j] || !eligible[j] || args[j].bits != args[i].bits || prep[j].ngc != prep[i].ngc ||
+                prep[j].block.x != prep[i].block.x || prep[j].multi != prep[i].multi)
+                continue;
+            gp.p[gp.n] = prep[j].sp;
+            gp.first_block[gp.n + 1] = gp.first_block[gp.n] + (int)prep[j].grid.x;
+            lds = prep[j].lds > lds ? prep[j].lds : lds;
+            ++gp.n;
+            done[j] = 1;
+        }
+        const hipError_t e = (args[i].bits == 4)
+            ? launch_grouped_bits<4>(gp, prep[i].ngc, prep[i].multi, (unsigned)gp.first_block[gp.n], prep[i].block.x, lds, st)
+            : launch_grouped_bits<8>(gp, prep[i].ngc, prep[i].multi, (unsigned)gp.first_block[gp.n], prep[i].block.x, lds, st);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_splitk_reduce(const float* workspace, void* C_fp16, int64_t MN, int split_k, hipStream_t st) {

@@ -101,6 +101,7 @@ def test_argument_validation_happens_before_any_launch():
     assert lib.rtn_unpack(None, 64, 512, 4, FAKE, None) == 1
     assert lib.rtn_dequantize(FAKE, FAKE, 64, 512, 4, 100, FAKE, None) == 3
     assert lib.rtn_layer_forward(None, 1, FAKE, 256, None) == 1
+    assert lib.rtn_grouped_forward(None, 1, FAKE, 256, None) == 1
 
 
 def test_bad_valid_combination_is_not_launched_without_gpu():

@@ -485,6 +485,46 @@ def test_full_size_405b_selective_layer(rtn):
         print(f"405b layer M={M} ok", flush=True)
 
 
+def test_grouped_forward_expert_modules(rtn):
+    """rtn_grouped_forward on independent expert-like modules (per-expert precision in mixture-of-experts models, Section 6): more
+    modules of one class than a grouped launch holds, several classes (int4 g128, int4 g32, int8 per-channel),
+    different shapes and row counts per module, and modules the grouped launch cannot merge (more than 16 rows, a
+    long K that splits across workgroups); every output against the oracle."""
+    rng = np.random.default_rng(77)
+    specs = []
+    for e in range(20):                                                   # one class, > 16 members, ragged M
+        specs.append((int(rng.integers(1, 8)), 768, 2048, 4, 128))
+    for e in range(3):
+        specs.append((int(rng.integers(1, 5)), 512, 1024, 4, 32))
+    for e in range(3):
+        specs.append((int(rng.integers(1, 17)), 1024, 1536, 8, 0))
+    specs.append((16, 640, 4096, 4, 128))                                 # 17 staged rows: several stages
+    specs.append((40, 512, 1024, 4, 128))                                 # wide kernel
+    specs.append((9, 256, 14336, 4, 128))                                 # long K: split across workgroups
+    mods, refs = [], []
+    for idx, (M, N, K, bits, g) in enumerate(specs):
+        W = _to_np(synth.normal_weight(N, K, 0.02, seed=900 + idx, device=DEV))
+        gg = K if g <= 0 else g
+        codes, scales = O.rtn_quantize(W, bits, gg)
+        A_t = synth.activation(M, K, seed=950 + idx, device=DEV)
+        mods.append(dict(A=A_t, qweight=torch.from_numpy(O.pack_gfx950(codes, bits)).to(DEV),
+                         scales=torch.from_numpy(scales).to(DEV), bits=bits, group_size=g,
+                         C=torch.full((M, N), float("nan"), dtype=torch.float16, device=DEV)))
+        refs.append(O.rtn_linear(_to_np(A_t), codes, scales, gg))
+    rtn.rtn_grouped_forward(mods)
+    torch.cuda.synchronize()
+    for i, (m, ref) in enumerate(zip(mods, refs)):
+        H.assert_linear_close(_to_np(m["C"]), ref, f"grouped module {i} {specs[i]}")
+    # a single module and a pair behave like the plain call
+    for lo, hi in ((0, 1), (20, 22)):
+        for m in mods[lo:hi]:
+            m["C"].fill_(float("nan"))
+        rtn.rtn_grouped_forward(mods[lo:hi])
+        torch.cuda.synchronize()
+        for i in range(lo, hi):
+            H.assert_linear_close(_to_np(mods[i]["C"]), refs[i], f"grouped subset module {i}")
+
+
 def test_selective_precision_layer(rtn):
     """Mixed 4-/8-bit decoder layer through rtn_layer_forward (Section 4.3), 405B-shaped at 1/8 width
     here; the full-width layer is exercised by the benchmark."""
