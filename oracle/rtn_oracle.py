@@ -10,6 +10,8 @@ what the paper's method computes:
 * ``rtn_scale`` / ``rtn_quantize``   -- symmetric round-to-nearest, Eq. 1 and Eq. 2
   of Section 2.2 (RTN), applied group-wise along every output channel as that
   section's last paragraphs describe.
+* ``rtn_quantize_asym`` / ``rtn_dequantize_asym`` / ``rtn_linear_asym`` -- the asymmetric
+  variant that Section 2.2 mentions (integer zero point), reading R10.
 * ``rtn_dequantize`` / ``rtn_linear`` -- the weight-only W4A16 / W8A16 linear layer
   of Section 2.3 and Section 5: C = A (q * S)^T, as a float64 GEMM on the
   dequantised weights.
@@ -35,6 +37,17 @@ R5  A group whose stored scale is zero (all-zero group, or amax so small that
     amax / D rounds to fp16 zero) gets scale +0 and all codes 0.
 R6  "truncate" of Eq. 1 = clamp to [-2^(b-1), 2^(b-1)-1].
 R7  Groups run along the input dimension K of each output row.
+R10 Asymmetric variant (Section 2.2 only says that it subtracts an integer zero point Z
+    from the result of Int()).  Taken here: the group's range [alpha, beta] =
+    [min(min r, 0), max(max r, 0)] always contains zero, so that zero is reproduced
+    exactly and Z fits the code range; S = fp16 of (beta - alpha) / (2^b - 1) with the
+    difference and the quotient each rounded to fp32 first (the precision the kernel
+    computes the scale in -- the difference of two fp16 values need not fit fp32);
+    Z = clamp(rne(alpha / S), -(2^b - 1), 0) + 2^(b-1), which sends alpha to the lowest
+    code; q = clamp(rne(r / S) - Z) (the tie rule applies to r / S, before Z is
+    subtracted); dequantised value S * (q + Z).  S == 0: Z = 2^(b-1), q = -2^(b-1),
+    i.e. the value 0.  The symmetric variant is not a special case of this one (its
+    range is [-max|r|, max|r|] and it never uses the lowest code's counterpart).
 
 Parity pins: tests/test_oracle_pins.py (worked examples in tests/golden/, exact
 rational cross-check, invariants, closed forms, brute force).  Model-level outputs
@@ -132,6 +145,70 @@ def rtn_linear(A: np.ndarray, codes: np.ndarray, scales: np.ndarray, group_size:
     for n0 in range(0, N, row_block):
         n1 = min(N, n0 + row_block)
         Wd = rtn_dequantize(codes[n0:n1], np.asarray(scales)[n0:n1], group_size)
+        out[:, n0:n1] = A64 @ Wd.T
+    return out
+
+
+def rtn_quantize_asym(W: np.ndarray, bits: int, group_size: int):
+    """Group-wise asymmetric RTN (Section 2.2's remark on the asymmetric variant; reading R10).
+
+    W: fp16 [N, K].  Returns (codes int8 [N, K], scales fp16 [N, K // g], zeros int16 [N, K // g])
+    with dequantised weights S * (q + Z).
+
+    alpha / S and w / S are exact real quotients rounded once to an integer: as in the
+    symmetric case both operands carry 11-bit significands, so the float64 quotient is
+    either an exact tie or far from one, and np.rint rounds the exact quotient half to even.
+    """
+    W = np.asarray(W)
+    if W.dtype != np.float16 or W.ndim != 2:
+        raise ValueError("W must be fp16 [N, K]")
+    N, K = W.shape
+    g = int(group_size)
+    if g <= 0 or K % g != 0:
+        raise ValueError("group_size must divide K")
+    if not np.all(np.isfinite(W)):
+        raise ValueError("W must be finite")
+    lo, hi = qrange(bits)
+    levels = (1 << bits) - 1
+    Wg = W.reshape(N, K // g, g)
+    alpha = np.minimum(Wg.min(axis=2), np.float16(0))            # fp16, <= 0
+    beta = np.maximum(Wg.max(axis=2), np.float16(0))             # fp16, >= 0
+    with np.errstate(over="ignore"):                             # a range beyond fp16 gives an infinite scale: rejected below
+        width = beta.astype(np.float32) - alpha.astype(np.float32)   # one fp32 rounding
+        scales = (width / np.float32(levels)).astype(np.float16)     # fp32 quotient, then fp16
+    if not np.all(np.isfinite(scales)):
+        raise ValueError("group range overflows the fp16 scale")
+    s64 = scales.astype(np.float64)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        t = np.rint(alpha.astype(np.float64) / s64)              # code of alpha before the shift, <= 0
+        t = np.where(s64 == 0.0, 0.0, t)
+        t = np.clip(t, -levels, 0)
+        zeros = t - lo                                           # Z = rne(alpha / S) + 2^(b-1)
+        r = np.rint(Wg.astype(np.float64) / s64[:, :, None])     # Int() before truncation: ties to even on r / S
+        r = np.where(s64[:, :, None] == 0.0, 0.0, r)
+    q = np.clip(r - zeros[:, :, None], lo, hi)
+    return q.reshape(N, K).astype(np.int8), scales, zeros.astype(np.int16)
+
+
+def rtn_dequantize_asym(codes: np.ndarray, scales: np.ndarray, zeros: np.ndarray, group_size: int) -> np.ndarray:
+    """float64 [N, K] of S * (q + Z) (reading R10)."""
+    codes = np.asarray(codes)
+    N, K = codes.shape
+    g = int(group_size)
+    s = np.asarray(scales, dtype=np.float16).astype(np.float64).reshape(N, K // g)
+    z = np.asarray(zeros).astype(np.float64).reshape(N, K // g)
+    return ((codes.astype(np.float64).reshape(N, K // g, g) + z[:, :, None]) * s[:, :, None]).reshape(N, K)
+
+
+def rtn_linear_asym(A: np.ndarray, codes: np.ndarray, scales: np.ndarray, zeros: np.ndarray, group_size: int,
+                    row_block: int = 4096) -> np.ndarray:
+    """C[m, n] = sum_k A[m, k] * S[n, k // g] * (q[n, k] + Z[n, k // g]) in float64."""
+    A64 = np.asarray(A, dtype=np.float16).astype(np.float64)
+    N = codes.shape[0]
+    out = np.empty((A64.shape[0], N), dtype=np.float64)
+    for n0 in range(0, N, row_block):
+        n1 = min(N, n0 + row_block)
+        Wd = rtn_dequantize_asym(codes[n0:n1], np.asarray(scales)[n0:n1], np.asarray(zeros)[n0:n1], group_size)
         out[:, n0:n1] = A64 @ Wd.T
     return out
 

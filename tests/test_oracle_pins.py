@@ -282,3 +282,131 @@ def test_selective_precision_accounting():
     assert O.plan_bits(0, 80, 2, "first", 1, (1, 3, 4)) == 4
     assert O.plan_bits(0, 80, 4, "first", 1, (1, 3, 4)) == 8
     assert O.plan_bits(1, 80, 4, "first", 1, (1, 3, 4)) == 4
+
+
+# --------------------------------------------------------------------------------------
+# Asymmetric variant (Section 2.2's remark; reading R10 in the oracle's header)
+# --------------------------------------------------------------------------------------
+def _round_binary(x: F, precision: int, min_quantum_exp: int) -> F:
+    """Round-half-even of a non-negative rational to a binary format with `precision` significand bits and smallest
+    quantum 2^min_quantum_exp (IEEE rounding restated with exact rationals; no overflow handling)."""
+    if x == 0:
+        return F(0)
+    e = x.numerator.bit_length() - x.denominator.bit_length()          # floor(log2 x) or one more
+    if F(2) ** e > x:
+        e -= 1
+    qe = max(e - precision + 1, min_quantum_exp)
+    quantum = F(2) ** qe
+    return _rne(x / quantum) * quantum
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_asym_matches_exact_rationals(bits):
+    rng = np.random.default_rng(100 + bits)
+    lo, hi = O.qrange(bits)
+    levels = (1 << bits) - 1
+    g = 32
+    W = (rng.standard_normal((8, 2 * g)) * 0.02).astype(np.float16)
+    W[0, :g] += np.float16(0.05)                       # mostly positive group
+    W[1, :g] = np.abs(W[1, :g])                        # all non-negative: alpha = 0
+    W[2, :g] = -np.abs(W[2, :g])                       # all non-positive: beta = 0
+    W[3, :g] = 0                                       # all zero
+    W[4, :g] = np.float16(3e-7) * (np.arange(g) % 5 - 1)     # subnormal scale
+    W[5, :g] = np.float16(0.37)                        # constant group (range is [0, 0.37])
+    # planted ties with an odd shift: range [-3, 12] in units of s = 2^-5, halves in between
+    W[6, :g] = (np.arange(g) % 31 * 0.5 - 3.0) * 2.0 ** -5
+    W[6, 0], W[6, 1] = -3.0 * 2.0 ** -5, 12.0 * 2.0 ** -5
+    W[7, :g] = np.float16(1.0) + np.float16(2.0 ** -10) * np.arange(g)     # far from zero, narrow spread
+    W[7, g] = np.float16(-2.0 ** -20) * np.float16(1.0 + 2.0 ** -10)     # beta - alpha does not fit fp32
+    W[7, g + 1] = np.float16(1.0)
+    # a (beta, alpha) pair where rounding beta - alpha to fp32 moves the fp16 scale (found by search over fp16 pairs)
+    hb, ha = {4: (16008, 33279), 8: (17014, 33217)}[bits]
+    W[5, g:] = 0
+    W[5, g] = np.array([hb], dtype=np.uint16).view(np.float16)[0]
+    W[5, g + 1] = np.array([ha], dtype=np.uint16).view(np.float16)[0]
+    codes, scales, zeros = O.rtn_quantize_asym(W, bits, g)
+    exact = (F(float(W[5, g])) - F(float(W[5, g + 1]))) / levels
+    assert _frac(scales[5, 1]) != _round_binary(exact, 11, -24)       # the fp32 steps are visible in this group
+    for n in range(W.shape[0]):
+        for j in range(2):
+            grp = [_frac(v) for v in W[n, j * g:(j + 1) * g]]
+            alpha, beta = min(min(grp), F(0)), max(max(grp), F(0))
+            width32 = _round_binary(beta - alpha, 24, -149)
+            s32 = _round_binary(width32 / levels, 24, -149)
+            s = _round_binary(s32, 11, -24)
+            assert _frac(scales[n, j]) == s, (n, j)
+            t = 0 if s == 0 else max(-levels, min(0, _rne(alpha / s)))
+            assert int(zeros[n, j]) == t - lo, (n, j)
+            for k in range(g):
+                r = 0 if s == 0 else _rne(grp[k] / s)
+                assert int(codes[n, j * g + k]) == max(lo, min(hi, r - (t - lo))), (n, j, k)
+    # the planted ties are ties, the shift is odd, and they went to even BEFORE the shift
+    if bits == 4:
+        assert float(scales[6, 0]) == 2.0 ** -5 and int(zeros[6, 0]) == -3 + 8
+        # k = 7, 9, 11: w / s = 0.5, 1.5, 2.5 -> 0, 2, 2 -> minus Z = 5
+        assert [int(codes[6, k]) for k in (7, 9, 11)] == [0 - 5, 2 - 5, 2 - 5]
+    assert scales[3, 0] == 0 and int(zeros[3, 0]) == -lo and (codes[3, :g] == lo).all()
+    assert float(scales[7, 1]) > 0          # the inexact-difference group went through
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_asym_nearest_level_zero_and_grid(bits):
+    rng = np.random.default_rng(5)
+    lo, hi = O.qrange(bits)
+    g = 64
+    W = (rng.standard_normal((32, 4 * g)) * 0.02 + 0.01).astype(np.float16)
+    W[:, ::7] = 0
+    codes, scales, zeros = O.rtn_quantize_asym(W, bits, g)
+    deq = O.rtn_dequantize_asym(codes, scales, zeros, g)
+    W64 = W.astype(np.float64)
+    s = np.repeat(scales.astype(np.float64), g, axis=1)
+    z = np.repeat(zeros.astype(np.float64), g, axis=1)
+    assert np.all(deq[W == 0] == 0.0)                                   # zero is a level of every group
+    # every code is a nearest level among all 2^b levels of its group (brute force over the levels)
+    best = np.full(W.shape, np.inf)
+    for q in range(lo, hi + 1):
+        best = np.minimum(best, np.abs(W64 - s * (q + z)))
+    assert np.all(np.abs(W64 - deq) <= best * (1 + 1e-12) + 1e-300)
+    # inside the covered range the error is at most half a step; the range ends can lose at most the scale's rounding
+    inside = (codes > lo) & (codes < hi)
+    assert np.all(np.abs(W64 - deq)[inside] <= s[inside] / 2)
+    assert np.all(np.abs(W64 - deq) <= s * (0.5 + ((1 << bits) - 1) * 2.0 ** -11))
+    # a group already on a shifted grid is reproduced exactly, with the shift as its zero point
+    c = 2.0 ** -7
+    Wg = (c * (np.arange(1 << bits) - 3)).astype(np.float16)[None, :].repeat(2, axis=0)
+    codes, scales, zeros = O.rtn_quantize_asym(Wg, bits, 1 << bits)
+    assert float(scales[0, 0]) == c and int(zeros[0, 0]) == -3 - lo
+    assert codes[0].tolist() == list(range(lo, hi + 1))
+    assert np.array_equal(O.rtn_dequantize_asym(codes, scales, zeros, 1 << bits), Wg.astype(np.float64))
+    # asymmetric resolution on a one-sided group is twice the symmetric one
+    Wp = np.abs(W[:4])
+    _, s_sym = O.rtn_quantize(Wp, bits, g)
+    _, s_asym, _ = O.rtn_quantize_asym(Wp, bits, g)
+    ratio = s_sym.astype(np.float64) / s_asym.astype(np.float64)
+    assert np.all(np.abs(ratio - ((1 << bits) - 1) / hi) < 0.01)
+
+
+def test_asym_linear_identity_and_bruteforce():
+    rng = np.random.default_rng(11)
+    N, K, M, g = 16, 128, 3, 32
+    W = (rng.standard_normal((N, K)) * 0.02 + 0.015).astype(np.float16)
+    A = rng.standard_normal((M, K)).astype(np.float16)
+    codes, scales, zeros = O.rtn_quantize_asym(W, 4, g)
+    C = O.rtn_linear_asym(A, codes, scales, zeros, g)
+    # sum_k A S (q + Z) = [symmetric-form linear on the same codes] + sum_groups Z S (sum of A over the group)
+    Asum = A.astype(np.float64).reshape(M, K // g, g).sum(axis=2)                     # [M, G]
+    corr = Asum @ (zeros.astype(np.float64) * scales.astype(np.float64)).T           # [M, N]
+    assert np.allclose(C, O.rtn_linear(A, codes, scales, g) + corr, rtol=1e-12, atol=1e-12)
+    # pure-Python loops
+    for m in range(M):
+        for n in range(0, N, 5):
+            acc = 0.0
+            for k in range(K):
+                acc += float(A[m, k]) * float(scales[n, k // g]) * (int(codes[n, k]) + int(zeros[n, k // g]))
+            assert abs(acc - C[m, n]) < 1e-9
+    # closeness to the unquantised product: asymmetric beats symmetric on shifted weights
+    exact = A.astype(np.float64) @ W.astype(np.float64).T
+    cs, ss = O.rtn_quantize(W, 4, g)
+    err_a = np.linalg.norm(C - exact)
+    err_s = np.linalg.norm(O.rtn_linear(A, cs, ss, g) - exact)
+    assert err_a < err_s
