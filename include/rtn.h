@@ -197,6 +197,29 @@ typedef struct {
 rtn_status rtn_layer_forward(const rtn_module* mods, int n_mods, void* dev_workspace,
                              size_t workspace_nbytes, void* stream);
 
+/* ---- Asymmetric variant (the remark after Eq. 1 in Section 2.2: an integer zero point Z is
+ * subtracted from the result of Int()).  The paper gives no more than that; this library
+ * takes, per group of g columns of a row:
+ *   [alpha, beta] = [min(min w, 0), max(max w, 0)]      (zero is always a level)
+ *   S = fp16((beta - alpha) / (2^b - 1)), difference and quotient rounded to fp32 first
+ *   Z = clamp(rne(alpha / S), -(2^b - 1), 0) + 2^(b-1)  (alpha goes to the lowest code)
+ *   q = clamp(rne(w / S) - Z, -2^(b-1), 2^(b-1) - 1)    (ties on w / S, before Z)
+ * and the dequantised weight is S * (q + Z).  S == 0 gives Z = 2^(b-1), q = -2^(b-1).
+ * Codes use the same packed layout (rtn_unpack returns q); dev_zeros is fp16 [N, K/g]
+ * holding the integers Z; sizes as for the scales (rtn_scales_nbytes).  Group sizes, shapes,
+ * alignment and error behaviour as for rtn_quantize / rtn_dequantize / rtn_linear.
+ * rtn_linear_asym always runs the small-batch kernel (16 rows at a time re-read the weights):
+ * for large M dequantise once with rtn_dequantize_asym and call rtn_gemm_fp16. */
+rtn_status rtn_quantize_asym(const void* dev_W, int64_t N, int64_t K, int bits, int group_size,
+                             void* dev_qweight, void* dev_scales, void* dev_zeros, void* stream);
+rtn_status rtn_dequantize_asym(const void* dev_qweight, const void* dev_scales, const void* dev_zeros,
+                               int64_t N, int64_t K, int bits, int group_size, void* dev_W_fp16,
+                               void* stream);
+/*   C[m, n] = fp16( sum_k A[m, k] * S[n, k/g] * (q[n, k] + Z[n, k/g]) ), fp32 accumulation. */
+rtn_status rtn_linear_asym(const void* dev_A, int64_t M, const void* dev_qweight, const void* dev_scales,
+                           const void* dev_zeros, int64_t N, int64_t K, int bits, int group_size,
+                           void* dev_C, void* dev_workspace, size_t workspace_nbytes, void* stream);
+
 /* Grouped call for modules that do not depend on one another: the experts of a
  * mixture-of-experts layer, each with its own weight matrix, its own rows of activations
  * and -- the per-expert precision that Section 6 (Discussion) proposes, with the Mixtral

@@ -74,6 +74,12 @@ def _load() -> C.CDLL:
     lib.rtn_linear_dense.argtypes = [vp, i64, vp, vp, i64, i64, ci, ci, vp, vp, sz, vp, sz, vp]
     lib.rtn_layer_forward.restype = ci
     lib.rtn_layer_forward.argtypes = [C.POINTER(rtn_module), ci, vp, sz, vp]
+    lib.rtn_quantize_asym.restype = ci
+    lib.rtn_quantize_asym.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp]
+    lib.rtn_dequantize_asym.restype = ci
+    lib.rtn_dequantize_asym.argtypes = [vp, vp, vp, i64, i64, ci, ci, vp, vp]
+    lib.rtn_linear_asym.restype = ci
+    lib.rtn_linear_asym.argtypes = [vp, i64, vp, vp, vp, i64, i64, ci, ci, vp, vp, sz, vp]
     lib.rtn_grouped_forward.restype = ci
     lib.rtn_grouped_forward.argtypes = [C.POINTER(rtn_module), ci, vp, sz, vp]
     lib.rtn_plan_bits.restype = ci
@@ -87,6 +93,7 @@ _lib = _load()
 EXPORTS = ["rtn_status_str", "rtn_layout_version", "rtn_qweight_nbytes", "rtn_scales_nbytes",
            "rtn_workspace_nbytes", "rtn_quantize", "rtn_quantize_host_staging_nbytes", "rtn_quantize_from_host", "rtn_linear", "rtn_linear_ex", "rtn_linear_query",
            "rtn_unpack", "rtn_dequantize", "rtn_gemm_fp16", "rtn_dense_weight_nbytes", "rtn_linear_dense",
+           "rtn_quantize_asym", "rtn_dequantize_asym", "rtn_linear_asym",
            "rtn_layer_forward", "rtn_grouped_forward", "rtn_plan_bits", "rtn_plan_effective_bits"]
 
 
@@ -277,6 +284,45 @@ class LayerPlan:
 
 def rtn_layer_forward(modules, workspace: torch.Tensor = None):
     LayerPlan(modules, workspace).run()
+
+
+def rtn_quantize_asym(W: torch.Tensor, bits: int, group_size: int):
+    """W fp16 [N, K] on the GPU -> (qweight uint8, scales fp16 [N, K/g], zeros fp16 [N, K/g]); weight = S (q + Z)."""
+    _dev_fp16(W, "W")
+    N, K = W.shape
+    G = 1 if group_size <= 0 else K // max(group_size, 1)
+    nq = _lib.rtn_qweight_nbytes(N, K, bits)
+    if nq == 0:
+        raise ValueError("unsupported shape or bits")
+    q = torch.empty(nq, dtype=torch.uint8, device=W.device)
+    s = torch.empty((N, max(G, 1)), dtype=torch.float16, device=W.device)
+    z = torch.empty((N, max(G, 1)), dtype=torch.float16, device=W.device)
+    _check(_lib.rtn_quantize_asym(W.data_ptr(), N, K, bits, group_size, q.data_ptr(), s.data_ptr(), z.data_ptr(),
+                                  _stream()), "rtn_quantize_asym")
+    return q, s, z
+
+
+def rtn_dequantize_asym(qweight, scales, zeros, N, K, bits, group_size, out=None):
+    if out is None:
+        out = torch.empty((N, K), dtype=torch.float16, device=qweight.device)
+    _check(_lib.rtn_dequantize_asym(qweight.data_ptr(), scales.data_ptr(), zeros.data_ptr(), N, K, bits, group_size,
+                                    out.data_ptr(), _stream()), "rtn_dequantize_asym")
+    return out
+
+
+def rtn_linear_asym(A, qweight, scales, zeros, bits, group_size, out=None, workspace=None):
+    _dev_fp16(A, "A")
+    M, K = A.shape
+    N = scales.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=A.device)
+    if workspace is None:
+        workspace = torch.empty(max(256, _lib.rtn_workspace_nbytes(M, N, K, bits, group_size)), dtype=torch.uint8,
+                                device=A.device)
+    _check(_lib.rtn_linear_asym(A.data_ptr(), M, qweight.data_ptr(), scales.data_ptr(), zeros.data_ptr(), N, K, bits,
+                                group_size, out.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()),
+           "rtn_linear_asym")
+    return out
 
 
 def rtn_grouped_forward(modules, workspace: torch.Tensor = None):

@@ -476,6 +476,59 @@ rtn_status rtn_layer_forward(const rtn_module* mods, int n_mods, void* dev_works
     return RTN_OK;
 }
 
+rtn_status rtn_quantize_asym(const void* dev_W, int64_t N, int64_t K, int bits, int group_size,
+                             void* dev_qweight, void* dev_scales, void* dev_zeros, void* stream) {
+    if (!dev_W || !dev_qweight || !dev_scales || !dev_zeros) return RTN_ERR_NULL;
+    int64_t g;
+    rtn_status st = check_problem(N, K, bits, group_size, &g);
+    if (st != RTN_OK) return st;
+    if (!aligned16(dev_W) || !aligned16(dev_qweight) || !aligned16(dev_scales) || !aligned16(dev_zeros))
+        return RTN_ERR_ALIGN;
+    hipError_t e = rtn::launch_quantize_asym(dev_W, N, K, bits, g, dev_qweight, dev_scales, dev_zeros,
+                                             static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RTN_OK : RTN_ERR_HIP;
+}
+
+rtn_status rtn_dequantize_asym(const void* dev_qweight, const void* dev_scales, const void* dev_zeros,
+                               int64_t N, int64_t K, int bits, int group_size, void* dev_W_fp16, void* stream) {
+    if (!dev_qweight || !dev_scales || !dev_zeros || !dev_W_fp16) return RTN_ERR_NULL;
+    int64_t g;
+    rtn_status st = check_problem(N, K, bits, group_size, &g);
+    if (st != RTN_OK) return st;
+    if (!aligned16(dev_qweight) || !aligned16(dev_scales) || !aligned16(dev_zeros) || !aligned16(dev_W_fp16))
+        return RTN_ERR_ALIGN;
+    hipError_t e = rtn::launch_unpack(dev_qweight, dev_scales, N, K, bits, g, true, dev_W_fp16,
+                                      static_cast<hipStream_t>(stream), dev_zeros);
+    return e == hipSuccess ? RTN_OK : RTN_ERR_HIP;
+}
+
+rtn_status rtn_linear_asym(const void* dev_A, int64_t M, const void* dev_qweight, const void* dev_scales,
+                           const void* dev_zeros, int64_t N, int64_t K, int bits, int group_size,
+                           void* dev_C, void* dev_workspace, size_t workspace_nbytes, void* stream) {
+    if (!dev_A || !dev_qweight || !dev_scales || !dev_zeros || !dev_C) return RTN_ERR_NULL;
+    int64_t g;
+    rtn_status st = check_problem(N, K, bits, group_size, &g);
+    if (st != RTN_OK) return st;
+    if (M <= 0 || M > (1 << 20)) return RTN_ERR_SHAPE;
+    if (!aligned16(dev_A) || !aligned16(dev_qweight) || !aligned16(dev_scales) || !aligned16(dev_zeros) ||
+        !aligned16(dev_C) || !aligned16(dev_workspace))
+        return RTN_ERR_ALIGN;
+    LinearArgs a;
+    a.A = dev_A; a.qweight = dev_qweight; a.scales = dev_scales; a.C = dev_C; a.zeros = dev_zeros;
+    a.workspace = static_cast<float*>(dev_workspace);
+    a.M = M; a.N = N; a.K = K; a.g = g; a.bits = bits;
+    // the small-batch kernel, 16 rows per workgroup, planned as for min(M, 16) rows
+    LinearPlan h = auto_plan(M < 16 ? M : 16, N, K, bits, g, (size_t)device_max_lds(), 1);
+    rtn_linear_cfg cfg;
+    cfg.path = 1; cfg.prefetch = 1; cfg.waves_n = h.waves_n; cfg.waves_k = h.waves_k;
+    cfg.split_k = M <= 16 ? h.split_k : 1; cfg.m_rows16 = 1; cfg.n_tiles16 = 1;
+    LinearPlan p;
+    st = resolve_plan(a, &cfg, workspace_nbytes, &p);
+    if (st != RTN_OK) return st;
+    hipError_t e = rtn::launch_linear(a, p, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RTN_OK : RTN_ERR_HIP;
+}
+
 rtn_status rtn_grouped_forward(const rtn_module* mods, int n_mods, void* dev_workspace, size_t workspace_nbytes,
                                void* stream) {
     if (!mods) return RTN_ERR_NULL;

@@ -61,31 +61,39 @@ __device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t m
 // values one lane feeds to one 16x16x32 MFMA: and_or puts two nibbles under the 1024 exponent
 // (1024 + n, or 1024 + 16 n for a nibble sitting 4 bits up), one packed add / fma removes the
 // offset exactly.  9 vector ops per 8 weights.
-__device__ __forceinline__ half8_t unpack_word4(uint32_t w, uint32_t magic_v) {
-    const half2_t k1032 = {(half_t)1032.0f, (half_t)1032.0f};
+__device__ __forceinline__ half8_t unpack_word4_off(uint32_t w, uint32_t magic_v, half2_t sub_lo, half2_t add_hi) {
     const half2_t k16th = {(half_t)0.0625f, (half_t)0.0625f};
-    const half2_t k72 = {(half_t)-72.0f, (half_t)-72.0f};
     const uint32_t w8 = w >> 8;
     Half8Words r;
-    r.h2[0] = as_half2(and_or(w, 0x000F000Fu, magic_v)) - k1032;                               // nibbles 0,4
-    r.h2[1] = __builtin_elementwise_fma(as_half2(and_or(w, 0x00F000F0u, magic_v)), k16th, k72);   // nibbles 1,5
-    r.h2[2] = as_half2(and_or(w8, 0x000F000Fu, magic_v)) - k1032;                              // nibbles 2,6
-    r.h2[3] = __builtin_elementwise_fma(as_half2(and_or(w8, 0x00F000F0u, magic_v)), k16th, k72);  // nibbles 3,7
+    r.h2[0] = as_half2(and_or(w, 0x000F000Fu, magic_v)) - sub_lo;                                 // nibbles 0,4
+    r.h2[1] = __builtin_elementwise_fma(as_half2(and_or(w, 0x00F000F0u, magic_v)), k16th, add_hi);   // nibbles 1,5
+    r.h2[2] = as_half2(and_or(w8, 0x000F000Fu, magic_v)) - sub_lo;                                // nibbles 2,6
+    r.h2[3] = __builtin_elementwise_fma(as_half2(and_or(w8, 0x00F000F0u, magic_v)), k16th, add_hi);  // nibbles 3,7
     return r.v;
+}
+
+__device__ __forceinline__ half8_t unpack_word4(uint32_t w, uint32_t magic_v) {
+    const half2_t k1032 = {(half_t)1032.0f, (half_t)1032.0f};
+    const half2_t k72 = {(half_t)-72.0f, (half_t)-72.0f};
+    return unpack_word4_off(w, magic_v, k1032, k72);
 }
 
 // Two 32-bit words of 8-bit codes (offset binary, natural byte order) -> 8 fp16 values.
 // A byte permute places each byte under a 0x64 exponent byte (1024 + byte), one packed add
 // removes 1024 + 128.  8 vector ops per 8 weights.
-__device__ __forceinline__ half8_t unpack_words8(uint32_t w0, uint32_t w1) {
-    const half2_t k1152 = {(half_t)1152.0f, (half_t)1152.0f};
+__device__ __forceinline__ half8_t unpack_words8_off(uint32_t w0, uint32_t w1, half2_t sub) {
     const uint32_t E = 0x64646464u;
     Half8Words r;
-    r.h2[0] = as_half2(__builtin_amdgcn_perm(E, w0, 0x04010400u)) - k1152;
-    r.h2[1] = as_half2(__builtin_amdgcn_perm(E, w0, 0x04030402u)) - k1152;
-    r.h2[2] = as_half2(__builtin_amdgcn_perm(E, w1, 0x04010400u)) - k1152;
-    r.h2[3] = as_half2(__builtin_amdgcn_perm(E, w1, 0x04030402u)) - k1152;
+    r.h2[0] = as_half2(__builtin_amdgcn_perm(E, w0, 0x04010400u)) - sub;
+    r.h2[1] = as_half2(__builtin_amdgcn_perm(E, w0, 0x04030402u)) - sub;
+    r.h2[2] = as_half2(__builtin_amdgcn_perm(E, w1, 0x04010400u)) - sub;
+    r.h2[3] = as_half2(__builtin_amdgcn_perm(E, w1, 0x04030402u)) - sub;
     return r.v;
+}
+
+__device__ __forceinline__ half8_t unpack_words8(uint32_t w0, uint32_t w1) {
+    const half2_t k1152 = {(half_t)1152.0f, (half_t)1152.0f};
+    return unpack_words8_off(w0, w1, k1152);
 }
 
 // MFMA operand number i (0 .. MFMA_PER_TILE-1) of a 16-byte tile chunk.
@@ -95,6 +103,19 @@ __device__ __forceinline__ half8_t unpack_operand(const u32x4_t& chunk, int i, u
         return unpack_word4(chunk[i], magic_v);
     } else {
         return unpack_words8(chunk[2 * i], chunk[2 * i + 1]);
+    }
+}
+
+// The same with a per-lane integer zero point Z (asymmetric variant): the operand holds q + Z, exact for |Z| <= 2^(BITS-1)
+// (1024 + 2^(BITS-1) - Z and 64 + 2^(BITS-1) - Z are fp16 integers, so the subtraction is still exact).
+template <int BITS>
+__device__ __forceinline__ half8_t unpack_operand_zp(const u32x4_t& chunk, int i, uint32_t magic_v, float z) {
+    if constexpr (BITS == 4) {
+        const half_t lo = (half_t)(1032.0f - z), hi = (half_t)(z - 72.0f);
+        return unpack_word4_off(chunk[i], magic_v, (half2_t){lo, lo}, (half2_t){hi, hi});
+    } else {
+        const half_t lo = (half_t)(1152.0f - z);
+        return unpack_words8_off(chunk[2 * i], chunk[2 * i + 1], (half2_t){lo, lo});
     }
 }
 

@@ -28,12 +28,17 @@ struct LinearArgs {
     float* workspace;
     int64_t M, N, K, g;
     int bits;
+    const void* zeros = nullptr;   // fp16 [N, K/g] integer zero points (asymmetric variant; skinny kernel only) or null
 };
 
 hipError_t launch_quantize(const void* W, int64_t N, int64_t K, int bits, int64_t g, float divisor,
                            void* qweight, void* scales, hipStream_t st);
+// Asymmetric variant: codes, fp16 scales and fp16 integer zero points Z, dequantised weight S (q + Z).
+hipError_t launch_quantize_asym(const void* W, int64_t N, int64_t K, int bits, int64_t g, void* qweight, void* scales,
+                                void* zeros, hipStream_t st);
+// zeros: null for the symmetric variant.
 hipError_t launch_unpack(const void* qweight, const void* scales, int64_t N, int64_t K, int bits, int64_t g,
-                         bool dequant, void* out, hipStream_t st);
+                         bool dequant, void* out, hipStream_t st, const void* zeros = nullptr);
 hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t st);
 // n independent problems with resolved plans: compatible skinny-kernel launches are merged into grouped launches.
 hipError_t launch_linear_grouped(const LinearArgs* args, const LinearPlan* plans, int n, hipStream_t st);

@@ -48,6 +48,7 @@ struct SkinnyParams {
     const half_t* A;
     const uint8_t* qw;
     const half_t* scales;
+    const half_t* zeros;   // asymmetric variant only (ZP)
     half_t* C;
     float* ws;
     int M, N, K;
@@ -127,7 +128,7 @@ __device__ __forceinline__ typename ScaleVec<NGC>::raw_t load_scales(__amdgpu_bu
 // cores -- the wavefront-reduction GEMV the skinny MFMA path is measured against.
 // The body takes the workgroup's coordinates as arguments so that one launch can also serve several independent
 // problems (grouped launch below).
-template <int BITS, int NGC, int NB, bool MULTI, int MB, bool DOT>
+template <int BITS, int NGC, int NB, bool MULTI, int MB, bool DOT, bool ZP = false>
 __device__ __forceinline__ void skinny_body(const SkinnyParams& p, const int bx, const int by, const int bz) {
     typedef Geom<BITS> GM;
     typedef typename ScaleVec<NGC>::raw_t sraw_t;
@@ -153,6 +154,7 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& p, const int bx,
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.qw), 0, p.qw_bytes, kBufferFlags);
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<half_t*>(p.scales), 0, p.sc_bytes, kBufferFlags);
     const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<half_t*>(p.A), 0, p.a_bytes, kBufferFlags);
+    const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc(const_cast<half_t*>(ZP ? p.zeros : p.scales), 0, p.sc_bytes, kBufferFlags);
     const uint32_t w_lane = (uint32_t)nt * (uint32_t)p.KL * 1024u + lane * 16;
     const uint32_t s_lane = ((uint32_t)nt * 16 + nl) * (uint32_t)p.G * 2u;
     const uint32_t magic = fp16_magic_vgpr();
@@ -191,12 +193,16 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& p, const int bx,
     // ---- weight / scale prefetch: NB chunks in flight --------------------------------------------
     u32x4_t wbuf[NB][kChunkTiles];
     sraw_t sbuf[NB];
+    sraw_t zbuf[ZP ? NB : 1];             // zero points, same shape and offsets as the scales
+    (void)zbuf;
+    (void)rz;
     auto fetch = [&](int j, int ci) {
         const bool ok = nt_ok && ci < cw1;                            // wave-uniform
         const uint32_t si = (NGC > 1) ? (uint32_t)ci * NGC : (p.cpg_inv == 0 ? (uint32_t)ci : __umulhi((uint32_t)ci, p.cpg_inv));
         const uint32_t so = ok ? s_lane + si * 2u : kOutOfRange;
         const uint32_t wo = ok ? w_lane + (uint32_t)ci * (kChunkTiles * 1024u) : kOutOfRange;
         sbuf[j] = load_scales<NGC>(rs, so);                           // scales first: never the last to arrive
+        if constexpr (ZP) zbuf[j] = load_scales<NGC>(rz, so);
 #pragma unroll
         for (int c = 0; c < kChunkTiles; ++c)
             wbuf[j][c] = __builtin_amdgcn_raw_buffer_load_b128(rw, wo + c * 1024, 0, 2 /* nt: read-once stream */);
@@ -263,10 +269,15 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& p, const int bx,
                             float4_t part[MB];
 #pragma unroll
                             for (int b = 0; b < MB; ++b) part[b] = (float4_t){0.f, 0.f, 0.f, 0.f};
+                            float zp = 0.0f;
+                            if constexpr (ZP) zp = scale_at<NGC>(zbuf[j], gi);
+                            (void)zp;
 #pragma unroll
                             for (int q = 0; q < MPG; ++q) {
                                 const int i = gi * MPG + q;
-                                const half8_t bw = unpack_operand<BITS>(wbuf[j][i / GM::MPT], i % GM::MPT, magic);
+                                half8_t bw;
+                                if constexpr (ZP) bw = unpack_operand_zp<BITS>(wbuf[j][i / GM::MPT], i % GM::MPT, magic, zp);
+                                else bw = unpack_operand<BITS>(wbuf[j][i / GM::MPT], i % GM::MPT, magic);
 #pragma unroll
                                 for (int b = 0; b < MB; ++b) {
                                     const half8_t a = *reinterpret_cast<const half8_t*>(arow[b] + aoff + i * 32);
@@ -343,9 +354,9 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& p, const int bx,
     }
 }
 
-template <int BITS, int NGC, int NB, bool MULTI, int MB, bool DOT = false>
+template <int BITS, int NGC, int NB, bool MULTI, int MB, bool DOT = false, bool ZP = false>
 __global__ __launch_bounds__(1024) void skinny_mfma_kernel(const SkinnyParams p) {
-    skinny_body<BITS, NGC, NB, MULTI, MB, DOT>(p, blockIdx.x, blockIdx.y, blockIdx.z);
+    skinny_body<BITS, NGC, NB, MULTI, MB, DOT, ZP>(p, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 // Grouped launch: up to kMaxGroup independent problems of the same precision, group size and workgroup shape
@@ -508,6 +519,34 @@ static hipError_t launch_skinny(const SkinnyParams& sp, int ngc, int nb, bool mu
                  : launch_skinny_ngc<BITS, 4, false, 1>(sp, ngc, grid, block, lds, st);
 }
 
+// Asymmetric variant (per-group zero points): one chunk in flight, one 16-row block per wavefront.
+template <int BITS, int NGC>
+static void launch_skinny_zp_inst(const SkinnyParams& sp, bool multi, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
+    if constexpr (NGC <= Geom<BITS>::NM) {
+        if (multi) {
+            allow_large_lds(skinny_mfma_kernel<BITS, NGC, 1, true, 1, false, true>);
+            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, NGC, 1, true, 1, false, true>), grid, block, lds, st, sp);
+        } else {
+            allow_large_lds(skinny_mfma_kernel<BITS, NGC, 1, false, 1, false, true>);
+            hipLaunchKernelGGL((skinny_mfma_kernel<BITS, NGC, 1, false, 1, false, true>), grid, block, lds, st, sp);
+        }
+    }
+}
+
+template <int BITS>
+static hipError_t launch_skinny_zp(const SkinnyParams& sp, int ngc, bool multi, dim3 grid, dim3 block, size_t lds,
+                                   hipStream_t st) {
+    switch (ngc) {
+        case 1: launch_skinny_zp_inst<BITS, 1>(sp, multi, grid, block, lds, st); break;
+        case 2: launch_skinny_zp_inst<BITS, 2>(sp, multi, grid, block, lds, st); break;
+        case 4: launch_skinny_zp_inst<BITS, 4>(sp, multi, grid, block, lds, st); break;
+        case 8: launch_skinny_zp_inst<BITS, 8>(sp, multi, grid, block, lds, st); break;
+        case 16: launch_skinny_zp_inst<BITS, 16>(sp, multi, grid, block, lds, st); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 // Everything a skinny-kernel launch needs, derived from the problem and its plan.
 struct SkinnyLaunch {
     SkinnyParams sp;
@@ -525,6 +564,7 @@ static SkinnyLaunch prepare_skinny(const LinearArgs& a, const LinearPlan& p) {
     sp.A = static_cast<const half_t*>(a.A);
     sp.qw = static_cast<const uint8_t*>(a.qweight);
     sp.scales = static_cast<const half_t*>(a.scales);
+    sp.zeros = static_cast<const half_t*>(a.zeros);
     sp.C = static_cast<half_t*>(a.C);
     sp.ws = a.workspace;
     sp.M = (int)a.M; sp.N = (int)a.N; sp.K = (int)a.K;
@@ -564,11 +604,16 @@ static SkinnyLaunch prepare_skinny(const LinearArgs& a, const LinearPlan& p) {
 }
 
 hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t st) {
+    if (a.zeros && p.path != 1) return hipErrorInvalidValue;          // zero points: skinny kernel only
     if (p.path == 3) return launch_linear_wide(a, p, st);
     if (p.path == 4) return launch_linear_tile(a, p, st);
     const SkinnyLaunch L = prepare_skinny(a, p);
     hipError_t e;
-    if (p.path == 2) {
+    if (a.zeros) {
+        if (p.path != 1 || p.prefetch != 1 || p.m_rows16 != 1) return hipErrorInvalidValue;
+        e = (a.bits == 4) ? launch_skinny_zp<4>(L.sp, L.ngc, L.multi, L.grid, L.block, L.lds, st)
+                          : launch_skinny_zp<8>(L.sp, L.ngc, L.multi, L.grid, L.block, L.lds, st);
+    } else if (p.path == 2) {
         e = (a.bits == 4) ? launch_dot<4>(L.sp, L.ngc, L.grid, L.block, L.lds, st) : launch_dot<8>(L.sp, L.ngc, L.grid, L.block, L.lds, st);
     } else {
         e = (a.bits == 4) ? launch_skinny<4>(L.sp, L.ngc, p.prefetch, L.multi, p.m_rows16, L.grid, L.block, L.lds, st)

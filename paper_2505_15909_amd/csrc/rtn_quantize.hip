@@ -275,7 +275,8 @@ __global__ __launch_bounds__(1024) void quantize_resident_group_kernel(
 // ---------------------------------------------------------------------------------------
 template <int BITS, bool DEQUANT>
 __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t* __restrict__ qweight,
-                                                     const half_t* __restrict__ scales, void* __restrict__ out,
+                                                     const half_t* __restrict__ scales,
+                                                     const half_t* __restrict__ zeros, void* __restrict__ out,
                                                      int64_t N, int64_t K, int64_t g) {
     constexpr int TK = Layout<BITS>::TK;
     constexpr int MPT = Layout<BITS>::MFMA_PER_TILE;
@@ -295,9 +296,10 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t* __restrict__
         const int64_t k = kt * TK + i * 32 + kq * 8;
         if constexpr (DEQUANT) {
             const half_t s = scales[n * (K / g) + k / g];
+            const float z = zeros ? (float)zeros[n * (K / g) + k / g] : 0.0f;     // asymmetric variant: S (q + Z)
             half8_t o;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = (half_t)((float)v[e] * (float)s);
+            for (int e = 0; e < 8; ++e) o[e] = (half_t)(((float)v[e] + z) * (float)s);   // exact sum and product, one rounding
             *reinterpret_cast<half8_t*>(reinterpret_cast<half_t*>(out) + n * K + k) = o;
         } else {
             u32x2_t o = {0u, 0u};
@@ -356,18 +358,220 @@ hipError_t launch_quantize(const void* W, int64_t N, int64_t K, int bits, int64_
                      : launch_quantize_bits<8>(W, N, K, g, divisor, qweight, scales, st);
 }
 
+// ---------------------------------------------------------------------------------------
+// Asymmetric variant (the remark after Eq. 1 in Section 2.2: an integer zero point Z is subtracted from the
+// result of Int()).  Per group: [alpha, beta] = [min(min w, 0), max(max w, 0)];
+//   S = fp16( fp32_div( fp32(beta - alpha), 2^b - 1 ) )
+//   T = clamp( rint( fp32_div(alpha, S) ), -(2^b - 1), 0 ),   Z = T + 2^(b-1)   (stored as fp16, an exact integer)
+//   stored code u = clamp( rint(w / S) - T, 0, 2^b - 1 )      (= q + 2^(b-1) with q = clamp(rint(w / S) - Z))
+// and the dequantised weight is S (q + Z) = S (u + T).  rint(w / S) comes from the same two-step rounding as in the
+// symmetric kernels, y = fma(w, r, C), z = rint(y), now with C = 1536 and WITHOUT the zero point inside C: the tie
+// rule applies to w / S, and C must stay even.  |w / S| < 384 (2^b - 1 = 255 levels, times up to 1.5 when S is a
+// subnormal fp16 and rounds coarsely), so y lies in (1152, 1920), where fp32 values are the multiples of 2^-13;
+// |w r - w / S| <= 384 * 2^-24 < 2^-15 is less than half that step and less than the distance (> 2^-13 - 2^-15) of
+// any non-tie quotient from a half-integer, so both cases of the argument at the top of this file carry over.
+// alpha / S needs no such care: it is one IEEE division per group, its quotient is either exactly a half-integer
+// (representable, returned exactly) or further from one than fp32's spacing there.
+// The packing sums stay below 2^24 ((1536 + 255) * 4369 < 2^23).
+//
+// One wavefront per unit.  SUB == 1: a unit is one group of g >= TK columns of a 16-row tile-row, read twice
+// (second pass from cache).  SUB > 1: a unit is one tile holding SUB groups of TK / SUB columns.
+// ---------------------------------------------------------------------------------------
+struct AsymGroup {
+    float r, lo, hi;          // reciprocal scale, clamp bounds C + T and C + T + levels
+    uint32_t kconst;          // what the C + T of every code adds to a packed word
+};
+
+__device__ __forceinline__ uint32_t pk_min(uint32_t m, uint32_t x) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(half2_t, m), __builtin_bit_cast(half2_t, x)));
+}
+__device__ __forceinline__ uint32_t pk_max(uint32_t m, uint32_t x) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(half2_t, m), __builtin_bit_cast(half2_t, x)));
+}
+
+// Row-wise (alpha, beta) of a lane's running packed min / max: across the pair, then across the four lanes of a row.
+__device__ __forceinline__ void row_range(uint32_t mn2, uint32_t mx2, float* alpha, float* beta) {
+    const half2_t a = __builtin_bit_cast(half2_t, mn2), b = __builtin_bit_cast(half2_t, mx2);
+    float lo = fminf(fminf((float)a[0], (float)a[1]), 0.0f), hi = fmaxf(fmaxf((float)b[0], (float)b[1]), 0.0f);
+    lo = fminf(lo, __shfl_xor(lo, 16));
+    hi = fmaxf(hi, __shfl_xor(hi, 16));
+    lo = fminf(lo, __shfl_xor(lo, 32));
+    hi = fmaxf(hi, __shfl_xor(hi, 32));
+    *alpha = lo;
+    *beta = hi;
+}
+
+template <int BITS>
+__device__ __forceinline__ AsymGroup asym_group(float alpha, float beta, half_t* s_out, half_t* z_out) {
+    constexpr float LEVELS = (float)((1 << BITS) - 1);
+    constexpr float C = 1536.0f;
+    const float width = beta - alpha;                                // one fp32 rounding
+    const half_t s16 = (half_t)(width / LEVELS);                     // IEEE divide, then fp16 RNE
+    const float s = (float)s16;
+    float t = (s == 0.0f) ? 0.0f : rintf(alpha / s);                 // IEEE divide
+    t = fminf(fmaxf(t, -LEVELS), 0.0f);
+    AsymGroup gp;
+    gp.r = group_reciprocal(s);
+    gp.lo = C + t;
+    gp.hi = C + t + LEVELS;
+    const uint32_t base = (uint32_t)(C + t);
+    gp.kconst = (BITS == 4) ? base * 0x1111u * 0x10001u : base * 0x101u * 0x10001u;     // modulo 2^32
+    *s_out = s16;
+    *z_out = (half_t)(t + (float)(1 << (BITS - 1)));
+    return gp;
+}
+
+template <int BITS>
+__device__ __forceinline__ void quantize_octet_asym(const u32x4_t& raw, const AsymGroup& gp, uint32_t* out) {
+    Half8Words h;
+    h.v = __builtin_bit_cast(half8_t, raw);
+    float z[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        z[e] = __builtin_amdgcn_fmed3f(rintf(fmaf((float)h.v[e], gp.r, 1536.0f)), gp.lo, gp.hi);
+    if constexpr (BITS == 4) {
+        const float lo = fmaf(z[6], 4096.0f, fmaf(z[4], 256.0f, fmaf(z[2], 16.0f, z[0])));
+        const float hi = fmaf(z[7], 4096.0f, fmaf(z[5], 256.0f, fmaf(z[3], 16.0f, z[1])));
+        out[0] = (((uint32_t)hi << 16) + (uint32_t)lo) - gp.kconst;
+    } else {
+        const float a = fmaf(z[1], 256.0f, z[0]), b = fmaf(z[3], 256.0f, z[2]);
+        const float c = fmaf(z[5], 256.0f, z[4]), d = fmaf(z[7], 256.0f, z[6]);
+        out[0] = (((uint32_t)b << 16) + (uint32_t)a) - gp.kconst;
+        out[1] = (((uint32_t)d << 16) + (uint32_t)c) - gp.kconst;
+    }
+}
+
+template <int BITS, int SUB>
+__global__ __launch_bounds__(256) void quantize_asym_kernel(
+    const half_t* __restrict__ W, uint8_t* __restrict__ qweight, half_t* __restrict__ scales,
+    half_t* __restrict__ zeros, int64_t N, int64_t K, int64_t g, int64_t units) {
+    constexpr int TK = Layout<BITS>::TK;
+    constexpr int OPT = TK / 32;                          // octets (16-byte loads) per lane per tile
+    constexpr uint32_t kPosInf = 0x7C007C00u, kNegInf = 0xFC00FC00u;
+    const int lane = threadIdx.x & 63;
+    const int nl = lane & 15, kq = lane >> 4;
+    const int64_t KT = K / TK, G = K / g;
+    const int64_t U = (SUB == 1) ? G : KT;                // units per tile-row
+    const int tiles = (SUB == 1) ? (int)(g / TK) : 1;     // tiles per unit
+    const int64_t wave0 = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * (blockDim.x >> 6);
+    for (int64_t u = wave0; u < units; u += nwaves) {
+        const int64_t nt = u / U, j = u % U;
+        const int64_t n = nt * 16 + nl;
+        const int64_t kt0 = j * tiles;                    // first tile of the unit
+        const half_t* src = W + n * K + kt0 * TK + kq * 8;
+        AsymGroup gp[SUB];
+        if constexpr (SUB == 1) {
+            uint32_t mn = kPosInf, mx = kNegInf;
+            for (int t = 0; t < tiles * OPT; ++t) {
+                const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(src + t * 32);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    mn = pk_min(mn, raw[i]);
+                    mx = pk_max(mx, raw[i]);
+                }
+            }
+            float alpha, beta;
+            row_range(mn, mx, &alpha, &beta);
+            half_t s16, z16;
+            gp[0] = asym_group<BITS>(alpha, beta, &s16, &z16);
+            if (kq == 0) {
+                scales[n * G + j] = s16;
+                zeros[n * G + j] = z16;
+            }
+        } else {
+            constexpr int OPS = OPT / SUB;                // octets per lane per group
+#pragma unroll
+            for (int sg = 0; sg < SUB; ++sg) {
+                uint32_t mn = kPosInf, mx = kNegInf;
+#pragma unroll
+                for (int t = 0; t < OPS; ++t) {
+                    const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(src + (sg * OPS + t) * 32);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        mn = pk_min(mn, raw[i]);
+                        mx = pk_max(mx, raw[i]);
+                    }
+                }
+                float alpha, beta;
+                row_range(mn, mx, &alpha, &beta);
+                half_t s16, z16;
+                gp[sg] = asym_group<BITS>(alpha, beta, &s16, &z16);
+                if (kq == 0) {
+                    scales[n * G + j * SUB + sg] = s16;
+                    zeros[n * G + j * SUB + sg] = z16;
+                }
+            }
+        }
+        for (int tp = 0; tp < tiles; ++tp) {
+            u32x4_t o;
+            if constexpr (BITS == 4) {
+#pragma unroll
+                for (int t = 0; t < OPT; ++t) {
+                    const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(src + tp * TK + t * 32);
+                    uint32_t wd[1];
+                    quantize_octet_asym<BITS>(raw, gp[SUB == 1 ? 0 : t / (OPT / SUB)], wd);
+                    o[t] = wd[0];
+                }
+            } else {
+#pragma unroll
+                for (int t = 0; t < OPT; ++t) {
+                    const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(src + tp * TK + t * 32);
+                    uint32_t wd[2];
+                    quantize_octet_asym<BITS>(raw, gp[SUB == 1 ? 0 : t / (OPT / SUB)], wd);
+                    o[2 * t] = wd[0];
+                    o[2 * t + 1] = wd[1];
+                }
+            }
+            *reinterpret_cast<u32x4_t*>(qweight + ((nt * KT + kt0 + tp) * 64 + lane) * 16) = o;
+        }
+    }
+}
+
+template <int BITS>
+static hipError_t launch_quantize_asym_bits(const void* W, int64_t N, int64_t K, int64_t g, void* qweight, void* scales,
+                                            void* zeros, hipStream_t st) {
+    constexpr int TK = Layout<BITS>::TK;
+    const half_t* w = static_cast<const half_t*>(W);
+    uint8_t* q = static_cast<uint8_t*>(qweight);
+    half_t* s = static_cast<half_t*>(scales);
+    half_t* z = static_cast<half_t*>(zeros);
+    const int64_t units = (g < TK) ? (N / 16) * (K / TK) : (N / 16) * (K / g);
+    int64_t blocks = (units + 3) / 4;
+    if (blocks > 256 * 64) blocks = 256 * 64;             // grid-stride beyond this
+    dim3 grid((unsigned)blocks), block(256);
+    if (g >= TK) {
+        hipLaunchKernelGGL((quantize_asym_kernel<BITS, 1>), grid, block, 0, st, w, q, s, z, N, K, g, units);
+    } else if (TK / g == 2) {
+        hipLaunchKernelGGL((quantize_asym_kernel<BITS, 2>), grid, block, 0, st, w, q, s, z, N, K, g, units);
+    } else if constexpr (BITS == 4) {
+        if (TK / g != 4) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((quantize_asym_kernel<BITS, 4>), grid, block, 0, st, w, q, s, z, N, K, g, units);
+    } else {
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_asym(const void* W, int64_t N, int64_t K, int bits, int64_t g, void* qweight, void* scales,
+                                void* zeros, hipStream_t st) {
+    return bits == 4 ? launch_quantize_asym_bits<4>(W, N, K, g, qweight, scales, zeros, st)
+                     : launch_quantize_asym_bits<8>(W, N, K, g, qweight, scales, zeros, st);
+}
+
 hipError_t launch_unpack(const void* qweight, const void* scales, int64_t N, int64_t K, int bits, int64_t g,
-                         bool dequant, void* out, hipStream_t st) {
+                         bool dequant, void* out, hipStream_t st, const void* zeros) {
     const int64_t chunks = N * K * bits / 8 / 16;
     dim3 grid((unsigned)((chunks + 255) / 256)), block(256);
     const uint8_t* q = static_cast<const uint8_t*>(qweight);
     const half_t* s = static_cast<const half_t*>(scales);
+    const half_t* z = static_cast<const half_t*>(zeros);
     if (bits == 4) {
-        if (dequant) hipLaunchKernelGGL((unpack_kernel<4, true>), grid, block, 0, st, q, s, out, N, K, g);
-        else hipLaunchKernelGGL((unpack_kernel<4, false>), grid, block, 0, st, q, s, out, N, K, g);
+        if (dequant) hipLaunchKernelGGL((unpack_kernel<4, true>), grid, block, 0, st, q, s, z, out, N, K, g);
+        else hipLaunchKernelGGL((unpack_kernel<4, false>), grid, block, 0, st, q, s, z, out, N, K, g);
     } else {
-        if (dequant) hipLaunchKernelGGL((unpack_kernel<8, true>), grid, block, 0, st, q, s, out, N, K, g);
-        else hipLaunchKernelGGL((unpack_kernel<8, false>), grid, block, 0, st, q, s, out, N, K, g);
+        if (dequant) hipLaunchKernelGGL((unpack_kernel<8, true>), grid, block, 0, st, q, s, z, out, N, K, g);
+        else hipLaunchKernelGGL((unpack_kernel<8, false>), grid, block, 0, st, q, s, z, out, N, K, g);
     }
     return hipGetLastError();
 }

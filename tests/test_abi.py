@@ -102,6 +102,15 @@ def test_argument_validation_happens_before_any_launch():
     assert lib.rtn_dequantize(FAKE, FAKE, 64, 512, 4, 100, FAKE, None) == 3
     assert lib.rtn_layer_forward(None, 1, FAKE, 256, None) == 1
     assert lib.rtn_grouped_forward(None, 1, FAKE, 256, None) == 1
+    # asymmetric variant: same validation, plus the zero-point array
+    assert lib.rtn_quantize_asym(FAKE, 64, 512, 4, 128, FAKE, FAKE, None, None) == 1
+    assert lib.rtn_quantize_asym(FAKE, 64, 512, 5, 128, FAKE, FAKE, FAKE, None) == 2
+    assert lib.rtn_quantize_asym(FAKE, 64, 512, 4, 100, FAKE, FAKE, FAKE, None) == 3
+    assert lib.rtn_quantize_asym(FAKE, 60, 512, 4, 128, FAKE, FAKE, FAKE, None) == 4
+    assert lib.rtn_quantize_asym(FAKE, 64, 512, 4, 128, FAKE, FAKE, FAKE + 8, None) == 5
+    assert lib.rtn_dequantize_asym(FAKE, FAKE, None, 64, 512, 4, 128, FAKE, None) == 1
+    assert lib.rtn_linear_asym(FAKE, 1, FAKE, FAKE, None, 64, 512, 4, 128, FAKE, FAKE, 256, None) == 1
+    assert lib.rtn_linear_asym(FAKE, 0, FAKE, FAKE, FAKE, 64, 512, 4, 128, FAKE, FAKE, 256, None) == 4
 
 
 def test_bad_valid_combination_is_not_launched_without_gpu():

@@ -545,3 +545,105 @@ def test_selective_precision_layer(rtn):
         torch.cuda.synchronize()
         for m, ref, mod in zip(mods, refs, shapes):
             H.assert_linear_close(_to_np(m["C"]), ref, f"layer {mod} M={M}")
+
+
+# ----------------------------------------------------------------------------------------
+# asymmetric variant (integer zero points; the remark after Eq. 1 in Section 2.2)
+# ----------------------------------------------------------------------------------------
+def _asym_both(rtn, W_t, bits, g):
+    qw, sc, zp = rtn.rtn_quantize_asym(W_t, bits, g)
+    torch.cuda.synchronize()
+    W = _to_np(W_t)
+    gg = W.shape[1] if g <= 0 else g
+    codes, scales, zeros = O.rtn_quantize_asym(W, bits, gg)
+    return qw, sc, zp, codes, scales, zeros, gg
+
+
+def _assert_asym_equal(rtn, qw, sc, zp, codes, scales, zeros, bits):
+    N, K = codes.shape
+    assert np.array_equal(_to_np(sc).view(np.uint16), scales.view(np.uint16))
+    assert np.array_equal(_to_np(zp).astype(np.float64), zeros.astype(np.float64))
+    assert np.array_equal(_to_np(qw), O.pack_gfx950(codes, bits))
+    assert np.array_equal(_to_np(rtn.rtn_unpack(qw, N, K, bits)), codes)
+
+
+@pytest.mark.parametrize("bits,g", [(4, 32), (4, 64), (4, 128), (4, 256), (4, 1024), (4, 0), (8, 32), (8, 64), (8, 128),
+                                     (8, 512), (8, 0)])
+@pytest.mark.parametrize("N,K,shift", [(80, 2048, 0.0), (272, 3072, 0.013), (16, 14336, -0.02)])
+def test_asym_quantize_bit_exact(rtn, bits, g, N, K, shift):
+    if g > K or (g > 0 and K % g):
+        pytest.skip("group does not divide K")
+    W_t = (synth.normal_weight(N, K, 0.02, seed=N + K + bits, device=DEV).float() + shift).half()
+    qw, sc, zp, codes, scales, zeros, gg = _asym_both(rtn, W_t, bits, g)
+    _assert_asym_equal(rtn, qw, sc, zp, codes, scales, zeros, bits)
+    # dequantise: fp16 of the exact product S (q + Z)
+    deq = O.rtn_dequantize_asym(codes, scales, zeros, gg).astype(np.float16)
+    got = _to_np(rtn.rtn_dequantize_asym(qw, sc, zp, N, K, bits, g))
+    assert np.array_equal(got.view(np.uint16), deq.view(np.uint16))
+
+
+@pytest.mark.parametrize("bits,g", [(4, 128), (8, 64), (4, 32), (8, 32), (4, 512)])
+def test_asym_quantize_adversarial(rtn, bits, g):
+    """One-sided groups, all-zero groups, constant groups, exact ties with odd and even shifts, subnormal scales,
+    the largest fp16 range, and a range whose width does not fit fp32."""
+    N, K = 64, 1024
+    rng = np.random.default_rng(23)
+    W = (rng.standard_normal((N, K)) * 0.02 + 0.004).astype(np.float16)
+    levels = (1 << bits) - 1
+    W[0, :g] = np.abs(W[0, :g])
+    W[1, :g] = -np.abs(W[1, :g])
+    W[2, :g] = 0.0
+    W[3, :g] = -0.0
+    W[4, :g] = np.float16(0.3)
+    W[5, :g] = np.float16(-0.3)
+    W[6, 0], W[6, 1] = 65504.0, -65504.0
+    W[7, :g] = (rng.integers(-3, 9, size=g) * 2.0 ** -24).astype(np.float16)        # scale of 0 or 1 ulp
+    for r in range(8, 24):                       # ties: range [-a, levels - a] in units of s, halves in between
+        a = int(rng.integers(0, levels + 1))
+        s = 2.0 ** -int(rng.integers(4, 9))
+        W[r, :g] = (rng.integers(-2 * a, 2 * (levels - a) + 1, size=g) * 0.5 * s).astype(np.float16)
+        W[r, 0], W[r, 1] = -a * s, (levels - a) * s
+    for r, a in zip(range(24, 36), (10, 11, 17, 180, 190, 191, 300, 317, 500, 700, 1000, 1023)):   # subnormal scales
+        W[r, :g] = (rng.integers(-a // 3, a + 1, size=g) * 2.0 ** -24).astype(np.float16)
+        W[r, 0] = np.float16(a * 2.0 ** -24)
+        W[r, 1] = np.float16(-(a // 3) * 2.0 ** -24)
+    hb, ha = {4: (16008, 33279), 8: (17014, 33217)}[bits]          # fp32 rounding of beta - alpha moves the scale
+    W[36, :g] = 0
+    W[36, 0] = np.array([hb], dtype=np.uint16).view(np.float16)[0]
+    W[36, 1] = np.array([ha], dtype=np.uint16).view(np.float16)[0]
+    W[37, :g] = np.float16(1.0) + np.float16(2.0 ** -10) * (np.arange(g) % 200)   # far from zero, narrow spread
+    W_t = torch.from_numpy(W).to(DEV)
+    qw, sc, zp, codes, scales, zeros, _ = _asym_both(rtn, W_t, bits, g)
+    _assert_asym_equal(rtn, qw, sc, zp, codes, scales, zeros, bits)
+    qw, sc, zp, codes, scales, zeros, _ = _asym_both(rtn, W_t, bits, 0)
+    _assert_asym_equal(rtn, qw, sc, zp, codes, scales, zeros, bits)
+
+
+@pytest.mark.parametrize("bits,g", [(4, 32), (4, 128), (4, 512), (4, 0), (8, 32), (8, 128), (8, 0)])
+def test_asym_linear(rtn, bits, g):
+    """rtn_linear_asym against the oracle: small batches (one launch), more than 16 rows (16-row blocks), a long K that
+    splits across workgroups, a ragged N; weights shifted away from zero so that the zero points matter."""
+    for (M, N, K) in ((1, 272, 2048), (3, 80, 4096), (16, 64, 3072), (40, 48, 2048), (7, 32, 14336)):
+        W = _to_np((synth.normal_weight(N, K, 0.02, seed=M + N + bits, device=DEV).float() + 0.015).half())
+        gg = K if g <= 0 else g
+        codes, scales, zeros = O.rtn_quantize_asym(W, bits, gg)
+        A_t = synth.activation(M, K, seed=77 + M, device=DEV)
+        qw = torch.from_numpy(O.pack_gfx950(codes, bits)).to(DEV)
+        sc = torch.from_numpy(scales).to(DEV)
+        zp = torch.from_numpy(zeros.astype(np.float16)).to(DEV)
+        C = rtn.rtn_linear_asym(A_t, qw, sc, zp, bits, g)
+        torch.cuda.synchronize()
+        ref = O.rtn_linear_asym(_to_np(A_t), codes, scales, zeros, gg)
+        H.assert_linear_close(_to_np(C), ref, f"asym int{bits} g={g} M={M} N={N} K={K}")
+        # the zero points are really used: the symmetric formula on the same codes is outside the parity tolerance
+        assert np.linalg.norm(O.rtn_linear(_to_np(A_t), codes, scales, gg) - ref) > 4e-3 * np.linalg.norm(ref)
+    # large M: dequantise once, then the dense GEMM
+    M, N, K = 300, 256, 1024
+    W_t = (synth.normal_weight(N, K, 0.02, seed=5, device=DEV).float() + 0.01).half()
+    qw, sc, zp, codes, scales, zeros, gg = _asym_both(rtn, W_t, bits, g)
+    A_t = synth.activation(M, K, seed=9, device=DEV)
+    Wd = rtn.rtn_dequantize_asym(qw, sc, zp, N, K, bits, g)
+    C = rtn.rtn_gemm_fp16(A_t, Wd)
+    torch.cuda.synchronize()
+    ref = _to_np(A_t).astype(np.float64) @ O.rtn_dequantize_asym(codes, scales, zeros, gg).astype(np.float16).astype(np.float64).T
+    H.assert_linear_close(_to_np(C), ref, f"asym dual path int{bits} g={g}")
