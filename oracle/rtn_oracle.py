@@ -11,7 +11,7 @@ what the paper's method computes:
   of Section 2.2 (RTN), applied group-wise along every output channel as that
   section's last paragraphs describe.
 * ``rtn_quantize_asym`` / ``rtn_dequantize_asym`` / ``rtn_linear_asym`` -- the asymmetric
-  variant that Section 2.2 mentions (integer zero point), reading R10.
+  variant that Section 2.2 mentions (integer zero point), reading R8.
 * ``rtn_dequantize`` / ``rtn_linear`` -- the weight-only W4A16 / W8A16 linear layer
   of Section 2.3 and Section 5: C = A (q * S)^T, as a float64 GEMM on the
   dequantised weights.
@@ -37,7 +37,7 @@ R5  A group whose stored scale is zero (all-zero group, or amax so small that
     amax / D rounds to fp16 zero) gets scale +0 and all codes 0.
 R6  "truncate" of Eq. 1 = clamp to [-2^(b-1), 2^(b-1)-1].
 R7  Groups run along the input dimension K of each output row.
-R10 Asymmetric variant (Section 2.2 only says that it subtracts an integer zero point Z
+R8  Asymmetric variant (Section 2.2 only says that it subtracts an integer zero point Z
     from the result of Int()).  Taken here: the group's range [alpha, beta] =
     [min(min r, 0), max(max r, 0)] always contains zero, so that zero is reproduced
     exactly and Z fits the code range; S = fp16 of (beta - alpha) / (2^b - 1) with the
@@ -150,7 +150,7 @@ def rtn_linear(A: np.ndarray, codes: np.ndarray, scales: np.ndarray, group_size:
 
 
 def rtn_quantize_asym(W: np.ndarray, bits: int, group_size: int):
-    """Group-wise asymmetric RTN (Section 2.2's remark on the asymmetric variant; reading R10).
+    """Group-wise asymmetric RTN (Section 2.2's remark on the asymmetric variant; reading R8).
 
     W: fp16 [N, K].  Returns (codes int8 [N, K], scales fp16 [N, K // g], zeros int16 [N, K // g])
     with dequantised weights S * (q + Z).
@@ -191,7 +191,7 @@ def rtn_quantize_asym(W: np.ndarray, bits: int, group_size: int):
 
 
 def rtn_dequantize_asym(codes: np.ndarray, scales: np.ndarray, zeros: np.ndarray, group_size: int) -> np.ndarray:
-    """float64 [N, K] of S * (q + Z) (reading R10)."""
+    """float64 [N, K] of S * (q + Z) (reading R8)."""
     codes = np.asarray(codes)
     N, K = codes.shape
     g = int(group_size)

@@ -285,7 +285,7 @@ def test_selective_precision_accounting():
 
 
 # --------------------------------------------------------------------------------------
-# Asymmetric variant (Section 2.2's remark; reading R10 in the oracle's header)
+# Asymmetric variant (Section 2.2's remark; reading R8 in the oracle's header)
 # --------------------------------------------------------------------------------------
 def _round_binary(x: F, precision: int, min_quantum_exp: int) -> F:
     """Round-half-even of a non-negative rational to a binary format with `precision` significand bits and smallest
