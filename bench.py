@@ -207,7 +207,7 @@ def report_crossover(args, rtn, synth, torch, np, dev) -> int:
     bits = args.bits
     g = 128 if bits == 4 else 0
     Ms = [int(x) for x in args.batches.split(",")]
-    ws = torch.empty(16 << 20, dtype=torch.uint8, device=dev)
+    ws = torch.empty(128 << 20, dtype=torch.uint8, device=dev)      # room for the dense GEMM's split-K partials
     print(f"# {args.report_crossover} shapes, int{bits}; us per call (HIP events, 6 back-to-back calls, best of 3; one weight copy, "
           f"so matrices under 256 MB are cache-resident): fused = rtn_linear; dual = rtn_linear_dense (dequantise to fp16 + "
           f"own dense GEMM); gemm = the dense GEMM alone on already dequantised weights")

@@ -162,8 +162,8 @@ rtn_status rtn_dequantize(const void* dev_qweight, const void* dev_scales, int64
 /* Dense 16-bit GEMM, the second half of the large-input path of Section 5:
  *   C[m, n] = fp16( sum_k A[m, k] * W[n, k] ), fp32 accumulation on the matrix cores.
  *   dev_A fp16 [M, K]; dev_W_fp16 fp16 [N, K] row-major (what rtn_dequantize writes); dev_C fp16 [M, N].
- * K % 128 == 0, N % 16 == 0.  dev_workspace may be NULL (no split-K); otherwise it is used for split-K partials
- * when M and N give fewer 128 x 128 output tiles than compute units. */
+ * K % 128 == 0, N % 16 == 0.  dev_workspace may be NULL (no split-K); otherwise it may be used for split-K partials
+ * ([split][M][N] fp32, as many splits as fit) when M and N give too few 128 x 256 output tiles for the compute units. */
 rtn_status rtn_gemm_fp16(const void* dev_A, int64_t M, const void* dev_W_fp16, int64_t N, int64_t K, void* dev_C,
                          void* dev_workspace, size_t workspace_nbytes, void* stream);
 

@@ -10,7 +10,7 @@ constexpr size_t kMaxLdsBytes = 160 * 1024;   // LDS of one gfx950 compute unit,
 // Resolved launch configuration of the fused dequantise-GEMM.
 struct LinearPlan {
     int path;       // 1 = MFMA skinny kernel, 2 = vector-ALU dot kernel, 3 = wide MFMA kernel (larger batches),
-                    // 4 = 128 x 128 tile kernel (matrix-core bound batches)
+                    // 4 = tile kernel, 128 or 256 rows x 256 columns per workgroup (matrix-core bound batches)
     int prefetch;   // k-chunks in flight per wavefront (register buffers): 1, 2 or 4
     int waves_n;    // wavefronts along N per workgroup
     int waves_k;    // wavefronts along K per workgroup
@@ -45,7 +45,7 @@ hipError_t launch_linear_grouped(const LinearArgs* args, const LinearPlan* plans
 // Path 3 (wide MFMA kernel): plan check (group size a multiple of 128, 2-4 row blocks, 1/2/4 tile-rows, at most 8 blocks) and launch.
 bool wide_plan_valid(const LinearArgs& a, const LinearPlan& p);
 hipError_t launch_linear_wide(const LinearArgs& a, const LinearPlan& p, hipStream_t st);
-// Path 4 (128 x 128 tile kernel, weights dequantised into LDS): plan check (group size a multiple of 128) and launch.
+// Path 4 (tile kernel, weights dequantised into LDS): plan check (group size a multiple of 128) and launch.
 bool tile_plan_valid(const LinearArgs& a, const LinearPlan& p);
 hipError_t launch_linear_tile(const LinearArgs& a, const LinearPlan& p, hipStream_t st);
 // Dense fp16 GEMM C[M,N] = A[M,K] W[N,K]^T with the same tile kernel (K a multiple of 128); split_k > 1 goes
