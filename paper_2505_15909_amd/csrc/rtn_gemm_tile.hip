@@ -213,6 +213,20 @@ __global__ __launch_bounds__(kThreads, 2) void tile_gemm_kernel(const TileParams
             a_load(set, t + 1 + PD);
             if ((u & 1) == 0) b_load_packed(cset, (t >> 1) + PD);   // the chunk just finished leaves its registers
         }
+        if constexpr (MBW == 4 && BSRC == 0) {
+            // Requested instruction order of the step: the first slice's operand reads, then the MFMAs in groups with one
+            // LDS store, one global load and a few of the second slice's reads between them.  Left to itself the compiler
+            // puts all stores after all MFMAs, and both wavefronts of a SIMD then leave the matrix pipe idle together.
+            constexpr int NR = 2 * (MBW + 4), NM = 2 * MBW * 4, NW = NA + 4;
+            __builtin_amdgcn_sched_group_barrier(0x100, NR / 2, 0);
+#pragma unroll
+            for (int i = 0; i < NW; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, NM / NW, 0);
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, (NR / 2 + NW - 1) / NW, 0);
+            }
+        }
         __syncthreads();
     };
 
@@ -277,10 +291,13 @@ hipError_t launch_tile_inst(const TileParams& tp, dim3 grid, hipStream_t st) {
 
 // rows16: 16-row blocks per wavefront (4 or 8), 0 = choose.
 hipError_t launch_tile(TileParams& tp, int bsrc, int64_t M, int rows16, hipStream_t st) {
-    // 256-row tiles only when there are several rounds of them for every compute unit: they halve the unpack and
-    // operand traffic per flop (a few per cent at thousands of rows) but quarter the number of workgroups
+    // 128- or 256-row tiles: one workgroup runs per compute unit, so the launch takes rounds of 256 tiles; a 256-row
+    // tile takes about 1.85 times as long as a 128-row one (it halves the unpack and operand traffic per flop), so it
+    // pays when it does not waste most of a round (measured on the 8B shapes at 1024 and 4096 rows).
     const int64_t xb = (tp.N + kTN - 1) / kTN;
-    const bool tall = rows16 ? rows16 == 8 : (M > 128 && xb * ((M + 255) / 256) * tp.split_k >= 1024);
+    const int64_t r_short = (xb * ((M + 127) / 128) * tp.split_k + 255) / 256;
+    const int64_t r_tall = (xb * ((M + 255) / 256) * tp.split_k + 255) / 256;
+    const bool tall = rows16 ? rows16 == 8 : (M > 128 && 1.85 * (double)r_tall < (double)r_short);
     const int tm = tall ? 256 : 128;
     tp.XB = (int)xb;
     tp.ZB = (int)((M + tm - 1) / tm);
