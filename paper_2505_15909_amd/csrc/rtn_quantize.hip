@@ -528,6 +528,78 @@ __global__ __launch_bounds__(256) void quantize_asym_kernel(
     }
 }
 
+// Wide groups (per-channel and the like): one 16-wavefront workgroup per (16-row tile-row, group); wavefront w takes the
+// tiles w, w + 16, ... of the group, the row ranges meet in LDS, and every wavefront then packs its own tiles (second
+// read from cache).
+template <int BITS>
+__global__ __launch_bounds__(1024) void quantize_asym_wide_kernel(
+    const half_t* __restrict__ W, uint8_t* __restrict__ qweight, half_t* __restrict__ scales,
+    half_t* __restrict__ zeros, int64_t N, int64_t K, int64_t g) {
+    constexpr int TK = Layout<BITS>::TK;
+    constexpr int OPT = TK / 32;
+    constexpr uint32_t kPosInf = 0x7C007C00u, kNegInf = 0xFC00FC00u;
+    __shared__ float lo_s[16][16], hi_s[16][16];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nl = lane & 15, kq = lane >> 4;
+    const int64_t KT = K / TK, G = K / g;
+    const int tiles = (int)(g / TK);
+    const int64_t u = blockIdx.x;
+    const int64_t nt = u / G, j = u % G;
+    const int64_t n = nt * 16 + nl;
+    const int64_t kt0 = j * tiles;
+    const half_t* src = W + n * K + kt0 * TK + kq * 8;
+    uint32_t mn = kPosInf, mx = kNegInf;
+    for (int tp = wave; tp < tiles; tp += 16) {
+#pragma unroll
+        for (int t = 0; t < OPT; ++t) {
+            const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(src + tp * TK + t * 32);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                mn = pk_min(mn, raw[i]);
+                mx = pk_max(mx, raw[i]);
+            }
+        }
+    }
+    float alpha, beta;
+    row_range(mn, mx, &alpha, &beta);               // a wavefront without tiles contributes (0, 0), which the range contains anyway
+    if (kq == 0) {
+        lo_s[wave][nl] = alpha;
+        hi_s[wave][nl] = beta;
+    }
+    __syncthreads();
+    alpha = lo_s[0][nl];
+    beta = hi_s[0][nl];
+#pragma unroll
+    for (int w = 1; w < 16; ++w) {
+        alpha = fminf(alpha, lo_s[w][nl]);
+        beta = fmaxf(beta, hi_s[w][nl]);
+    }
+    half_t s16, z16;
+    const AsymGroup gp = asym_group<BITS>(alpha, beta, &s16, &z16);
+    if (wave == 0 && kq == 0) {
+        scales[n * G + j] = s16;
+        zeros[n * G + j] = z16;
+    }
+    for (int tp = wave; tp < tiles; tp += 16) {
+        u32x4_t o;
+#pragma unroll
+        for (int t = 0; t < OPT; ++t) {
+            const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(src + tp * TK + t * 32);
+            if constexpr (BITS == 4) {
+                uint32_t wd[1];
+                quantize_octet_asym<BITS>(raw, gp, wd);
+                o[t] = wd[0];
+            } else {
+                uint32_t wd[2];
+                quantize_octet_asym<BITS>(raw, gp, wd);
+                o[2 * t] = wd[0];
+                o[2 * t + 1] = wd[1];
+            }
+        }
+        *reinterpret_cast<u32x4_t*>(qweight + ((nt * KT + kt0 + tp) * 64 + lane) * 16) = o;
+    }
+}
+
 template <int BITS>
 static hipError_t launch_quantize_asym_bits(const void* W, int64_t N, int64_t K, int64_t g, void* qweight, void* scales,
                                             void* zeros, hipStream_t st) {
@@ -540,7 +612,9 @@ static hipError_t launch_quantize_asym_bits(const void* W, int64_t N, int64_t K,
     int64_t blocks = (units + 3) / 4;
     if (blocks > 256 * 64) blocks = 256 * 64;             // grid-stride beyond this
     dim3 grid((unsigned)blocks), block(256);
-    if (g >= TK) {
+    if (g >= 16 * TK) {                                   // at least one tile per wavefront of a 16-wavefront workgroup
+        hipLaunchKernelGGL((quantize_asym_wide_kernel<BITS>), dim3((unsigned)units), dim3(1024), 0, st, w, q, s, z, N, K, g);
+    } else if (g >= TK) {
         hipLaunchKernelGGL((quantize_asym_kernel<BITS, 1>), grid, block, 0, st, w, q, s, z, N, K, g, units);
     } else if (TK / g == 2) {
         hipLaunchKernelGGL((quantize_asym_kernel<BITS, 2>), grid, block, 0, st, w, q, s, z, N, K, g, units);
