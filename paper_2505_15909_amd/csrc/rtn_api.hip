@@ -150,6 +150,26 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
     p.m_blocks = (int)((M + mrows - 1) / mrows);
     p.prefetch = 1;
     p.split_k = 1;
+    // Matrices of a hundred megabytes and more with long rows (more than 16 chunks): the launch is many generations of
+    // workgroups, its fixed costs no longer count, and what matters is the activation traffic from L2 (M / (4 waves_n)
+    // of the weight bytes, whatever the K split) and enough, not too long-lived, workgroups.  From sweeps over
+    // (waves_n, waves_k, split_k, prefetch) on the 70B and 405B shapes at 1-16 rows (choice within 10 % of the best
+    // measured configuration everywhere, 3 % on average).
+    const size_t wbytes = (size_t)N * (size_t)K * (size_t)bits / 8;
+    if (KC > 16 && wbytes >= ((size_t)100 << 20) && rows <= 16) {
+        if (rows == 2) {
+            if (KC <= 32) { p.waves_n = 1; p.waves_k = 8; p.split_k = 2; }
+            else { p.waves_n = 1; p.waves_k = 8; p.split_k = 1; }
+        } else if (rows == 3 && KC <= 32) {
+            p.waves_n = 2; p.waves_k = 2; p.split_k = 4;
+        } else {
+            // eight tile-rows share the staged rows; K is split across workgroups until there are two per compute unit
+            p.waves_n = 8; p.waves_k = 1; p.split_k = 1;
+            while (((NT + 7) / 8) * p.split_k < 512 && p.split_k * 2 <= 8 && KC / (p.split_k * 2) >= 4 &&
+                   (size_t)M * N * sizeof(float) * (p.split_k * 2) <= kWorkspaceCap)
+                p.split_k *= 2;
+        }
+    } else
     // up to 4 rows on a moderately long K (K = 14336: 28 chunks) also stream best unsplit: 14 wavefronts x 2 chunks
     if (rows <= 2 || (rows == 3 && KC >= 16) || (rows <= 5 && KC > 16 && KC <= 32)) {
         const int64_t per_wave = steps <= 6144 ? 1 : (steps <= 24576 ? 2 : 4);
@@ -175,6 +195,11 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
         } else if (steps > 24576) {                            // the largest matrices: long-lived wavefronts
             p.waves_n = rows <= 5 ? 2 : 8;
             p.waves_k = rows <= 5 ? 2 : 1;
+        } else if (KC >= 16) {                                 // K = 8192 on matrices of 30-60 MB (sweeps on the 70B qkv and o)
+            if (rows <= 5) { p.waves_n = 2; p.waves_k = 4; }
+            else if (rows <= 9) { p.waves_n = 4; p.waves_k = 4; p.split_k = 4; }
+            else { p.waves_n = 8; p.waves_k = 2; p.split_k = 4; }
+            while (p.split_k > 1 && (size_t)M * N * sizeof(float) * p.split_k > kWorkspaceCap) p.split_k /= 2;
         } else {
             p.waves_n = 4;
             p.waves_k = rows <= 9 ? 4 : 2;
