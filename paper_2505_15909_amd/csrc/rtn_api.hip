@@ -181,6 +181,10 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
             while (p.waves_k > KC) p.waves_k /= 2;
         }
         p.waves_n = (steps > 24576 && p.waves_k < 8) ? 8 / p.waves_k : 1;    // eight wavefronts only for the largest
+        if (p.waves_k > 8 && KC == 16) {                       // 16 one-chunk wavefronts: two tile-rows of 8 do better (8-bit 8B qkv)
+            p.waves_k = 8;
+            p.waves_n = NT >= 384 ? 2 : 1;
+        }
     } else if (steps <= 6144) {
         p.waves_k = round_pow2(KC, 1, 8);
         while (p.waves_k > KC) p.waves_k /= 2;
@@ -192,6 +196,9 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
             int64_t split = 4;
             while (split > 1 && (size_t)M * N * sizeof(float) * split > kWorkspaceCap) --split;
             p.split_k = (int)split;
+        } else if (steps > 24576 && NT <= 2048) {              // many chunk-steps in few tile-rows (8-bit 8B gate_up)
+            p.waves_n = 4;
+            p.waves_k = 2;
         } else if (steps > 24576) {                            // the largest matrices: long-lived wavefronts
             p.waves_n = rows <= 5 ? 2 : 8;
             p.waves_k = rows <= 5 ? 2 : 1;
