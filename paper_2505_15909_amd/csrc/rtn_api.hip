@@ -163,9 +163,9 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
         } else if (rows == 3 && KC <= 32) {
             p.waves_n = 2; p.waves_k = 2; p.split_k = 4;
         } else {
-            // eight tile-rows share the staged rows; K is split across workgroups until there are two per compute unit
+            // eight tile-rows share the staged rows; K is split across workgroups until there are 1.5 per compute unit
             p.waves_n = 8; p.waves_k = 1; p.split_k = 1;
-            while (((NT + 7) / 8) * p.split_k < 512 && p.split_k * 2 <= 8 && KC / (p.split_k * 2) >= 4 &&
+            while (((NT + 7) / 8) * p.split_k < 384 && p.split_k * 2 <= 8 && KC / (p.split_k * 2) >= 4 &&
                    (size_t)M * N * sizeof(float) * (p.split_k * 2) <= kWorkspaceCap)
                 p.split_k *= 2;
         }
