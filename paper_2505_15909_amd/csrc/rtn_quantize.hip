@@ -207,31 +207,37 @@ __global__ __launch_bounds__(1024) void quantize_large_group_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
-// Medium groups (the per-channel case for K up to 14336): as above a workgroup of 16 wavefronts owns a
-// (row-tile, group) unit, but the whole 16 x g block stays in registers between the amax pass and the
-// packing pass (LPL 16-byte loads per lane, 16 KiB x LPL per workgroup), so W is read exactly once.
-// Wavefront w owns tiles w, w + 16, ...; tiles past the end of the group are neither loaded nor stored.
+// Medium and wide groups (the per-channel case): a workgroup of 16 wavefronts owns ROWS rows of a (row-tile, group)
+// unit and keeps that ROWS x g block in registers between the amax pass and the packing pass (LPL 16-byte loads
+// per lane, 16 KiB x LPL per workgroup), so W is read exactly once.  ROWS = 16: g up to 14336; ROWS = 8 or 4 (two or
+// four workgroups per row-tile, each writing its 128- or 64-byte runs of every tile): g up to 28672 or 57344.
+// A wavefront covers 16 / ROWS consecutive tiles per step (lane -> row nl % ROWS of tile nl / ROWS); tiles past the
+// end of the group are neither loaded nor stored.
 // ---------------------------------------------------------------------------------------
-template <int BITS, int LPL>
+template <int BITS, int LPL, int ROWS>
 __global__ __launch_bounds__(1024) void quantize_resident_group_kernel(
     const half_t* __restrict__ W, uint8_t* __restrict__ qweight, half_t* __restrict__ scales,
     int64_t N, int64_t K, int64_t g, float divisor) {
     constexpr int TK = Layout<BITS>::TK;
     constexpr int OPT = TK / 32;
-    constexpr int TPW = LPL / OPT;                        // tiles per wavefront
-    __shared__ float row_max[16][16];                    // [wave][row]
+    constexpr int TPW = LPL / OPT;                        // steps per wavefront
+    constexpr int TPS = 16 / ROWS;                        // tiles per wavefront per step, row blocks per row-tile
+    __shared__ float row_max[16][ROWS];                   // [wave][row]
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nl = lane & 15, kq = lane >> 4;
+    const int rl = nl % ROWS, sub = nl / ROWS;
     const int64_t G = K / g, KT = K / TK;
     const int TPG = (int)(g / TK);
-    const int64_t u = blockIdx.x;
+    const int64_t u = blockIdx.x / TPS;
+    const int hb = (int)(blockIdx.x % TPS);               // which ROWS-row block of the row-tile
     const int64_t nt = u / G, j = u % G;
-    const half_t* src = W + (nt * 16 + nl) * K + j * g + kq * 8;
+    const int64_t row = nt * 16 + hb * ROWS + rl;
+    const half_t* src = W + row * K + j * g + kq * 8;
 
     u32x4_t raw[TPW][OPT];
 #pragma unroll
     for (int i = 0; i < TPW; ++i) {
-        const int tp = wave + 16 * i;
+        const int tp = (wave + 16 * i) * TPS + sub;
 #pragma unroll
         for (int t = 0; t < OPT; ++t) {
             raw[i][t] = u32x4_t{0u, 0u, 0u, 0u};
@@ -244,21 +250,23 @@ __global__ __launch_bounds__(1024) void quantize_resident_group_kernel(
 #pragma unroll
         for (int t = 0; t < OPT; ++t) m2 = octet_amax(raw[i][t], m2);
     float m = amax_of_pair(m2);
-    m = fmaxf(m, __shfl_xor(m, 16));
+    m = fmaxf(m, __shfl_xor(m, 16));                      // the four k-quarters of a tile
     m = fmaxf(m, __shfl_xor(m, 32));
-    if (kq == 0) row_max[wave][nl] = m;
+    if constexpr (ROWS <= 8) m = fmaxf(m, __shfl_xor(m, 8));    // the tiles of this step that hold the same row
+    if constexpr (ROWS <= 4) m = fmaxf(m, __shfl_xor(m, 4));
+    if (kq == 0 && sub == 0) row_max[wave][rl] = m;
     __syncthreads();
     m = 0.0f;
 #pragma unroll
-    for (int w = 0; w < 16; ++w) m = fmaxf(m, row_max[w][nl]);
+    for (int w = 0; w < 16; ++w) m = fmaxf(m, row_max[w][rl]);
     const float s = scale_from_amax(m, divisor);
     const float r = group_reciprocal(s);
-    if (wave == 0 && kq == 0) scales[(nt * 16 + nl) * G + j] = (half_t)s;
+    if (wave == 0 && kq == 0 && sub == 0) scales[row * G + j] = (half_t)s;
 
-    uint8_t* dst = qweight + ((nt * KT + j * TPG) * 64 + lane) * 16;
+    uint8_t* dst = qweight + ((nt * KT + j * TPG) * 64 + kq * 16 + hb * ROWS + rl) * 16;
 #pragma unroll
     for (int i = 0; i < TPW; ++i) {
-        const int tp = wave + 16 * i;
+        const int tp = (wave + 16 * i) * TPS + sub;
         u32x4_t chunk;
         uint32_t words[4];
 #pragma unroll
@@ -313,6 +321,22 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t* __restrict__
     }
 }
 
+template <int BITS, int ROWS>
+static void launch_resident_rows(int64_t lpl, dim3 grid, dim3 block, hipStream_t st, const half_t* w, uint8_t* q, half_t* s,
+                                 int64_t N, int64_t K, int64_t g, float divisor) {
+    if (lpl <= 8) hipLaunchKernelGGL((quantize_resident_group_kernel<BITS, 8, ROWS>), grid, block, 0, st, w, q, s, N, K, g, divisor);
+    else if (lpl <= 16) hipLaunchKernelGGL((quantize_resident_group_kernel<BITS, 16, ROWS>), grid, block, 0, st, w, q, s, N, K, g, divisor);
+    else hipLaunchKernelGGL((quantize_resident_group_kernel<BITS, 28, ROWS>), grid, block, 0, st, w, q, s, N, K, g, divisor);
+}
+
+template <int BITS>
+static void launch_resident(int rows, int64_t lpl, dim3 grid, dim3 block, hipStream_t st, const half_t* w, uint8_t* q, half_t* s,
+                            int64_t N, int64_t K, int64_t g, float divisor) {
+    if (rows == 16) launch_resident_rows<BITS, 16>(lpl, grid, block, st, w, q, s, N, K, g, divisor);
+    else if (rows == 8) launch_resident_rows<BITS, 8>(lpl, grid, block, st, w, q, s, N, K, g, divisor);
+    else launch_resident_rows<BITS, 4>(lpl, grid, block, st, w, q, s, N, K, g, divisor);
+}
+
 template <int BITS>
 static hipError_t launch_quantize_bits(const void* W, int64_t N, int64_t K, int64_t g, float divisor,
                                        void* qweight, void* scales, hipStream_t st) {
@@ -338,13 +362,15 @@ static hipError_t launch_quantize_bits(const void* W, int64_t N, int64_t K, int6
         if (tpg == 1) hipLaunchKernelGGL((quantize_small_group_kernel<BITS, 1, 1>), grid, block, 0, st, w, q, s, N, K, units, divisor);
         else if (tpg == 2) hipLaunchKernelGGL((quantize_small_group_kernel<BITS, 2, 1>), grid, block, 0, st, w, q, s, N, K, units, divisor);
         else hipLaunchKernelGGL((quantize_small_group_kernel<BITS, 4, 1>), grid, block, 0, st, w, q, s, N, K, units, divisor);
-    } else if (tpg * (TK / 32) <= 16 * 28) {
-        // the unit fits the registers of one 16-wavefront workgroup: 8, 16 or 28 loads per lane
-        const int64_t lpl = (tpg * (TK / 32) + 15) / 16;
-        dim3 grid((unsigned)units), block(1024);
-        if (lpl <= 8) hipLaunchKernelGGL((quantize_resident_group_kernel<BITS, 8>), grid, block, 0, st, w, q, s, N, K, g, divisor);
-        else if (lpl <= 16) hipLaunchKernelGGL((quantize_resident_group_kernel<BITS, 16>), grid, block, 0, st, w, q, s, N, K, g, divisor);
-        else hipLaunchKernelGGL((quantize_resident_group_kernel<BITS, 28>), grid, block, 0, st, w, q, s, N, K, g, divisor);
+    } else if (tpg * (TK / 32) <= 4 * 16 * 28) {
+        // the unit, or a half or a quarter of its rows, fits the registers of one 16-wavefront workgroup: 8, 16 or 28
+        // loads per lane
+        const int64_t octets = tpg * (TK / 32);
+        const int rows = octets <= 16 * 28 ? 16 : (octets <= 2 * 16 * 28 ? 8 : 4);
+        const int tps = 16 / rows;
+        const int64_t lpl = ((tpg + 16 * tps - 1) / (16 * tps)) * (TK / 32);
+        dim3 grid((unsigned)(units * tps)), block(1024);
+        launch_resident<BITS>(rows, lpl, grid, block, st, w, q, s, N, K, g, divisor);
     } else {
         dim3 grid((unsigned)units), block(1024);
         hipLaunchKernelGGL((quantize_large_group_kernel<BITS>), grid, block, 0, st, w, q, s, N, K, g, divisor);

@@ -88,10 +88,11 @@ def test_quantize_adversarial(rtn, bits, g, flags):
 
 @pytest.mark.parametrize("bits", [4, 8])
 @pytest.mark.parametrize("K,g", [(4096, 0), (5120, 0), (8192, 0), (11264, 0), (14336, 0), (16384, 0), (28672, 0),
-                                 (8192, 4096), (14336, 7168), (32768, 16384)])
+                                 (8192, 4096), (14336, 7168), (32768, 16384), (19456, 0), (40960, 0), (53248, 0), (57344, 0),
+                                 (65536, 0)])
 def test_quantize_large_groups_every_kernel(rtn, bits, K, g):
-    """Per-channel and wide groups: the register-resident kernels (8, 16, 28 loads per lane, including groups
-    that do not fill the last wavefront's tiles) and the two-pass kernel beyond them."""
+    """Per-channel and wide groups: the register-resident kernels (8, 16, 28 loads per lane; 16, 8 or 4 rows per
+    workgroup; groups that do not fill the last wavefront's tiles) and the two-pass kernel beyond 57344 columns."""
     N = 48
     W_t = synth.heavy_tail_weight(N, K, 0.02, seed=K + bits, device=DEV)
     qw, sc, codes, scales = _quantize_both(W_t, bits, g)
