@@ -302,3 +302,12 @@ def test_every_automatic_plan_is_a_valid_configuration():
                 assert st == 8, (st, M, N, K, bits, g, q)      # accepted by validation; the launch fails without a GPU
                 checked += 1
     assert checked > 3000
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build measures one GPU; asking the benchmark for more exits with a message before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
