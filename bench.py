@@ -38,7 +38,7 @@ BITS, GROUP = 4, 128
 CACHE_BYTES = 256e6
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # very command, scaled by a copy kernel of known size (FETCH_SIZE x 1.997, WRITE_SIZE x 1.000).
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 29035108   # profiles/skinny_mfma_llama8b_w4a16_hbm_traffic.txt
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 29034971   # profiles/skinny_mfma_llama8b_w4a16_hbm_traffic.txt
 
 
 def _time_linear(rtn, torch, np, A, qws, sc, bits, g, cfg, ws, reps=3, graph=True):
