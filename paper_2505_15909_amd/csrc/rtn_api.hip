@@ -171,7 +171,7 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
         }
     } else
     // up to 4 rows on a moderately long K (K = 14336: 28 chunks) also stream best unsplit: 14 wavefronts x 2 chunks
-    if (rows <= 2 || (rows == 3 && KC >= 16) || (rows <= 5 && KC > 16 && KC <= 32)) {
+    if (rows <= 2 || (rows == 3 && KC >= 16) || (rows <= 5 && KC > 16 && KC <= 32 && NT <= 384)) {
         const int64_t per_wave = steps <= 6144 ? 1 : (steps <= 24576 ? 2 : 4);
         const int64_t even = (KC + per_wave - 1) / per_wave;   // wavefronts that each get exactly per_wave chunks
         if (even <= 16 && KC % even == 0) {
@@ -191,7 +191,7 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
         p.waves_n = NT >= 384 ? 2 : 1;
     } else if (rows <= 16) {
         if (KC > 16) {                                         // long K: about 7-14 chunks per workgroup
-            p.waves_n = 4;
+            p.waves_n = (rows <= 5 && KC <= 32) ? 2 : 4;       // few rows: two tile-rows share them, more workgroups
             p.waves_k = KC <= 32 ? 4 : 2;
             int64_t split = 4;
             while (split > 1 && (size_t)M * N * sizeof(float) * split > kWorkspaceCap) --split;
