@@ -6,6 +6,12 @@ inputs to fp16, take max|w|, divide by D, round once to fp16 (the stored scale),
 every weight by the stored scale, round half to even, clamp to [-2^(b-1), 2^(b-1)-1].
 
 Run:  python tests/golden/derive_worked_examples.py  > tests/golden/rtn_worked_examples.txt
+      python tests/golden/derive_worked_examples.py asym  > tests/golden/rtn_asym_worked_examples.txt
+
+The second form derives examples of the asymmetric variant (the remark after Eq. 1: an integer zero point is subtracted
+from the result of Int()) under this library's reading: range [alpha, beta] = [min(min w, 0), max(max w, 0)];
+S = fp16(fp32(fp32(beta - alpha) / (2^b - 1))); Z = clamp(rne(alpha / S), -(2^b - 1), 0) + 2^(b-1);
+q = clamp(rne(w / S) - Z); all-zero scale: Z = 2^(b-1), q = -2^(b-1).
 """
 from fractions import Fraction as F
 import struct
@@ -65,7 +71,52 @@ def example(name, decimals, bits, divisor: F):
           f"scale_bits=0x{sb:04X} q={','.join(str(v) for v in q)}")
 
 
+def round_to_fp32(x: F) -> F:
+    """Round-to-nearest-even of a non-negative rational to fp32 (24 significant bits, smallest quantum 2^-149)."""
+    if x == 0:
+        return F(0)
+    e = x.numerator.bit_length() - x.denominator.bit_length()
+    if F(2) ** e > x:
+        e -= 1
+    quantum = F(2) ** max(e - 23, -149)
+    return rne_int(x / quantum) * quantum
+
+
+def example_asym(name, decimals, bits):
+    wb = [decimal_to_half_bits(d) for d in decimals]
+    w = [half_bits_to_fraction(h) for h in wb]
+    levels = (1 << bits) - 1
+    lo, hi = -(1 << (bits - 1)), (1 << (bits - 1)) - 1
+    alpha, beta = min(min(w), F(0)), max(max(w), F(0))
+    sb = round_to_half_bits(round_to_fp32(round_to_fp32(beta - alpha) / levels))
+    s = half_bits_to_fraction(sb)
+    t = 0 if s == 0 else max(-levels, min(0, rne_int(alpha / s)))
+    z = t - lo
+    q = [max(lo, min(hi, (0 if s == 0 else rne_int(v / s)) - z)) for v in w]
+    print(f"{name} bits={bits} w={','.join(decimals)} scale_bits=0x{sb:04X} zero={z} q={','.join(str(v) for v in q)}")
+
+
+def main_asym():
+    print("# Worked examples of the asymmetric variant (Section 2.2, the remark after Eq. 1), derived by")
+    print("# derive_worked_examples.py asym with exact rationals; weight = S * (q + zero).")
+    base = ["0.7", "-0.35", "0.05", "0.1", "-0.25", "0.45", "0", "-0.7"]
+    example_asym("plain4", base, 4)
+    example_asym("plain8", base, 8)
+    example_asym("positive4", ["0.1", "0.2", "0.35", "0.8", "0.05", "0.6", "0.75", "0.4"], 4)
+    example_asym("negative8", ["-0.1", "-0.2", "-0.35", "-0.8", "-0.05", "-0.6", "-0.75", "-0.4"], 8)
+    example_asym("grid4", [repr((k - 3) / 128) for k in range(16)], 4)      # multiples of 2^-7: exact decimals
+    example_asym("ties_odd_zero4", ["-3", "12", "0.5", "1.5", "2.5", "-0.5", "-1.5", "-2.5"], 4)
+    example_asym("shifted8", ["1.0", "1.001", "1.01", "1.05", "0.99", "1.1", "0.95", "1.02"], 8)
+    example_asym("zeros4", ["0", "-0", "0", "0"], 4)
+    example_asym("tiny4", ["0.00000005960464477539", "0.00000011920928955078", "-0.00000023841857910156", "0"], 4)
+    example_asym("wide_range8", ["60000", "-60000", "1", "-1", "30000.5", "0.25", "-12345", "7"], 8)
+
+
 if __name__ == "__main__":
+    import sys
+    if len(sys.argv) > 1 and sys.argv[1] == "asym":
+        main_asym()
+        sys.exit(0)
     print("# Worked examples of Eq. 1 / Eq. 2 (Section 2.2), derived by derive_worked_examples.py")
     print("# with exact rationals.  divisor 7 / 127 = 2^(b-1)-1 (graded rule); 15/2 / 255/2 = Eq. 2.")
     base = ["0.7", "-0.35", "0.05", "0.1", "-0.25", "0.45", "0", "-0.7"]

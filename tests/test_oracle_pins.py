@@ -287,6 +287,32 @@ def test_selective_precision_accounting():
 # --------------------------------------------------------------------------------------
 # Asymmetric variant (Section 2.2's remark; reading R8 in the oracle's header)
 # --------------------------------------------------------------------------------------
+GOLDEN_ASYM = os.path.join(os.path.dirname(__file__), "golden", "rtn_asym_worked_examples.txt")
+
+
+def _golden_asym_cases():
+    out = []
+    with open(GOLDEN_ASYM) as fh:
+        for line in fh:
+            if line.startswith("#") or not line.strip():
+                continue
+            name, *kv = line.split()
+            d = dict(item.split("=", 1) for item in kv)
+            out.append((name, int(d["bits"]), d["w"].split(","), int(d["scale_bits"], 16), int(d["zero"]),
+                        [int(v) for v in d["q"].split(",")]))
+    return out
+
+
+@pytest.mark.parametrize("case", _golden_asym_cases(), ids=lambda c: c[0])
+def test_asym_worked_examples(case):
+    """Examples derived with exact rationals by tests/golden/derive_worked_examples.py (imports neither side)."""
+    name, bits, w, scale_bits, zero, q = case
+    W = np.array([[float(v) for v in w]], dtype=np.float16)
+    codes, scales, zeros = O.rtn_quantize_asym(W, bits, W.shape[1])
+    assert int(scales.view(np.uint16)[0, 0]) == scale_bits
+    assert int(zeros[0, 0]) == zero
+    assert codes[0].tolist() == q
+
 def _round_binary(x: F, precision: int, min_quantum_exp: int) -> F:
     """Round-half-even of a non-negative rational to a binary format with `precision` significand bits and smallest
     quantum 2^min_quantum_exp (IEEE rounding restated with exact rationals; no overflow handling)."""
