@@ -208,8 +208,9 @@ rtn_status rtn_layer_forward(const rtn_module* mods, int n_mods, void* dev_works
  * Codes use the same packed layout (rtn_unpack returns q); dev_zeros is fp16 [N, K/g]
  * holding the integers Z; sizes as for the scales (rtn_scales_nbytes).  Group sizes, shapes,
  * alignment and error behaviour as for rtn_quantize / rtn_dequantize / rtn_linear.
- * rtn_linear_asym always runs the small-batch kernel (16 rows at a time re-read the weights):
- * for large M dequantise once with rtn_dequantize_asym and call rtn_gemm_fp16. */
+ * rtn_linear_asym runs the small-batch kernel up to 16 rows and the wide MFMA kernel above (group
+ * sizes that are multiples of 128; other group sizes go 16 rows at a time and re-read the weights);
+ * for thousands of rows dequantise once with rtn_dequantize_asym and call rtn_gemm_fp16. */
 rtn_status rtn_quantize_asym(const void* dev_W, int64_t N, int64_t K, int bits, int group_size,
                              void* dev_qweight, void* dev_scales, void* dev_zeros, void* stream);
 rtn_status rtn_dequantize_asym(const void* dev_qweight, const void* dev_scales, const void* dev_zeros,

@@ -561,14 +561,25 @@ rtn_status rtn_linear_asym(const void* dev_A, int64_t M, const void* dev_qweight
     a.A = dev_A; a.qweight = dev_qweight; a.scales = dev_scales; a.C = dev_C; a.zeros = dev_zeros;
     a.workspace = static_cast<float*>(dev_workspace);
     a.M = M; a.N = N; a.K = K; a.g = g; a.bits = bits;
-    // the small-batch kernel, 16 rows per workgroup, planned as for min(M, 16) rows
-    LinearPlan h = auto_plan(M < 16 ? M : 16, N, K, bits, g, (size_t)device_max_lds(), 1);
-    rtn_linear_cfg cfg;
-    cfg.path = 1; cfg.prefetch = 1; cfg.waves_n = h.waves_n; cfg.waves_k = h.waves_k;
-    cfg.split_k = M <= 16 ? h.split_k : 1; cfg.m_rows16 = 1; cfg.n_tiles16 = 1;
     LinearPlan p;
-    st = resolve_plan(a, &cfg, workspace_nbytes, &p);
-    if (st != RTN_OK) return st;
+    rtn_linear_cfg cfg;
+    bool planned = false;
+    if (M > 16 && g % 128 == 0) {
+        // the wide kernel's zero-point instantiations: 8 wavefronts, at most two tile-rows per wavefront
+        LinearPlan h;
+        wide_plan(M, N, K, bits, &h);
+        cfg.path = 3; cfg.prefetch = 1; cfg.waves_n = 8; cfg.waves_k = 1; cfg.split_k = h.split_k;
+        cfg.m_rows16 = h.m_rows16; cfg.n_tiles16 = h.n_tiles16 > 2 ? 2 : h.n_tiles16;
+        planned = resolve_plan(a, &cfg, workspace_nbytes, &p) == RTN_OK;
+    }
+    if (!planned) {
+        // the small-batch kernel, 16 rows per workgroup, planned as for min(M, 16) rows
+        LinearPlan h = auto_plan(M < 16 ? M : 16, N, K, bits, g, (size_t)device_max_lds(), 1);
+        cfg.path = 1; cfg.prefetch = 1; cfg.waves_n = h.waves_n; cfg.waves_k = h.waves_k;
+        cfg.split_k = M <= 16 ? h.split_k : 1; cfg.m_rows16 = 1; cfg.n_tiles16 = 1;
+        st = resolve_plan(a, &cfg, workspace_nbytes, &p);
+        if (st != RTN_OK) return st;
+    }
     hipError_t e = rtn::launch_linear(a, p, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? RTN_OK : RTN_ERR_HIP;
 }

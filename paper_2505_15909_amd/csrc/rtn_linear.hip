@@ -604,7 +604,7 @@ static SkinnyLaunch prepare_skinny(const LinearArgs& a, const LinearPlan& p) {
 }
 
 hipError_t launch_linear(const LinearArgs& a, const LinearPlan& p, hipStream_t st) {
-    if (a.zeros && p.path != 1) return hipErrorInvalidValue;          // zero points: skinny kernel only
+    if (a.zeros && p.path != 1 && p.path != 3) return hipErrorInvalidValue;   // zero points: skinny and wide kernels only
     if (p.path == 3) return launch_linear_wide(a, p, st);
     if (p.path == 4) return launch_linear_tile(a, p, st);
     const SkinnyLaunch L = prepare_skinny(a, p);

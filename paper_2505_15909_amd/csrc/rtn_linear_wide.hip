@@ -36,6 +36,7 @@ struct WideParams {
     const half_t* A;
     const uint8_t* qw;
     const half_t* scales;
+    const half_t* zeros;   // asymmetric variant only (ZP)
     half_t* C;
     float* ws;
     int M, N, K;
@@ -56,7 +57,8 @@ struct WideParams {
 // first MFMA of the step takes as a constant operand instead of a cleared register.
 // At least two wavefronts per SIMD (256 registers each): the MFMAs then keep their accumulators in ordinary
 // vector registers, where the scale multiply-add can read them directly.
-template <int BITS, int MB, int NBW, bool G1, int WV>
+// ZP: asymmetric variant -- the integer zero point of the step's group goes into the unpack (operand = q + Z).
+template <int BITS, int MB, int NBW, bool G1, int WV, bool ZP = false>
 __global__ __launch_bounds__(64 * WV, WV <= 8 ? 2 : 4) void wide_mfma_kernel(const WideParams p) {
     constexpr int TK = Layout<BITS>::TK;
     constexpr int MPT = Layout<BITS>::MFMA_PER_TILE;
@@ -84,6 +86,8 @@ __global__ __launch_bounds__(64 * WV, WV <= 8 ? 2 : 4) void wide_mfma_kernel(con
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(p.qw), 0, p.qw_bytes, kBufferFlags);
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<half_t*>(p.scales), 0, p.sc_bytes, kBufferFlags);
     const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(const_cast<half_t*>(p.A), 0, p.a_bytes, kBufferFlags);
+    const __amdgpu_buffer_rsrc_t rz = __builtin_amdgcn_make_buffer_rsrc(const_cast<half_t*>(ZP ? p.zeros : p.scales), 0, p.sc_bytes, kBufferFlags);
+    (void)rz;
     const uint32_t magic = fp16_magic_vgpr();
 
     const int nt0 = (xb * WV + wave) * NBW;               // first tile-row of this wavefront
@@ -122,6 +126,8 @@ __global__ __launch_bounds__(64 * WV, WV <= 8 ? 2 : 4) void wide_mfma_kernel(con
     // ---- weight / scale ring, three k-steps deep ----
     u32x4_t wbuf[3][NBW][TPS];
     uint16_t sbuf[3][NBW];
+    uint16_t zbuf[ZP ? 3 : 1][NBW];                        // zero points, same offsets as the scales
+    (void)zbuf;
     auto w_load = [&](int slot, int t) {
         const bool in = t < T;
         const uint32_t ks = (uint32_t)(ks0 + t);
@@ -130,6 +136,7 @@ __global__ __launch_bounds__(64 * WV, WV <= 8 ? 2 : 4) void wide_mfma_kernel(con
         for (int r = 0; r < NBW; ++r) {
             const bool ok = in && nt_ok[r];
             sbuf[slot][r] = __builtin_amdgcn_raw_buffer_load_b16(rs, ok ? s_lane[r] + j * 2u : kOutOfRange, 0, 0);
+            if constexpr (ZP) zbuf[slot][r] = __builtin_amdgcn_raw_buffer_load_b16(rz, ok ? s_lane[r] + j * 2u : kOutOfRange, 0, 0);
 #pragma unroll
             for (int c = 0; c < TPS; ++c)
                 wbuf[slot][r][c] = __builtin_amdgcn_raw_buffer_load_b128(
@@ -175,7 +182,9 @@ __global__ __launch_bounds__(64 * WV, WV <= 8 ? 2 : 4) void wide_mfma_kernel(con
                 a[b] = *reinterpret_cast<const half8_t*>(abase + (b * 256 + ((i * 4 + kq) ^ nl)) * 16);
 #pragma unroll
             for (int r = 0; r < NBW; ++r) {
-                const half8_t bw = unpack_operand<BITS>(wbuf[slot][r][i / MPT], i % MPT, magic);
+                half8_t bw;
+                if constexpr (ZP) bw = unpack_operand_zp<BITS>(wbuf[slot][r][i / MPT], i % MPT, magic, (float)__builtin_bit_cast(half_t, zbuf[slot][r]));
+                else bw = unpack_operand<BITS>(wbuf[slot][r][i / MPT], i % MPT, magic);
 #pragma unroll
                 for (int b = 0; b < MB; ++b) {
                     const float4_t c_in = (G1 && i == 0) ? (float4_t){0.f, 0.f, 0.f, 0.f} : part[b][r];
@@ -238,6 +247,28 @@ hipError_t launch_wide_g1(const WideParams& wp, dim3 grid, hipStream_t st) {
     return hipGetLastError();
 }
 
+// Asymmetric variant: 8 wavefronts, one or two tile-rows per wavefront.
+template <int BITS, int MB, int NBW>
+hipError_t launch_wide_zp(const WideParams& wp, dim3 grid, hipStream_t st) {
+    dim3 block(64 * 8);
+    if (wp.spg == 1) hipLaunchKernelGGL((wide_mfma_kernel<BITS, MB, NBW, true, 8, true>), grid, block, 0, st, wp);
+    else hipLaunchKernelGGL((wide_mfma_kernel<BITS, MB, NBW, false, 8, true>), grid, block, 0, st, wp);
+    return hipGetLastError();
+}
+
+template <int BITS>
+hipError_t launch_wide_zp_bits(const WideParams& wp, int mb, int nbw, dim3 grid, hipStream_t st) {
+    switch (mb * 10 + nbw) {
+        case 21: return launch_wide_zp<BITS, 2, 1>(wp, grid, st);
+        case 22: return launch_wide_zp<BITS, 2, 2>(wp, grid, st);
+        case 31: return launch_wide_zp<BITS, 3, 1>(wp, grid, st);
+        case 32: return launch_wide_zp<BITS, 3, 2>(wp, grid, st);
+        case 41: return launch_wide_zp<BITS, 4, 1>(wp, grid, st);
+        case 42: return launch_wide_zp<BITS, 4, 2>(wp, grid, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 // Sixteen wavefronts leave 128 registers each: only the register tiles with one tile-row per wavefront.
 template <int BITS, int MB, int NBW>
 hipError_t launch_wide_wv(const WideParams& wp, int wv, dim3 grid, hipStream_t st) {
@@ -273,6 +304,7 @@ bool wide_plan_valid(const LinearArgs& a, const LinearPlan& p) {
     if (p.m_rows16 * p.n_tiles16 > 8) return false;       // register tile: at most 8 accumulator blocks
     if (p.waves_n != 4 && p.waves_n != 8 && !(p.waves_n == 16 && p.n_tiles16 == 1)) return false;
     if (p.split_k < 1 || p.split_k > a.K / kStepK) return false;
+    if (a.zeros && (p.waves_n != 8 || p.n_tiles16 > 2)) return false;      // the zero-point instantiations
     return true;
 }
 
@@ -282,6 +314,7 @@ hipError_t launch_linear_wide(const LinearArgs& a, const LinearPlan& p, hipStrea
     wp.A = static_cast<const half_t*>(a.A);
     wp.qw = static_cast<const uint8_t*>(a.qweight);
     wp.scales = static_cast<const half_t*>(a.scales);
+    wp.zeros = static_cast<const half_t*>(a.zeros);
     wp.C = static_cast<half_t*>(a.C);
     wp.ws = a.workspace;
     wp.M = (int)a.M; wp.N = (int)a.N; wp.K = (int)a.K;
@@ -302,8 +335,11 @@ hipError_t launch_linear_wide(const LinearArgs& a, const LinearPlan& p, hipStrea
     wp.a_bytes = (uint32_t)((size_t)a.M * a.K * 2);
     const int xb_pad = (wp.XB + kXcds - 1) / kXcds * kXcds;
     dim3 grid((unsigned)(xb_pad * wp.ZB), (unsigned)p.split_k, 1);
-    hipError_t e = (a.bits == 4) ? launch_wide_bits<4>(wp, p.m_rows16, p.n_tiles16, p.waves_n, grid, st)
-                                 : launch_wide_bits<8>(wp, p.m_rows16, p.n_tiles16, p.waves_n, grid, st);
+    hipError_t e;
+    if (a.zeros) e = (a.bits == 4) ? launch_wide_zp_bits<4>(wp, p.m_rows16, p.n_tiles16, grid, st)
+                                   : launch_wide_zp_bits<8>(wp, p.m_rows16, p.n_tiles16, grid, st);
+    else e = (a.bits == 4) ? launch_wide_bits<4>(wp, p.m_rows16, p.n_tiles16, p.waves_n, grid, st)
+                           : launch_wide_bits<8>(wp, p.m_rows16, p.n_tiles16, p.waves_n, grid, st);
     if (e != hipSuccess) return e;
     if (p.split_k > 1) e = launch_splitk_reduce(a.workspace, static_cast<half_t*>(a.C), a.M * a.N, p.split_k, st);
     return e;

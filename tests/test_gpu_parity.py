@@ -622,9 +622,11 @@ def test_asym_quantize_adversarial(rtn, bits, g):
 
 @pytest.mark.parametrize("bits,g", [(4, 32), (4, 128), (4, 512), (4, 0), (8, 32), (8, 128), (8, 0)])
 def test_asym_linear(rtn, bits, g):
-    """rtn_linear_asym against the oracle: small batches (one launch), more than 16 rows (16-row blocks), a long K that
+    """rtn_linear_asym against the oracle: small batches (one launch), more than 16 rows (the wide kernel's zero-point
+    instantiations where the group size allows, 16-row blocks of the small-batch kernel otherwise), a long K that
     splits across workgroups, a ragged N; weights shifted away from zero so that the zero points matter."""
-    for (M, N, K) in ((1, 272, 2048), (3, 80, 4096), (16, 64, 3072), (40, 48, 2048), (7, 32, 14336)):
+    for (M, N, K) in ((1, 272, 2048), (3, 80, 4096), (16, 64, 3072), (40, 48, 2048), (7, 32, 14336), (17, 272, 1024),
+                      (130, 80, 3072), (64, 528, 2048)):
         W = _to_np((synth.normal_weight(N, K, 0.02, seed=M + N + bits, device=DEV).float() + 0.015).half())
         gg = K if g <= 0 else g
         codes, scales, zeros = O.rtn_quantize_asym(W, bits, gg)
