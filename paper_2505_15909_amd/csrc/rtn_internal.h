@@ -28,7 +28,7 @@ struct LinearArgs {
     float* workspace;
     int64_t M, N, K, g;
     int bits;
-    const void* zeros = nullptr;   // fp16 [N, K/g] integer zero points (asymmetric variant; skinny kernel only) or null
+    const void* zeros = nullptr;   // fp16 [N, K/g] integer zero points (asymmetric variant; skinny and wide kernels) or null
 };
 
 hipError_t launch_quantize(const void* W, int64_t N, int64_t K, int bits, int64_t g, float divisor,
