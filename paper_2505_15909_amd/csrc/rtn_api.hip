@@ -157,9 +157,8 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
     // measured configuration everywhere, 3 % on average).
     const size_t wbytes = (size_t)N * (size_t)K * (size_t)bits / 8;
     if (KC > 16 && wbytes >= ((size_t)100 << 20) && rows <= 16) {
-        if (rows == 2) {
-            if (KC <= 32) { p.waves_n = 1; p.waves_k = 8; p.split_k = 2; }
-            else { p.waves_n = 1; p.waves_k = 8; p.split_k = 1; }
+        if (rows == 2) {                                       // one row: eight wavefronts along K, K in halves up to 32 chunks
+            p.waves_n = 1; p.waves_k = 8; p.split_k = KC <= 32 ? 2 : 1;
         } else if (rows == 3 && KC <= 32) {
             p.waves_n = 2; p.waves_k = 2; p.split_k = 4;
         } else {
