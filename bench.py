@@ -210,7 +210,7 @@ def report_crossover(args, rtn, synth, torch, np, dev) -> int:
     ws = torch.empty(128 << 20, dtype=torch.uint8, device=dev)      # room for the dense GEMM's split-K partials
     print(f"# {args.report_crossover} shapes, int{bits}; us per call (HIP events, 6 back-to-back calls, best of 3; one weight copy, "
           f"so matrices under 256 MB are cache-resident): fused = rtn_linear; dual = rtn_linear_dense (dequantise to fp16 + "
-          f"own dense GEMM); gemm = the dense GEMM alone on already dequantised weights")
+          f"own dense GEMM); gemm = the dense GEMM alone on already dequantised weights; last column (reference): the same dequantise followed by torch.matmul (hipBLASLt)")
 
     def timeit(fn, n=6):
         fn()
@@ -239,9 +239,15 @@ def report_crossover(args, rtn, synth, torch, np, dev) -> int:
             tf = timeit(lambda: rtn.rtn_linear(A, qw, sc, bits, g, out=out, workspace=ws))
             td = timeit(lambda: rtn.rtn_linear_dense(A, qw, sc, bits, g, tmp, out=out, workspace=ws))
             tg = timeit(lambda: rtn.rtn_gemm_fp16(A, Wd, out=out, workspace=ws))
+
+            def dual_vendor():                      # reference only: the same dequantise, then the vendor library's GEMM
+                rtn.rtn_dequantize(qw, sc, K, bits, g, out=Wd)
+                torch.matmul(A, Wd.t(), out=out)
+            tv = timeit(dual_vendor)
             path = rtn.rtn_linear_query(M, N, K, bits, g)["path"]
             print(f"{name:8s} {K:6d}->{N:6d} M={M:5d}  fused(path {path}) {tf:9.1f} us {fl / tf / 1e6:6.0f} TFLOP/s | dual {td:9.1f} us "
-                  f"{fl / td / 1e6:6.0f} TFLOP/s | gemm {tg:9.1f} us {fl / tg / 1e6:6.0f} TFLOP/s | fused/dual {tf / td:5.2f}", flush=True)
+                  f"{fl / td / 1e6:6.0f} TFLOP/s | gemm {tg:9.1f} us {fl / tg / 1e6:6.0f} TFLOP/s | fused/dual {tf / td:5.2f} | "
+                  f"dequantise + vendor GEMM {tv:9.1f} us, fused/that {tf / tv:5.2f}", flush=True)
         del qw, tmp, Wd
     return 0
 

@@ -189,9 +189,10 @@ def rtn_unpack(qweight: torch.Tensor, N: int, K: int, bits: int) -> torch.Tensor
     return codes
 
 
-def rtn_dequantize(qweight: torch.Tensor, scales: torch.Tensor, K: int, bits: int, group_size: int) -> torch.Tensor:
+def rtn_dequantize(qweight: torch.Tensor, scales: torch.Tensor, K: int, bits: int, group_size: int,
+                   out: torch.Tensor = None) -> torch.Tensor:
     N = scales.shape[0]
-    W = torch.empty((N, K), dtype=torch.float16, device=qweight.device)
+    W = out if out is not None else torch.empty((N, K), dtype=torch.float16, device=qweight.device)
     _check(_lib.rtn_dequantize(qweight.data_ptr(), scales.data_ptr(), N, K, bits, group_size, W.data_ptr(),
                                _stream()), "rtn_dequantize")
     return W
