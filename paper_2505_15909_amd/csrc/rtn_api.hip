@@ -126,9 +126,12 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
     // more than 16 rows: the wide kernel, except at 17-32 rows on matrices so large that the skinny kernel's
     // pure weight streaming still wins
     const bool wide_wins = g % 128 == 0 && (M > 32 || (M > 16 && (size_t)N * K * bits / 8 <= ((size_t)256 << 20)));
-    // a hundred rows and more, and at least one 128 x 256 output tile per compute unit without splitting K: the
-    // tile kernel (measured against the wide kernel on the 8B and 405B shapes at M = 128 ... 4096)
-    const bool tile_wins = g % 128 == 0 && M >= 128 && ((N + 255) / 256) * ((M + 127) / 128) >= 256;
+    // 128 rows and more, and enough 128 x 256 output tiles to fill 9/16 of the compute units without splitting K:
+    // the tile kernel (measured against the wide kernel on the 8B, 70B and 405B shapes at M = 128 ... 4096: it wins
+    // by 8-15 % from 144 tiles and loses from 128 down), unless its 128-row padding costs more than the wide
+    // kernel's 64-row padding
+    const bool tile_wins = g % 128 == 0 && M >= 128 && ((N + 255) / 256) * ((M + 127) / 128) >= 144 &&
+                           (M + 127) / 128 * 2 <= (M + 63) / 64;
     if (force_path == 4 || (force_path == 0 && tile_wins)) {
         p.path = 4;
         p.prefetch = 1; p.waves_n = 8; p.waves_k = 1; p.split_k = 1;

@@ -45,6 +45,7 @@ struct TileParams {
     int G;                  // groups per row (packed sources)
     int cpg;                // 128-column chunks per group
     uint32_t cpg_inv;       // floor(2^32 / cpg) + 1 (0 when cpg == 1)
+    uint32_t cpg_one;       // all ones when cpg == 1, else 0: chunk -> group is umulhi(c, cpg_inv) + (c & cpg_one)
     int KL;                 // packed tiles per weight row
     int XB, ZB;             // tiles along N, along M
     int split_k;
@@ -101,18 +102,18 @@ __global__ __launch_bounds__(kThreads, 2) void tile_gemm_kernel(const TileParams
     const uint32_t st_off = swizzled(st_r, st_p);            // + i * 64 rows * 128 bytes
     constexpr int NA = TM / 64;                              // pieces per thread per step
     u32x4_t areg[PD][NA];
-    auto a_load = [&](int set, int t) {
+    auto a_load = [&](int set, int t, int i0 = 0, int i1 = 2 * MBW / 4) {
 #pragma unroll
-        for (int i = 0; i < NA; ++i) {
+        for (int i = i0; i < i1; ++i) {
             const int row = st_r + 64 * i;
             const bool ok = t < T && row < a_rows;
             const uint32_t off = ok ? ((uint32_t)row * (uint32_t)p.K + (uint32_t)(ks0 + t) * kBK + st_p * 8) * 2u : kOutOfRange;
             areg[set][i] = __builtin_amdgcn_raw_buffer_load_b128(ra, off, 0, 0);
         }
     };
-    auto a_store = [&](int set, int stage) {
+    auto a_store = [&](int set, int stage, int i0 = 0, int i1 = 2 * MBW / 4) {
 #pragma unroll
-        for (int i = 0; i < NA; ++i) *reinterpret_cast<u32x4_t*>(lds + stage * STAGE + st_off + i * 8192) = areg[set][i];
+        for (int i = i0; i < i1; ++i) *reinterpret_cast<u32x4_t*>(lds + stage * STAGE + st_off + i * 8192) = areg[set][i];
     };
 
     // ---- weights ----
@@ -123,9 +124,9 @@ __global__ __launch_bounds__(kThreads, 2) void tile_gemm_kernel(const TileParams
     constexpr int NBR = BSRC == 0 ? 4 : 2 * TPC;
     u32x4_t breg[PD][NBR];
     uint16_t sreg[PD][2];
-    auto b_load_dense = [&](int set, int t) {
+    auto b_load_dense = [&](int set, int t, int i0 = 0, int i1 = 4) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = i0; i < i1; ++i) {
             const int row = st_r + 64 * i;
             const bool ok = t < T && row < b_rows;
             const uint32_t off = ok ? ((uint32_t)row * (uint32_t)p.K + (uint32_t)(ks0 + t) * kBK + st_p * 8) * 2u : kOutOfRange;
@@ -135,30 +136,33 @@ __global__ __launch_bounds__(kThreads, 2) void tile_gemm_kernel(const TileParams
     auto b_load_packed = [&](int set, int c) {               // chunk c of this workgroup
         const bool in = 2 * c < T;
         const uint32_t kc = (uint32_t)(kc0 + c);
-        const uint32_t j = p.cpg_inv == 0 ? kc : __umulhi(kc, p.cpg_inv);
+        // branch-free in wave-uniform values (a branch here would split the loop body and make its waits
+        // conservative): group index by multiply-high plus a masked term, out of range by an added constant
+        const uint32_t j = __umulhi(kc, p.cpg_inv) + (kc & p.cpg_one);
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             const int nt = n0 / 16 + 2 * wave + q;
-            const bool ok = in && nt * 16 < p.N;
-            sreg[set][q] = __builtin_amdgcn_raw_buffer_load_b16(rs, ok ? ((uint32_t)(nt * 16 + nl) * (uint32_t)p.G + j) * 2u : kOutOfRange, 0, 0);
+            const uint32_t skip = (in && nt * 16 < p.N) ? 0u : kOutOfRange;     // offsets stay below 2^31
+            sreg[set][q] = __builtin_amdgcn_raw_buffer_load_b16(rs, ((uint32_t)(nt * 16 + nl) * (uint32_t)p.G + j) * 2u + skip, 0, 0);
 #pragma unroll
             for (int kt = 0; kt < TPC; ++kt)
                 breg[set][q * TPC + kt] = __builtin_amdgcn_raw_buffer_load_b128(
-                    rb, ok ? ((uint32_t)nt * (uint32_t)p.KL + kc * TPC + kt) * 1024u + lane * 16 : kOutOfRange, 0, 2 /* nt */);
+                    rb, ((uint32_t)nt * (uint32_t)p.KL + kc * TPC + kt) * 1024u + lane * 16 + skip, 0, 2 /* nt */);
         }
     };
-    auto b_store_dense = [&](int set, int stage) {
+    auto b_store_dense = [&](int set, int stage, int i0 = 0, int i1 = 4) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4_t*>(lds + stage * STAGE + A_BYTES + st_off + i * 8192) = breg[set][i];
+        for (int i = i0; i < i1; ++i) *reinterpret_cast<u32x4_t*>(lds + stage * STAGE + A_BYTES + st_off + i * 8192) = breg[set][i];
     };
-    auto b_store_packed = [&](int set, int half, int stage) {          // half = which 64 columns of the chunk
+    // half = which 64 columns of the chunk; [q0, q1) x [o0, o1): tile-rows and 32-column operands to store
+    auto b_store_packed = [&](int set, int half, int stage, int q0 = 0, int q1 = 2, int o0 = 0, int o1 = 2) {
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
+        for (int q = q0; q < q1; ++q) {
             const half_t s = __builtin_bit_cast(half_t, sreg[set][q]);
             const half2_t s2 = {s, s};
             const int row = (2 * wave + q) * 16 + nl;
 #pragma unroll
-            for (int o = 0; o < 2; ++o) {                                // two 32-column MFMA operands per half
+            for (int o = o0; o < o1; ++o) {                              // two 32-column MFMA operands per half
                 Half8Words h;
                 if constexpr (BSRC == 4) h.v = unpack_word4(breg[set][q][2 * half + o], magic);
                 else h.v = unpack_words8(breg[set][q * 2 + half][2 * o], breg[set][q * 2 + half][2 * o + 1]);
@@ -178,22 +182,29 @@ __global__ __launch_bounds__(kThreads, 2) void tile_gemm_kernel(const TileParams
     // operand rows of this lane: A rows wm*TM/2 + 16 b + nl, B rows wn*64 + 16 r + nl; ((row >> 1) & 7) == nl >> 1
     const uint32_t a_rd = (uint32_t)((wm * (TM / 2) + nl) * 128);
     const uint32_t b_rd = (uint32_t)(A_BYTES + (wn * 64 + nl) * 128);
+    half8_t bq[4];
+    auto b_read = [&](int stage, int i) {                     // the wavefront's four weight operands of slice i
+        const uint32_t po = (uint32_t)(((i * 4 + kq) ^ (nl >> 1)) * 16);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) bq[r] = *reinterpret_cast<const half8_t*>(lds + stage * STAGE + b_rd + r * 2048 + po);
+    };
+    auto compute_rows = [&](int stage, int i, int b0, int b1) {   // row blocks [b0, b1) of slice i against bq
+        const uint32_t po = (uint32_t)(((i * 4 + kq) ^ (nl >> 1)) * 16);
+        half8_t a[MBW];
+#pragma unroll
+        for (int b = b0; b < b1; ++b) a[b] = *reinterpret_cast<const half8_t*>(lds + stage * STAGE + a_rd + b * 2048 + po);
+#pragma unroll
+        for (int b = b0; b < b1; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[b][r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[b], bq[r], acc[b][r], 0, 0, 0);
+    };
+    auto compute_slice = [&](int stage, int i) {              // one 32-column slice of the step
+        b_read(stage, i);
+        compute_rows(stage, i, 0, MBW);
+    };
     auto compute = [&](int stage) {
-        const uint8_t* base = lds + stage * STAGE;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const uint32_t po = (uint32_t)(((i * 4 + kq) ^ (nl >> 1)) * 16);
-            half8_t a[MBW], bq[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) bq[r] = *reinterpret_cast<const half8_t*>(base + b_rd + r * 2048 + po);
-#pragma unroll
-            for (int b = 0; b < MBW; ++b) a[b] = *reinterpret_cast<const half8_t*>(base + a_rd + b * 2048 + po);
-#pragma unroll
-            for (int b = 0; b < MBW; ++b)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) acc[b][r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[b], bq[r], acc[b][r], 0, 0, 0);
-            if constexpr (MBW == 8) __builtin_amdgcn_sched_barrier(0);   // one slice's operands live at a time: 256 registers
-        }
+        compute_slice(stage, 0);
+        compute_slice(stage, 1);
     };
 
     // One step: arithmetic on stage (t & 1) while the next step's tiles go from registers into the other stage
@@ -201,19 +212,70 @@ __global__ __launch_bounds__(kThreads, 2) void tile_gemm_kernel(const TileParams
     auto step = [&](int u, int t) {
         const int stage = u & 1;
         const int set = PD == 2 ? (u & 1) : 0;               // register set that holds step t+1
+        if constexpr (MBW == 8) {
+            // tall tile: the step runs in four quarters (a 32-column slice x four of the eight row blocks), each with
+            // 16 MFMAs that carry a quarter of the step's LDS stores, dequantisation and global loads between them;
+            // at most four activation operands are live at a time (256 registers without spilling)
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                const int i = qd >> 1, bh = qd & 1;
+                if (bh == 0) b_read(stage, i);
+                compute_rows(stage, i, bh * 4, bh * 4 + 4);
+                a_store(set, stage ^ 1, qd, qd + 1);
+                if constexpr (BSRC == 0) b_store_dense(set, stage ^ 1, qd, qd + 1);
+                else b_store_packed(0, (u + 1) & 1, stage ^ 1, i, i + 1, bh, bh + 1);
+                a_load(set, t + 1 + PD, qd, qd + 1);
+                if constexpr (BSRC == 0) b_load_dense(set, t + 1 + PD, qd, qd + 1);
+                else if (qd == 3 && (u & 1) == 0) b_load_packed(0, (t >> 1) + PD);
+                if (bh == 0) __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+                else __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+                if constexpr (BSRC != 0) __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            __syncthreads();
+            return;
+        }
+        if constexpr (BSRC != 0 && MBW == 4) {
+            // short packed tile: two halves (a 32-column slice each), each with 16 MFMAs that carry one tile-row to
+            // dequantise, half of the activation staging and, every other step, the next chunk's loads
+            const int cset = PD == 2 ? (((u + 1) >> 1) & 1) : 0;    // set of chunk (t+1) >> 1, stored half (t+1) & 1
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                b_read(stage, h);
+                compute_rows(stage, h, 0, MBW);
+                a_store(set, stage ^ 1, h, h + 1);
+                b_store_packed(cset, (u + 1) & 1, stage ^ 1, h, h + 1);
+                a_load(set, t + 1 + PD, h, h + 1);
+                if (h == 1 && (u & 1) == 0) b_load_packed(cset, (t >> 1) + PD);   // the chunk just finished leaves its registers
+                __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            __syncthreads();
+            return;
+        }
+        // short dense tile
         compute(stage);
         a_store(set, stage ^ 1);
-        if constexpr (BSRC == 0) {
-            b_store_dense(set, stage ^ 1);
-            a_load(set, t + 1 + PD);
-            b_load_dense(set, t + 1 + PD);
-        } else {
-            const int cset = PD == 2 ? (((u + 1) >> 1) & 1) : 0;    // set of chunk (t+1) >> 1
-            b_store_packed(cset, (u + 1) & 1, stage ^ 1);           // its half (t+1) & 1
-            a_load(set, t + 1 + PD);
-            if ((u & 1) == 0) b_load_packed(cset, (t >> 1) + PD);   // the chunk just finished leaves its registers
-        }
-        if constexpr (MBW == 4 && BSRC == 0) {
+        b_store_dense(set, stage ^ 1);
+        a_load(set, t + 1 + PD);
+        b_load_dense(set, t + 1 + PD);
+        {
             // Requested instruction order of the step: the first slice's operand reads, then the MFMAs in groups with one
             // LDS store, one global load and a few of the second slice's reads between them.  Left to itself the compiler
             // puts all stores after all MFMAs, and both wavefronts of a SIMD then leave the matrix pipe idle together.
@@ -236,8 +298,16 @@ __global__ __launch_bounds__(kThreads, 2) void tile_gemm_kernel(const TileParams
     if constexpr (BSRC == 0) b_load_dense(0, 0); else b_load_packed(0, 0);
     a_store(0, 0);
     if constexpr (BSRC == 0) b_store_dense(0, 0); else b_store_packed(0, 0, 0);
-    a_load(0, 1);
-    if constexpr (BSRC == 0) b_load_dense(0, 1);
+    if constexpr (BSRC == 0 && MBW == 8) {                   // the tall dense step issues its loads piece by piece
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            a_load(0, 1, qd, qd + 1);
+            b_load_dense(0, 1, qd, qd + 1);
+        }
+    } else {
+        a_load(0, 1);
+        if constexpr (BSRC == 0) b_load_dense(0, 1);
+    }
     if constexpr (PD == 2) {
         if constexpr (BSRC != 0) b_load_packed(1, 1);
         a_load(1, 2);
@@ -292,12 +362,12 @@ hipError_t launch_tile_inst(const TileParams& tp, dim3 grid, hipStream_t st) {
 // rows16: 16-row blocks per wavefront (4 or 8), 0 = choose.
 hipError_t launch_tile(TileParams& tp, int bsrc, int64_t M, int rows16, hipStream_t st) {
     // 128- or 256-row tiles: one workgroup runs per compute unit, so the launch takes rounds of 256 tiles; a 256-row
-    // tile takes about 1.85 times as long as a 128-row one (it halves the unpack and operand traffic per flop), so it
-    // pays when it does not waste most of a round (measured on the 8B shapes at 1024 and 4096 rows).
+    // tile takes about 1.5 times as long as a 128-row one (it halves the unpack and operand traffic per flop), so it
+    // pays unless it wastes most of a round (measured on the 8B and 70B shapes at 512 to 4096 rows).
     const int64_t xb = (tp.N + kTN - 1) / kTN;
     const int64_t r_short = (xb * ((M + 127) / 128) * tp.split_k + 255) / 256;
     const int64_t r_tall = (xb * ((M + 255) / 256) * tp.split_k + 255) / 256;
-    const bool tall = rows16 ? rows16 == 8 : (M > 128 && 1.85 * (double)r_tall < (double)r_short);
+    const bool tall = rows16 ? rows16 == 8 : (M > 128 && 1.5 * (double)r_tall < (double)r_short);
     const int tm = tall ? 256 : 128;
     tp.XB = (int)xb;
     tp.ZB = (int)((M + tm - 1) / tm);
@@ -334,6 +404,7 @@ hipError_t launch_linear_tile(const LinearArgs& a, const LinearPlan& p, hipStrea
     tp.G = (int)(a.K / a.g);
     tp.cpg = (int)(a.g / kChunkK);
     tp.cpg_inv = tp.cpg == 1 ? 0u : (uint32_t)(((uint64_t)1 << 32) / (uint32_t)tp.cpg) + 1u;
+    tp.cpg_one = tp.cpg == 1 ? 0xFFFFFFFFu : 0u;
     tp.KL = (int)(a.K / (a.bits == 4 ? 128 : 64));
     tp.b_bytes = (uint32_t)((size_t)a.N * a.K * a.bits / 8);
     tp.sc_bytes = (uint32_t)((size_t)a.N * tp.G * 2);
@@ -349,7 +420,7 @@ hipError_t launch_gemm_fp16(const void* A, const void* W, void* C, float* worksp
     fill_common(tp, A, C, workspace, M, N, K, split_k);
     tp.B = W;
     tp.scales = static_cast<const half_t*>(W);           // unused by the dense source; any valid pointer
-    tp.G = 1; tp.cpg = 1; tp.cpg_inv = 0; tp.KL = 0;
+    tp.G = 1; tp.cpg = 1; tp.cpg_inv = 0; tp.cpg_one = 0xFFFFFFFFu; tp.KL = 0;
     tp.b_bytes = 0;
     tp.sc_bytes = 16;
     hipError_t e = launch_tile(tp, 0, M, 0, st);
