@@ -265,7 +265,7 @@ def test_linear_tile_kernel(rtn, bits, g, M):
     codes, scales, qw, sc, gg = _oracle_operands(N, K, bits, g, seed=8)
     A_t = synth.activation(M, K, seed=300 + M, device=DEV)
     ref = O.rtn_linear(_to_np(A_t), codes, scales, gg)
-    for split in (1, 2, 5):
+    for split in (1, 2, 3, 5):              # 20 chunks of 128 columns: 20, 10, 7/7/6 (odd: the loop's two-step tail), 4
         for rows16 in (0, 4, 8):            # tile height: chosen from M, 128 rows, 256 rows
             cfg = dict(path=4, split_k=split, m_rows16=rows16)
             C = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=cfg)
