@@ -174,12 +174,20 @@ __global__ __launch_bounds__(64 * WV, WV <= 8 ? 2 : 4) void wide_mfma_kernel(con
         const uint8_t* abase = lds_a + (t & 1) * BUF_BYTES + (nl * 16) * 16;
         // the group, or this workgroup's share of it, ends with this step
         const bool ends = G1 ? true : ((--left == 0) || (t == T - 1));
+        // the activation operands of a 32-column slice are read one slice ahead of the MFMAs that use them
+        half8_t a_next[MB];
+#pragma unroll
+        for (int b = 0; b < MB; ++b) a_next[b] = *reinterpret_cast<const half8_t*>(abase + (b * 256 + (kq ^ nl)) * 16);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             half8_t a[MB];
 #pragma unroll
-            for (int b = 0; b < MB; ++b)
-                a[b] = *reinterpret_cast<const half8_t*>(abase + (b * 256 + ((i * 4 + kq) ^ nl)) * 16);
+            for (int b = 0; b < MB; ++b) a[b] = a_next[b];
+            if (i < 3) {
+#pragma unroll
+                for (int b = 0; b < MB; ++b)
+                    a_next[b] = *reinterpret_cast<const half8_t*>(abase + (b * 256 + (((i + 1) * 4 + kq) ^ nl)) * 16);
+            }
 #pragma unroll
             for (int r = 0; r < NBW; ++r) {
                 half8_t bw;
@@ -192,6 +200,7 @@ __global__ __launch_bounds__(64 * WV, WV <= 8 ? 2 : 4) void wide_mfma_kernel(con
                 }
                 if (i == 3 && ends && r > 0) scale_row(slot, r - 1);     // overlaps the next tile-row's MFMAs
             }
+            if (i < 3) __builtin_amdgcn_sched_barrier(0);                // keeps the next slice's reads ahead of this slice's MFMAs
         }
         if (ends) {
             scale_row(slot, NBW - 1);
