@@ -198,14 +198,6 @@ __global__ __launch_bounds__(kThreads, 2) void tile_gemm_kernel(const TileParams
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[b][r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[b], bq[r], acc[b][r], 0, 0, 0);
     };
-    auto compute_slice = [&](int stage, int i) {              // one 32-column slice of the step
-        b_read(stage, i);
-        compute_rows(stage, i, 0, MBW);
-    };
-    auto compute = [&](int stage) {
-        compute_slice(stage, 0);
-        compute_slice(stage, 1);
-    };
 
     // One step: arithmetic on stage (t & 1) while the next step's tiles go from registers into the other stage
     // and the loads of step t+1+PD (chunk c+PD) are issued.  u = t & 3 is a literal at every call site.
@@ -254,40 +246,42 @@ __global__ __launch_bounds__(kThreads, 2) void tile_gemm_kernel(const TileParams
                 a_load(set, t + 1 + PD, h, h + 1);
                 if (h == 1 && (u & 1) == 0) b_load_packed(cset, (t >> 1) + PD);   // the chunk just finished leaves its registers
                 __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);
-                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);
-                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+#pragma unroll
+                for (int o = 0; o < 2; ++o) {                            // one operand: 2 MFMAs per 4 vector ops, then its store
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                    if (o == 0) {
+                        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                    }
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
             __syncthreads();
             return;
         }
-        // short dense tile
-        compute(stage);
-        a_store(set, stage ^ 1);
-        b_store_dense(set, stage ^ 1);
-        a_load(set, t + 1 + PD);
-        b_load_dense(set, t + 1 + PD);
-        {
-            // Requested instruction order of the step: the first slice's operand reads, then the MFMAs in groups with one
-            // LDS store, one global load and a few of the second slice's reads between them.  Left to itself the compiler
-            // puts all stores after all MFMAs, and both wavefronts of a SIMD then leave the matrix pipe idle together.
-            constexpr int NR = 2 * (MBW + 4), NM = 2 * MBW * 4, NW = NA + 4;
-            __builtin_amdgcn_sched_group_barrier(0x100, NR / 2, 0);
+        // short dense tile: two halves, each with 16 MFMAs that carry three of the step's six LDS stores and global loads
 #pragma unroll
-            for (int i = 0; i < NW; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, NM / NW, 0);
+        for (int h = 0; h < 2; ++h) {
+            b_read(stage, h);
+            compute_rows(stage, h, 0, MBW);
+            a_store(set, stage ^ 1, h, h + 1);
+            b_store_dense(set, stage ^ 1, 2 * h, 2 * h + 2);
+            a_load(set, t + 1 + PD, h, h + 1);
+            b_load_dense(set, t + 1 + PD, 2 * h, 2 * h + 2);
+            __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, (NR / 2 + NW - 1) / NW, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
     };
@@ -304,14 +298,20 @@ __global__ __launch_bounds__(kThreads, 2) void tile_gemm_kernel(const TileParams
             a_load(0, 1, qd, qd + 1);
             b_load_dense(0, 1, qd, qd + 1);
         }
+    } else if constexpr (BSRC == 0) {                        // the short dense step issues its loads half by half
+#pragma unroll
+        for (int s = 0; s < PD; ++s)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                a_load(s, 1 + s, h, h + 1);
+                b_load_dense(s, 1 + s, 2 * h, 2 * h + 2);
+            }
     } else {
         a_load(0, 1);
-        if constexpr (BSRC == 0) b_load_dense(0, 1);
-    }
-    if constexpr (PD == 2) {
-        if constexpr (BSRC != 0) b_load_packed(1, 1);
-        a_load(1, 2);
-        if constexpr (BSRC == 0) b_load_dense(1, 2);
+        if constexpr (PD == 2) {
+            b_load_packed(1, 1);
+            a_load(1, 2);
+        }
     }
     __syncthreads();
 
@@ -362,12 +362,13 @@ hipError_t launch_tile_inst(const TileParams& tp, dim3 grid, hipStream_t st) {
 // rows16: 16-row blocks per wavefront (4 or 8), 0 = choose.
 hipError_t launch_tile(TileParams& tp, int bsrc, int64_t M, int rows16, hipStream_t st) {
     // 128- or 256-row tiles: one workgroup runs per compute unit, so the launch takes rounds of 256 tiles; a 256-row
-    // tile takes about 1.5 times as long as a 128-row one (it halves the unpack and operand traffic per flop), so it
-    // pays unless it wastes most of a round (measured on the 8B and 70B shapes at 512 to 4096 rows).
+    // tile takes about 1.5 times as long as a 128-row one with packed weights (it halves the unpacking per flop) and
+    // 1.7 times with dense ones, so it pays unless it wastes most of a round (measured on the 8B and 70B shapes at
+    // 512 to 8192 rows).
     const int64_t xb = (tp.N + kTN - 1) / kTN;
     const int64_t r_short = (xb * ((M + 127) / 128) * tp.split_k + 255) / 256;
     const int64_t r_tall = (xb * ((M + 255) / 256) * tp.split_k + 255) / 256;
-    const bool tall = rows16 ? rows16 == 8 : (M > 128 && 1.5 * (double)r_tall < (double)r_short);
+    const bool tall = rows16 ? rows16 == 8 : (M > 128 && (bsrc == 0 ? 1.7 : 1.5) * (double)r_tall < (double)r_short);
     const int tm = tall ? 256 : 128;
     tp.XB = (int)xb;
     tp.ZB = (int)((M + tm - 1) / tm);
