@@ -131,16 +131,18 @@ rtn_status rtn_linear(const void* dev_A, int64_t M, const void* dev_qweight, con
 typedef struct {
     int path;      /* 0 auto, 1 MFMA skinny kernel, 2 vector-ALU dot-product kernel (M <= 4), 3 wide MFMA kernel
                       (group_size a multiple of 128; uses split_k, m_rows16 = 2..4, n_tiles16 and waves_n = 4, 8 or -- with
-                      n_tiles16 = 1 -- 16 wavefronts per workgroup), 4 tile kernel: 128 x 256 or
+                      n_tiles16 = 1 -- 16 wavefronts per workgroup; also m_rows16 = 8 with n_tiles16 = 2 and waves_n = 8:
+                      128 rows per workgroup, weights scaled in fp16 before the MFMA as in path 4, never chosen
+                      automatically), 4 tile kernel: 128 x 256 or
                       256 x 256 output tiles, weights dequantised to fp16 in LDS (group_size a multiple of 128; uses split_k and
                       m_rows16 = 4 or 8 for the tile height, 0 = chosen from M) */
     int prefetch;  /* k-chunks (4 KiB each) a wavefront keeps in flight: 1, 2 or 4 */
     int waves_n;   /* wavefronts of a workgroup along N (share the staged activations): 1, 2, 4, 8, 16 (a power of two) */
     int waves_k;   /* wavefronts of a workgroup along K (in-workgroup split-K): 1 .. 16; waves_n * waves_k <= 16 */
     int split_k;   /* workgroups along K (global split-K, reduced through the workspace) */
-    int m_rows16;  /* 16-row activation blocks each wavefront multiplies per weight tile: 1, 2 or 4 (path 3: 2, 3, 4) */
+    int m_rows16;  /* 16-row activation blocks each wavefront multiplies per weight tile: 1, 2 or 4 (path 3: 2, 3, 4, 8) */
     int n_tiles16; /* path 3: 16-column weight tile-rows per wavefront (share each activation operand): 1, 2 or 4;
-                      m_rows16 * n_tiles16 <= 8 */
+                      m_rows16 * n_tiles16 <= 8 (or 8 x 2) */
 } rtn_linear_cfg;
 
 rtn_status rtn_linear_ex(const void* dev_A, int64_t M, const void* dev_qweight, const void* dev_scales,

@@ -58,7 +58,10 @@ struct WideParams {
 // At least two wavefronts per SIMD (256 registers each): the MFMAs then keep their accumulators in ordinary
 // vector registers, where the scale multiply-add can read them directly.
 // ZP: asymmetric variant -- the integer zero point of the step's group goes into the unpack (operand = q + Z).
-template <int BITS, int MB, int NBW, bool G1, int WV, bool ZP = false>
+// PS: the weights are scaled in fp16 on their way into the MFMA (fp16(q S), one rounding per weight, as in the tile
+// kernel) instead of the group's partial sums in fp32: no second accumulator set, which is what lets a wavefront own
+// 128 rows (MB = 8: every unpacked operand feeds 8 MFMAs, and 4 scale multiplies replace 32 multiply-adds).
+template <int BITS, int MB, int NBW, bool G1, int WV, bool ZP = false, bool PS = false>
 __global__ __launch_bounds__(64 * WV, WV <= 8 ? 2 : 4) void wide_mfma_kernel(const WideParams p) {
     constexpr int TK = Layout<BITS>::TK;
     constexpr int MPT = Layout<BITS>::MFMA_PER_TILE;
@@ -144,22 +147,25 @@ __global__ __launch_bounds__(64 * WV, WV <= 8 ? 2 : 4) void wide_mfma_kernel(con
         }
     };
 
-    float4_t acc[MB][NBW], part[MB][NBW];
+    constexpr int NPART = PS ? 1 : MB;                    // no per-group partial sums when the weights are pre-scaled
+    float4_t acc[MB][NBW], part[NPART][NBW];
 #pragma unroll
     for (int b = 0; b < MB; ++b)
 #pragma unroll
         for (int r = 0; r < NBW; ++r) {
             acc[b][r] = (float4_t){0.f, 0.f, 0.f, 0.f};
-            part[b][r] = (float4_t){0.f, 0.f, 0.f, 0.f};
+            if (b < NPART) part[b][r] = (float4_t){0.f, 0.f, 0.f, 0.f};
         }
 
     auto scale_row = [&](int slot, int r) {
-        const float sc = (float)__builtin_bit_cast(half_t, sbuf[slot][r]);
+        if constexpr (!PS) {
+            const float sc = (float)__builtin_bit_cast(half_t, sbuf[slot][r]);
 #pragma unroll
-        for (int b = 0; b < MB; ++b) {
+            for (int b = 0; b < MB; ++b) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc[b][r][e] = fmaf(sc, part[b][r][e], acc[b][r][e]);
-            if constexpr (!G1) part[b][r] = (float4_t){0.f, 0.f, 0.f, 0.f};
+                for (int e = 0; e < 4; ++e) acc[b][r][e] = fmaf(sc, part[b][r][e], acc[b][r][e]);
+                if constexpr (!G1) part[b][r] = (float4_t){0.f, 0.f, 0.f, 0.f};
+            }
         }
     };
 
@@ -172,6 +178,39 @@ __global__ __launch_bounds__(64 * WV, WV <= 8 ? 2 : 4) void wide_mfma_kernel(con
         w_load((slot + 2) % 3, t + 2);
         __builtin_amdgcn_sched_barrier(0);                // keep the prefetch ahead of this step's arithmetic
         const uint8_t* abase = lds_a + (t & 1) * BUF_BYTES + (nl * 16) * 16;
+        if constexpr (PS) {
+            // pre-scaled weights: a 32-column slice is NBW scaled operands against the row blocks, four blocks at a time
+            constexpr int HB = MB > 4 ? 4 : MB, NH = MB / HB;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                half8_t bw[NBW];
+#pragma unroll
+                for (int r = 0; r < NBW; ++r) {
+                    Half8Words h;
+                    h.v = unpack_operand<BITS>(wbuf[slot][r][i / MPT], i % MPT, magic);
+                    const half_t sh = __builtin_bit_cast(half_t, sbuf[slot][r]);
+                    const half2_t s2 = {sh, sh};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) h.h2[e] = h.h2[e] * s2;
+                    bw[r] = h.v;
+                }
+#pragma unroll
+                for (int hb = 0; hb < NH; ++hb) {
+                    half8_t a[HB];
+#pragma unroll
+                    for (int b = 0; b < HB; ++b)
+                        a[b] = *reinterpret_cast<const half8_t*>(abase + ((hb * HB + b) * 256 + ((i * 4 + kq) ^ nl)) * 16);
+#pragma unroll
+                    for (int r = 0; r < NBW; ++r)
+#pragma unroll
+                        for (int b = 0; b < HB; ++b)
+                            acc[hb * HB + b][r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[b], bw[r], acc[hb * HB + b][r], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            __syncthreads();
+            return;
+        }
         // the group, or this workgroup's share of it, ends with this step
         const bool ends = G1 ? true : ((--left == 0) || (t == T - 1));
         // the activation operands of a 32-column slice are read one slice ahead of the MFMAs that use them
@@ -289,9 +328,16 @@ hipError_t launch_wide_wv(const WideParams& wp, int wv, dim3 grid, hipStream_t s
     return hipErrorInvalidValue;
 }
 
-// Register tiles of up to 8 accumulator blocks (MB * NBW <= 8) fit 256 registers without spilling.
+// Register tiles of up to 8 accumulator blocks (MB * NBW <= 8) fit 256 registers without spilling; the 128 x 32 tile
+// (16 blocks) does with pre-scaled weights, which need no second accumulator set.
 template <int BITS>
 hipError_t launch_wide_bits(const WideParams& wp, int mb, int nbw, int wv, dim3 grid, hipStream_t st) {
+    if (mb == 8) {
+        if (nbw != 2 || wv != 8) return hipErrorInvalidValue;
+        if (wp.spg == 1) hipLaunchKernelGGL((wide_mfma_kernel<BITS, 8, 2, true, 8, false, true>), grid, dim3(64 * 8), 0, st, wp);
+        else hipLaunchKernelGGL((wide_mfma_kernel<BITS, 8, 2, false, 8, false, true>), grid, dim3(64 * 8), 0, st, wp);
+        return hipGetLastError();
+    }
     switch (mb * 10 + nbw) {
         case 21: return launch_wide_wv<BITS, 2, 1>(wp, wv, grid, st);
         case 22: return launch_wide_wv<BITS, 2, 2>(wp, wv, grid, st);
@@ -308,6 +354,9 @@ hipError_t launch_wide_bits(const WideParams& wp, int mb, int nbw, int wv, dim3 
 
 bool wide_plan_valid(const LinearArgs& a, const LinearPlan& p) {
     if (a.g % kStepK != 0) return false;
+    if (p.m_rows16 == 8) {                                // 128 x 32 register tile, pre-scaled weights
+        return !a.zeros && p.n_tiles16 == 2 && p.waves_n == 8 && p.split_k >= 1 && p.split_k <= a.K / kStepK;
+    }
     if (p.m_rows16 < 2 || p.m_rows16 > 4) return false;
     if (p.n_tiles16 != 1 && p.n_tiles16 != 2 && p.n_tiles16 != 4) return false;
     if (p.m_rows16 * p.n_tiles16 > 8) return false;       // register tile: at most 8 accumulator blocks

@@ -256,6 +256,26 @@ def test_linear_wide_kernel(rtn, bits, g, M):
 
 
 @pytest.mark.parametrize("bits,g", [(4, 128), (4, 256), (4, 0), (8, 128), (8, 0)])
+@pytest.mark.parametrize("M", [20, 128, 130, 300])
+def test_linear_wide_kernel_128_rows(rtn, bits, g, M):
+    """The wide kernel's 128-row register tile (explicit configuration only): weights scaled in fp16 before the MFMA,
+    row blocks in two halves; ragged M and N, K split with uneven shares."""
+    N, K = 400, 2560
+    codes, scales, qw, sc, gg = _oracle_operands(N, K, bits, g, seed=9)
+    A_t = synth.activation(M, K, seed=400 + M, device=DEV)
+    ref = O.rtn_linear(_to_np(A_t), codes, scales, gg)
+    for split in (1, 3, 4):
+        cfg = dict(path=3, m_rows16=8, n_tiles16=2, waves_n=8, split_k=split)
+        C = rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=cfg)
+        torch.cuda.synchronize()
+        H.assert_linear_close(_to_np(C), ref, f"bits={bits} g={g} M={M} cfg={cfg}")
+    assert torch.equal(C, rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=cfg))
+    for bad in (dict(path=3, m_rows16=8, n_tiles16=1, waves_n=8), dict(path=3, m_rows16=8, n_tiles16=2, waves_n=4)):
+        with pytest.raises(rtn.RtnError):
+            rtn.rtn_linear(A_t, qw, sc, bits, g, cfg=bad)
+
+
+@pytest.mark.parametrize("bits,g", [(4, 128), (4, 256), (4, 0), (8, 128), (8, 0)])
 @pytest.mark.parametrize("M", [3, 64, 128, 130, 300])
 def test_linear_tile_kernel(rtn, bits, g, M):
     """The tile kernel (path 4): both tile heights, ragged M and N (a partly empty last tile in both directions), K
