@@ -83,15 +83,17 @@ def report(args, rtn, synth, torch, np, dev) -> int:
     """Per (matrix, M): launch time, weight-stream GB/s, % of the 8 TB/s HBM peak, useful TFLOP/s; and per layer set."""
     shapes = {"8b": synth.LLAMA_8B, "70b": synth.LLAMA_70B, "405b": synth.LLAMA_405B}[args.report]
     std = {"8b": 0.02, "70b": 0.02, "405b": 0.01}[args.report]
-    bits = args.bits
-    g = 128 if bits == 4 else 0
     Ms = [int(x) for x in args.batches.split(",")]
     ws = torch.empty(16 << 20, dtype=torch.uint8, device=dev)
     tot = {M: 0.0 for M in Ms}
     totb = 0
-    print(f"# {args.report} shapes, int{bits} {'group 128' if bits == 4 else 'per-channel'}; launches rotate over >= 600 MB of "
+    what = ("selective precision: qkv and gate_up int4 group 128, o and down int8 per-channel" if args.selective
+            else f"int{args.bits} {'group 128' if args.bits == 4 else 'per-channel'}")
+    print(f"# {args.report} shapes, {what}; launches rotate over >= 600 MB of "
           f"distinct packed copies; HIP-graph replay; times include the ~1.5 us dispatch gap")
     for idx, (name, (K, N)) in enumerate(shapes.items()):
+        bits = 8 if args.selective and name in ("o", "down") else (4 if args.selective else args.bits)
+        g = 128 if bits == 4 else 0
         W = synth.normal_weight(N, K, std, idx, dev)
         qw, sc = rtn.rtn_quantize(W, bits, g)
         del W
@@ -105,7 +107,7 @@ def report(args, rtn, synth, torch, np, dev) -> int:
             tot[M] += t
             t_hot = _time_linear(rtn, torch, np, A, qws[:1], sc, bits, g, None, ws, reps=12) if args.hot else None
             plan = rtn.rtn_linear_query(M, N, K, bits, g)
-            line = (f"{name:8s} {K:6d}->{N:6d} M={M:3d}  {t:8.2f} us  {nbytes / t / 1e3:7.0f} GB/s  "
+            line = (f"{name:8s} {'int' + str(bits) if args.selective else '':4s} {K:6d}->{N:6d} M={M:3d}  {t:8.2f} us  {nbytes / t / 1e3:7.0f} GB/s  "
                     f"{nbytes / t / 80e3:5.1f} %  {2.0 * M * N * K / t / 1e6:7.2f} TFLOP/s  ")
             if plan["path"] == 3:
                 line += (f"wide {plan['waves_n']} waves x {16 * plan['m_rows16']}x{16 * plan['n_tiles16']} split {plan['split_k']}")
@@ -326,6 +328,8 @@ def main() -> int:
     ap.add_argument("--report-grouped", action="store_true",
                     help="instead of the JSON line, time expert-like independent modules serially and through the grouped call")
     ap.add_argument("--bits", type=int, default=4, help="--report only: 4 (group 128) or 8 (per-channel)")
+    ap.add_argument("--selective", action="store_true",
+                    help="--report only: the selective-precision layer (modules 2 and 4 at 8 bit per-channel, the others at 4 bit g128)")
     ap.add_argument("--batches", type=str, default="1,2,4,8,16", help="--report only")
     ap.add_argument("--hot", action="store_true",
                     help="--report only: also time launches on a single weight copy (cache-resident when it fits the 256 MB Infinity Cache)")
