@@ -207,22 +207,26 @@ __global__ __launch_bounds__(1024) void quantize_large_group_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
-// Medium and wide groups (the per-channel case): a workgroup of 16 wavefronts owns ROWS rows of a (row-tile, group)
+// Medium and wide groups (the per-channel case): a workgroup of NW wavefronts owns ROWS rows of a (row-tile, group)
 // unit and keeps that ROWS x g block in registers between the amax pass and the packing pass (LPL 16-byte loads
-// per lane, 16 KiB x LPL per workgroup), so W is read exactly once.  ROWS = 16: g up to 14336; ROWS = 8 or 4 (two or
-// four workgroups per row-tile, each writing its 128- or 64-byte runs of every tile): g up to 28672 or 57344.
+// per lane, NW KiB x LPL per workgroup), so W is read exactly once.  Blocks of up to 8 loads per lane: 16 wavefronts,
+// all 16 rows.  Larger blocks, g up to 14336 or 28672: 8 wavefronts and 8 or 4 rows (two or four workgroups per
+// row-tile, each writing its 128- or 64-byte runs of every tile), so that two or three workgroups share a compute
+// unit and one loads while another packs and stores -- a single 16-wavefront workgroup per compute unit alternates
+// between the two (measured on the 70B and 405B shapes: 4.1-6.4 TB/s against 3.3-5.1).  g up to 57344: 16 wavefronts
+// and 4 rows (8 wavefronts would leave 32-byte runs, which halves the rate).
 // A wavefront covers 16 / ROWS consecutive tiles per step (lane -> row nl % ROWS of tile nl / ROWS); tiles past the
 // end of the group are neither loaded nor stored.
 // ---------------------------------------------------------------------------------------
-template <int BITS, int LPL, int ROWS>
-__global__ __launch_bounds__(1024) void quantize_resident_group_kernel(
+template <int BITS, int LPL, int ROWS, int NW = 16>
+__global__ __launch_bounds__(64 * NW) void quantize_resident_group_kernel(
     const half_t* __restrict__ W, uint8_t* __restrict__ qweight, half_t* __restrict__ scales,
     int64_t N, int64_t K, int64_t g, float divisor) {
     constexpr int TK = Layout<BITS>::TK;
     constexpr int OPT = TK / 32;
     constexpr int TPW = LPL / OPT;                        // steps per wavefront
     constexpr int TPS = 16 / ROWS;                        // tiles per wavefront per step, row blocks per row-tile
-    __shared__ float row_max[16][ROWS];                   // [wave][row]
+    __shared__ float row_max[NW][ROWS];                   // [wave][row]
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nl = lane & 15, kq = lane >> 4;
     const int rl = nl % ROWS, sub = nl / ROWS;
@@ -237,7 +241,7 @@ __global__ __launch_bounds__(1024) void quantize_resident_group_kernel(
     u32x4_t raw[TPW][OPT];
 #pragma unroll
     for (int i = 0; i < TPW; ++i) {
-        const int tp = (wave + 16 * i) * TPS + sub;
+        const int tp = (wave + NW * i) * TPS + sub;
 #pragma unroll
         for (int t = 0; t < OPT; ++t) {
             raw[i][t] = u32x4_t{0u, 0u, 0u, 0u};
@@ -258,7 +262,7 @@ __global__ __launch_bounds__(1024) void quantize_resident_group_kernel(
     __syncthreads();
     m = 0.0f;
 #pragma unroll
-    for (int w = 0; w < 16; ++w) m = fmaxf(m, row_max[w][rl]);
+    for (int w = 0; w < NW; ++w) m = fmaxf(m, row_max[w][rl]);
     const float s = scale_from_amax(m, divisor);
     const float r = group_reciprocal(s);
     if (wave == 0 && kq == 0 && sub == 0) scales[row * G + j] = (half_t)s;
@@ -266,7 +270,7 @@ __global__ __launch_bounds__(1024) void quantize_resident_group_kernel(
     uint8_t* dst = qweight + ((nt * KT + j * TPG) * 64 + kq * 16 + hb * ROWS + rl) * 16;
 #pragma unroll
     for (int i = 0; i < TPW; ++i) {
-        const int tp = (wave + 16 * i) * TPS + sub;
+        const int tp = (wave + NW * i) * TPS + sub;
         u32x4_t chunk;
         uint32_t words[4];
 #pragma unroll
@@ -322,19 +326,22 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint8_t* __restrict__
 }
 
 template <int BITS, int ROWS>
-static void launch_resident_rows(int64_t lpl, dim3 grid, dim3 block, hipStream_t st, const half_t* w, uint8_t* q, half_t* s,
-                                 int64_t N, int64_t K, int64_t g, float divisor) {
-    if (lpl <= 8) hipLaunchKernelGGL((quantize_resident_group_kernel<BITS, 8, ROWS>), grid, block, 0, st, w, q, s, N, K, g, divisor);
-    else if (lpl <= 16) hipLaunchKernelGGL((quantize_resident_group_kernel<BITS, 16, ROWS>), grid, block, 0, st, w, q, s, N, K, g, divisor);
-    else hipLaunchKernelGGL((quantize_resident_group_kernel<BITS, 28, ROWS>), grid, block, 0, st, w, q, s, N, K, g, divisor);
+static void launch_resident_rows8(int64_t lpl, dim3 grid, hipStream_t st, const half_t* w, uint8_t* q, half_t* s,
+                                  int64_t N, int64_t K, int64_t g, float divisor) {
+    dim3 block(512);
+    if (lpl <= 16) hipLaunchKernelGGL((quantize_resident_group_kernel<BITS, 16, ROWS, 8>), grid, block, 0, st, w, q, s, N, K, g, divisor);
+    else hipLaunchKernelGGL((quantize_resident_group_kernel<BITS, 28, ROWS, 8>), grid, block, 0, st, w, q, s, N, K, g, divisor);
 }
 
+// rows == 16: 16 wavefronts and at most 8 loads per lane; 8 wavefronts: 8 or 4 rows, 16 or 28 loads per lane;
+// 16 wavefronts and 4 rows: 28 loads per lane
 template <int BITS>
-static void launch_resident(int rows, int64_t lpl, dim3 grid, dim3 block, hipStream_t st, const half_t* w, uint8_t* q, half_t* s,
+static void launch_resident(int rows, int nw, int64_t lpl, dim3 grid, hipStream_t st, const half_t* w, uint8_t* q, half_t* s,
                             int64_t N, int64_t K, int64_t g, float divisor) {
-    if (rows == 16) launch_resident_rows<BITS, 16>(lpl, grid, block, st, w, q, s, N, K, g, divisor);
-    else if (rows == 8) launch_resident_rows<BITS, 8>(lpl, grid, block, st, w, q, s, N, K, g, divisor);
-    else launch_resident_rows<BITS, 4>(lpl, grid, block, st, w, q, s, N, K, g, divisor);
+    if (rows == 16) hipLaunchKernelGGL((quantize_resident_group_kernel<BITS, 8, 16, 16>), grid, dim3(1024), 0, st, w, q, s, N, K, g, divisor);
+    else if (nw == 16) hipLaunchKernelGGL((quantize_resident_group_kernel<BITS, 28, 4, 16>), grid, dim3(1024), 0, st, w, q, s, N, K, g, divisor);
+    else if (rows == 8) launch_resident_rows8<BITS, 8>(lpl, grid, st, w, q, s, N, K, g, divisor);
+    else launch_resident_rows8<BITS, 4>(lpl, grid, st, w, q, s, N, K, g, divisor);
 }
 
 template <int BITS>
@@ -362,15 +369,22 @@ static hipError_t launch_quantize_bits(const void* W, int64_t N, int64_t K, int6
         if (tpg == 1) hipLaunchKernelGGL((quantize_small_group_kernel<BITS, 1, 1>), grid, block, 0, st, w, q, s, N, K, units, divisor);
         else if (tpg == 2) hipLaunchKernelGGL((quantize_small_group_kernel<BITS, 2, 1>), grid, block, 0, st, w, q, s, N, K, units, divisor);
         else hipLaunchKernelGGL((quantize_small_group_kernel<BITS, 4, 1>), grid, block, 0, st, w, q, s, N, K, units, divisor);
-    } else if (tpg * (TK / 32) <= 4 * 16 * 28) {
-        // the unit, or a half or a quarter of its rows, fits the registers of one 16-wavefront workgroup: 8, 16 or 28
-        // loads per lane
+    } else if (tpg * (TK / 32) <= 8 * 8 * 28) {
+        // the unit, or a half, a quarter or an eighth of its rows, fits the registers of one workgroup
         const int64_t octets = tpg * (TK / 32);
-        const int rows = octets <= 16 * 28 ? 16 : (octets <= 2 * 16 * 28 ? 8 : 4);
-        const int tps = 16 / rows;
-        const int64_t lpl = ((tpg + 16 * tps - 1) / (16 * tps)) * (TK / 32);
-        dim3 grid((unsigned)(units * tps)), block(1024);
-        launch_resident<BITS>(rows, lpl, grid, block, st, w, q, s, N, K, g, divisor);
+        int rows = 16, nw = 16;
+        int64_t lpl = ((tpg + 15) / 16) * (TK / 32);          // 16 wavefronts, all 16 rows
+        if (lpl > 8) {
+            if (octets <= 4 * 8 * 28) {                       // 8 wavefronts, 8 or 4 rows
+                rows = octets <= 2 * 8 * 28 ? 8 : 4;
+                nw = 8;
+            } else {                                          // 16 wavefronts, 4 rows: 64-byte runs at least
+                rows = 4;
+            }
+            lpl = ((tpg + nw * (16 / rows) - 1) / (nw * (16 / rows))) * (TK / 32);
+        }
+        dim3 grid((unsigned)(units * (16 / rows)));
+        launch_resident<BITS>(rows, nw, lpl, grid, st, w, q, s, N, K, g, divisor);
     } else {
         dim3 grid((unsigned)units), block(1024);
         hipLaunchKernelGGL((quantize_large_group_kernel<BITS>), grid, block, 0, st, w, q, s, N, K, g, divisor);
