@@ -11,8 +11,10 @@
 // 2 x TM x 256 x 64 flops, 85 flop/B at TM = 128 and 128 flop/B at TM = 256 (packed int4 weights: 175 and
 // 210 flop/B), against 64 flop/B for 128 x 128 tiles.
 // K advances in steps of 64 columns through two LDS stages (one barrier per step); a row of a staged tile is
-// 128 bytes = eight 16-byte pieces, stored at piece ^ ((row >> 1) & 7) so that both the staging writes and the
-// b128 operand reads of 16 consecutive rows touch all 64 banks exactly once.  Global loads run two steps
+// 128 bytes = eight 16-byte pieces, stored at piece ^ (row & 7): conflict-free for the row-wise staging writes, for
+// the b128 operand reads (lane -> row nl, piece 4 i + kq) and for the stores of dequantised weights, which have the
+// operand pattern (16-byte stores go through 128 bytes per cycle, eight lanes at a time: with piece ^ ((row >> 1) & 7)
+// every such store took twice as long, by the bank-conflict counter).  Global loads run two steps
 // (activations, dense weights) or one 128-column chunk (packed weights) ahead of their LDS stores, in registers.
 //
 // Fused dequantisation: a packed tile is unpacked once per workgroup (not once per wavefront), multiplied by
@@ -54,7 +56,7 @@ struct TileParams {
 };
 
 __device__ __forceinline__ uint32_t swizzled(int row, int piece) {      // byte offset inside a staged tile
-    return (uint32_t)(row * 128 + ((piece ^ ((row >> 1) & 7)) * 16));
+    return (uint32_t)(row * 128 + ((piece ^ (row & 7)) * 16));
 }
 
 // BSRC: 0 = dense fp16 weights, 4 / 8 = packed codes.  MBW: 16-row blocks per wavefront along M (4 or 8).
@@ -98,7 +100,7 @@ __global__ __launch_bounds__(kThreads, 2) void tile_gemm_kernel(const TileParams
     const uint32_t magic = fp16_magic_vgpr();
 
     // ---- staging of row-major fp16 tiles (A always, B when dense): thread -> piece st_p of rows st_r + 64 i ----
-    const int st_p = tid & 7, st_r = tid >> 3;               // ((st_r + 64 i) >> 1) & 7 does not depend on i
+    const int st_p = tid & 7, st_r = tid >> 3;               // (st_r + 64 i) & 7 does not depend on i
     const uint32_t st_off = swizzled(st_r, st_p);            // + i * 64 rows * 128 bytes
     constexpr int NA = TM / 64;                              // pieces per thread per step
     u32x4_t areg[PD][NA];
@@ -179,17 +181,17 @@ __global__ __launch_bounds__(kThreads, 2) void tile_gemm_kernel(const TileParams
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc[b][r] = (float4_t){0.f, 0.f, 0.f, 0.f};
 
-    // operand rows of this lane: A rows wm*TM/2 + 16 b + nl, B rows wn*64 + 16 r + nl; ((row >> 1) & 7) == nl >> 1
+    // operand rows of this lane: A rows wm*TM/2 + 16 b + nl, B rows wn*64 + 16 r + nl; (row & 7) == (nl & 7)
     const uint32_t a_rd = (uint32_t)((wm * (TM / 2) + nl) * 128);
     const uint32_t b_rd = (uint32_t)(A_BYTES + (wn * 64 + nl) * 128);
     half8_t bq[4];
     auto b_read = [&](int stage, int i) {                     // the wavefront's four weight operands of slice i
-        const uint32_t po = (uint32_t)(((i * 4 + kq) ^ (nl >> 1)) * 16);
+        const uint32_t po = (uint32_t)(((i * 4 + kq) ^ (nl & 7)) * 16);
 #pragma unroll
         for (int r = 0; r < 4; ++r) bq[r] = *reinterpret_cast<const half8_t*>(lds + stage * STAGE + b_rd + r * 2048 + po);
     };
     auto compute_rows = [&](int stage, int i, int b0, int b1) {   // row blocks [b0, b1) of slice i against bq
-        const uint32_t po = (uint32_t)(((i * 4 + kq) ^ (nl >> 1)) * 16);
+        const uint32_t po = (uint32_t)(((i * 4 + kq) ^ (nl & 7)) * 16);
         half8_t a[MBW];
 #pragma unroll
         for (int b = b0; b < b1; ++b) a[b] = *reinterpret_cast<const half8_t*>(lds + stage * STAGE + a_rd + b * 2048 + po);
