@@ -501,14 +501,33 @@ __global__ __launch_bounds__(256) void quantize_asym_kernel(
         const int64_t kt0 = j * tiles;                    // first tile of the unit
         const half_t* src = W + n * K + kt0 * TK + kq * 8;
         AsymGroup gp[SUB];
+        // units of up to kKeep octets per lane (groups of up to 256 codes at 4 bits, 512 at 8 bits) stay in registers between the range pass and the
+        // packing pass; larger ones are read again, from cache
+        constexpr int kKeep = 8;
+        const bool resident = tiles * OPT <= kKeep;
+        u32x4_t keep[kKeep];
         if constexpr (SUB == 1) {
             uint32_t mn = kPosInf, mx = kNegInf;
-            for (int t = 0; t < tiles * OPT; ++t) {
-                const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(src + t * 32);
+            if (resident) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    mn = pk_min(mn, raw[i]);
-                    mx = pk_max(mx, raw[i]);
+                for (int t = 0; t < kKeep; ++t) {
+                    keep[t] = t < tiles * OPT ? *reinterpret_cast<const u32x4_t*>(src + t * 32) : u32x4_t{0u, 0u, 0u, 0u};
+                    if (t < tiles * OPT) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            mn = pk_min(mn, keep[t][i]);
+                            mx = pk_max(mx, keep[t][i]);
+                        }
+                    }
+                }
+            } else {
+                for (int t = 0; t < tiles * OPT; ++t) {
+                    const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(src + t * 32);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        mn = pk_min(mn, raw[i]);
+                        mx = pk_max(mx, raw[i]);
+                    }
                 }
             }
             float alpha, beta;
@@ -527,6 +546,7 @@ __global__ __launch_bounds__(256) void quantize_asym_kernel(
 #pragma unroll
                 for (int t = 0; t < OPS; ++t) {
                     const u32x4_t raw = *reinterpret_cast<const u32x4_t*>(src + (sg * OPS + t) * 32);
+                    keep[sg * OPS + t] = raw;             // one tile per unit: OPT <= kKeep octets
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         mn = pk_min(mn, raw[i]);
@@ -542,6 +562,23 @@ __global__ __launch_bounds__(256) void quantize_asym_kernel(
                     zeros[n * G + j * SUB + sg] = z16;
                 }
             }
+        }
+        if (resident) {
+#pragma unroll
+            for (int tp = 0; tp < kKeep / OPT; ++tp) {
+                if (tp < tiles) {
+                    u32x4_t o;
+#pragma unroll
+                    for (int t = 0; t < OPT; ++t) {
+                        uint32_t wd[BITS == 4 ? 1 : 2];
+                        quantize_octet_asym<BITS>(keep[tp * OPT + t], gp[SUB == 1 ? 0 : t / (OPT / SUB)], wd);
+                        if constexpr (BITS == 4) o[t] = wd[0];
+                        else { o[2 * t] = wd[0]; o[2 * t + 1] = wd[1]; }
+                    }
+                    *reinterpret_cast<u32x4_t*>(qweight + ((nt * KT + kt0 + tp) * 64 + lane) * 16) = o;
+                }
+            }
+            continue;
         }
         for (int tp = 0; tp < tiles; ++tp) {
             u32x4_t o;
