@@ -91,8 +91,9 @@ def test_quantize_adversarial(rtn, bits, g, flags):
                                  (8192, 4096), (14336, 7168), (32768, 16384), (19456, 0), (40960, 0), (53248, 0), (57344, 0),
                                  (65536, 0)])
 def test_quantize_large_groups_every_kernel(rtn, bits, K, g):
-    """Per-channel and wide groups: the register-resident kernels (8, 16, 28 loads per lane; 16, 8 or 4 rows per
-    workgroup; groups that do not fill the last wavefront's tiles) and the two-pass kernel beyond 57344 columns."""
+    """Per-channel and wide groups: the register-resident kernels (16 wavefronts x 16 rows with up to 8 loads per lane;
+    8 wavefronts x 8 or 4 rows with 16 or 28; 16 wavefronts x 4 rows with 28; groups that do not fill the last
+    wavefront's tiles) and the two-pass kernel beyond 57344 columns."""
     N = 48
     W_t = synth.heavy_tail_weight(N, K, 0.02, seed=K + bits, device=DEV)
     qw, sc, codes, scales = _quantize_both(W_t, bits, g)
