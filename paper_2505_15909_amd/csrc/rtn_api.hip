@@ -123,9 +123,14 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
                      int64_t steps_hint = 0) {
     LinearPlan p;
     p.n_tiles16 = 1;
-    // more than 16 rows: the wide kernel, except at 17-32 rows on matrices so large that the skinny kernel's
-    // pure weight streaming still wins
-    const bool wide_wins = g % 128 == 0 && (M > 32 || (M > 16 && (size_t)N * K * bits / 8 <= ((size_t)256 << 20)));
+    // more than 16 rows: the wide kernel, except at 17-32 rows on large matrices, where the skinny kernel's pure
+    // weight streaming still wins.  4 bit: from 40 MB with rows of 8192 columns and more, 16 wavefronts side by side
+    // (6-20 % faster on the 70B and 405B shapes except the 70B o matrix; the wide kernel wins on every 8B shape).
+    // 8 bit: above 256 MB, 8 wavefronts (the 16-wavefront shape is faster on some of those matrices, slower on others).
+    const size_t packed_bytes = (size_t)N * K * bits / 8;
+    const bool streams16 = M <= 32 && bits == 4 && packed_bytes >= ((size_t)40 << 20) && K >= 8192;
+    const bool streams_at_32 = streams16 || (M <= 32 && packed_bytes > ((size_t)256 << 20));
+    const bool wide_wins = g % 128 == 0 && M > 16 && !streams_at_32;
     // 128 rows and more, and enough 128 x 256 output tiles to fill 9/16 of the compute units without splitting K:
     // the tile kernel (measured against the wide kernel on the 8B, 70B and 405B shapes at M = 128 ... 4096: it wins
     // by 8-15 % from 144 tiles and loses from 128 down), unless its 128-row padding costs more than the wide
@@ -214,12 +219,12 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
             p.waves_k = rows <= 9 ? 4 : 2;
         }
     } else {
-        // more than 16 rows: wide workgroups share the staged rows; K is split across workgroups
-        // only as far as needed to occupy the compute units
-        p.waves_n = 8;
+        // more than 16 rows: wide workgroups share the staged rows (16 wavefronts on the large matrices that stay on
+        // this kernel at 17-32 rows); K is split across workgroups only as far as needed to occupy the compute units
+        p.waves_n = streams16 ? 16 : 8;
         p.waves_k = 1;
-        int64_t wgs = ((NT + 15) / 16) * p.m_blocks;
-        while (wgs * p.split_k < 256 && p.split_k * 2 <= kMaxSplitK && p.split_k * 2 <= KC &&
+        const int64_t wgs = ((NT + 15) / 16) * p.m_blocks, want = streams16 ? 140 : 256;
+        while (wgs * p.split_k < want && p.split_k * 2 <= (streams16 ? 8 : kMaxSplitK) && p.split_k * 2 <= KC &&
                (size_t)M * N * sizeof(float) * (p.split_k * 2) <= kWorkspaceCap)
             p.split_k *= 2;
     }
