@@ -94,13 +94,17 @@ __global__ __launch_bounds__(64 * WV, WV <= 8 ? 2 : 4) void wide_mfma_kernel(con
     const uint32_t magic = fp16_magic_vgpr();
 
     const int nt0 = (xb * WV + wave) * NBW;               // first tile-row of this wavefront
+    // Load addresses: the lane's part goes into the vector offset, fixed for the whole kernel (out of range once and
+    // for all for tile-rows and activation rows that do not exist); the k-step's part is wave-uniform and goes into the
+    // scalar offset, so a step's loads cost no vector instructions.  Prefetches past the workgroup's last step load
+    // that last step again (in bounds, never used).
     uint32_t w_lane[NBW], s_lane[NBW];
     bool nt_ok[NBW];
 #pragma unroll
     for (int r = 0; r < NBW; ++r) {
         nt_ok[r] = nt0 + r < p.NT;
-        w_lane[r] = (uint32_t)(nt0 + r) * (uint32_t)p.KL * 1024u + lane * 16;
-        s_lane[r] = ((uint32_t)(nt0 + r) * 16 + nl) * (uint32_t)p.G * 2u;
+        w_lane[r] = nt_ok[r] ? (uint32_t)(nt0 + r) * (uint32_t)p.KL * 1024u + lane * 16 : kOutOfRange;
+        s_lane[r] = nt_ok[r] ? ((uint32_t)(nt0 + r) * 16 + nl) * (uint32_t)p.G * 2u : kOutOfRange;
     }
 
     // ---- activation staging: thread t moves the 16-byte piece st_p of rows st_row0, st_row0 + RP, ... ----
@@ -108,14 +112,16 @@ __global__ __launch_bounds__(64 * WV, WV <= 8 ? 2 : 4) void wide_mfma_kernel(con
     constexpr int NP = (ROWS + RP - 1) / RP;              // passes
     const int st_p = tid & 15, st_row0 = tid >> 4;        // row & 15 == st_row0 & 15 in every pass
     u32x4_t areg[NP];
-    auto a_load = [&](int t) {                            // k-step t of this workgroup (out of range: zeros)
+    uint32_t a_lane[NP];
 #pragma unroll
-        for (int i = 0; i < NP; ++i) {
-            const int row = st_row0 + RP * i;
-            const bool ok = t < T && row < ROWS && m0 + row < p.M;
-            const uint32_t off = ok ? ((uint32_t)(m0 + row) * (uint32_t)p.K + (uint32_t)(ks0 + t) * kStepK + st_p * 8) * 2u : kOutOfRange;
-            areg[i] = __builtin_amdgcn_raw_buffer_load_b128(ra, off, 0, 0);
-        }
+    for (int i = 0; i < NP; ++i) {
+        const int row = st_row0 + RP * i;
+        a_lane[i] = (row < ROWS && m0 + row < p.M) ? ((uint32_t)(m0 + row) * (uint32_t)p.K + st_p * 8) * 2u : kOutOfRange;
+    }
+    auto a_load = [&](int t) {                            // k-step t of this workgroup (rows that do not exist: zeros)
+        const int so = (int)((uint32_t)(ks0 + min(t, T - 1)) * (kStepK * 2u));
+#pragma unroll
+        for (int i = 0; i < NP; ++i) areg[i] = __builtin_amdgcn_raw_buffer_load_b128(ra, a_lane[i], so, 0);
     };
     auto a_store = [&](int buf) {
 #pragma unroll
@@ -132,18 +138,15 @@ __global__ __launch_bounds__(64 * WV, WV <= 8 ? 2 : 4) void wide_mfma_kernel(con
     uint16_t zbuf[ZP ? 3 : 1][NBW];                        // zero points, same offsets as the scales
     (void)zbuf;
     auto w_load = [&](int slot, int t) {
-        const bool in = t < T;
-        const uint32_t ks = (uint32_t)(ks0 + t);
+        const uint32_t ks = (uint32_t)(ks0 + min(t, T - 1));
         const uint32_t j = (G1 || p.spg_inv == 0) ? ks : __umulhi(ks, p.spg_inv);
 #pragma unroll
         for (int r = 0; r < NBW; ++r) {
-            const bool ok = in && nt_ok[r];
-            sbuf[slot][r] = __builtin_amdgcn_raw_buffer_load_b16(rs, ok ? s_lane[r] + j * 2u : kOutOfRange, 0, 0);
-            if constexpr (ZP) zbuf[slot][r] = __builtin_amdgcn_raw_buffer_load_b16(rz, ok ? s_lane[r] + j * 2u : kOutOfRange, 0, 0);
+            sbuf[slot][r] = __builtin_amdgcn_raw_buffer_load_b16(rs, s_lane[r], (int)(j * 2u), 0);
+            if constexpr (ZP) zbuf[slot][r] = __builtin_amdgcn_raw_buffer_load_b16(rz, s_lane[r], (int)(j * 2u), 0);
 #pragma unroll
             for (int c = 0; c < TPS; ++c)
-                wbuf[slot][r][c] = __builtin_amdgcn_raw_buffer_load_b128(
-                    rw, ok ? w_lane[r] + (ks * TPS + c) * 1024u : kOutOfRange, 0, 2 /* nt */);
+                wbuf[slot][r][c] = __builtin_amdgcn_raw_buffer_load_b128(rw, w_lane[r], (int)((ks * TPS + c) * 1024u), 2 /* nt */);
         }
     };
 
