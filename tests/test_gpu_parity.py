@@ -406,6 +406,34 @@ def test_linear_is_deterministic(rtn):
             assert torch.equal(o, outs[0])
 
 
+@pytest.mark.parametrize("M,cfg", [(1, dict(waves_k=4, split_k=2)), (8, dict(waves_n=4, waves_k=2, split_k=4)),
+                                   (16, dict(waves_n=4, waves_k=1, split_k=8)), (4, None)])
+def test_linear_split_k_graph_replays_match_direct_calls(rtn, M, cfg):
+    """A K-split call recorded into a HIP graph: every replay, with direct calls and fresh activations in between,
+    gives the bits of the direct call (the split partial sums are added in a fixed order on both routes)."""
+    N, K = 1024, 14336
+    codes, scales, qw, sc, gg = _oracle_operands(N, K, 4, 128, seed=31)
+    nws = max(256, rtn._lib.rtn_workspace_nbytes(M, N, K, 4, 128))
+    A_static = synth.activation(M, K, seed=100, device=DEV)
+    ws_g = torch.empty(nws, dtype=torch.uint8, device=DEV)
+    out_g = torch.empty((M, N), dtype=torch.float16, device=DEV)
+    rtn.rtn_linear(A_static, qw, sc, 4, 128, cfg=cfg)      # a direct call before the recording
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        rtn.rtn_linear(A_static, qw, sc, 4, 128, out=out_g, workspace=ws_g, cfg=cfg)
+    for rep in range(4):
+        A_new = synth.activation(M, K, seed=101 + rep, device=DEV)
+        A_static.copy_(A_new)
+        want = rtn.rtn_linear(A_new, qw, sc, 4, 128, cfg=cfg)
+        torch.cuda.synchronize()
+        graph.replay()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, want), (M, cfg, rep)
+    H.assert_linear_close(_to_np(out_g), O.rtn_linear(_to_np(A_static), codes, scales, gg), f"graph replay M={M}")
+
+
 # ----------------------------------------------------------------------------------------
 # the paper-shaped configurations at full size (rows of the weight matrix are independent, so the
 # oracle checks a stripe of 16-row tiles; the GPU runs the full shape in its default configuration)
