@@ -84,7 +84,7 @@ def report(args, rtn, synth, torch, np, dev) -> int:
     shapes = {"8b": synth.LLAMA_8B, "70b": synth.LLAMA_70B, "405b": synth.LLAMA_405B}[args.report]
     std = {"8b": 0.02, "70b": 0.02, "405b": 0.01}[args.report]
     Ms = [int(x) for x in args.batches.split(",")]
-    ws = torch.empty(16 << 20, dtype=torch.uint8, device=dev)
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device=dev)
     tot = {M: 0.0 for M in Ms}
     totb = 0
     what = ("selective precision: qkv and gate_up int4 group 128, o and down int8 per-channel" if args.selective

@@ -78,7 +78,8 @@ int rtn_layout_version(void);
 /* Sizes in bytes of the buffers the caller must provide; 0 if the arguments are invalid.
  * qweight: N*K*bits/8.  scales: N*(K/g)*2.  workspace (rtn_linear, rtn_layer_forward):
  * fp32 split-K partial sums; an upper bound over every configuration the library may
- * choose for this problem; never more than 16 MiB. */
+ * choose for this problem; never more than 16 MiB, except for 128 and more rows on large
+ * 4-bit matrices, where the chosen plan may split K further (never more than 64 MiB). */
 size_t rtn_qweight_nbytes(int64_t N, int64_t K, int bits);
 size_t rtn_scales_nbytes(int64_t N, int64_t K, int group_size);
 size_t rtn_workspace_nbytes(int64_t M, int64_t N, int64_t K, int bits, int group_size);
@@ -132,8 +133,8 @@ typedef struct {
     int path;      /* 0 auto, 1 MFMA skinny kernel, 2 vector-ALU dot-product kernel (M <= 4), 3 wide MFMA kernel
                       (group_size a multiple of 128; uses split_k, m_rows16 = 2..4, n_tiles16 and waves_n = 4, 8 or -- with
                       n_tiles16 = 1 -- 16 wavefronts per workgroup; also m_rows16 = 8 with n_tiles16 = 2 and waves_n = 8:
-                      128 rows per workgroup, weights scaled in fp16 before the MFMA as in path 4, never chosen
-                      automatically), 4 tile kernel: 128 x 256 or
+                      128 rows per workgroup, weights scaled in fp16 before the MFMA as in path 4, chosen automatically
+                      for 128 and more rows on large 4-bit matrices below the tile kernel's range), 4 tile kernel: 128 x 256 or
                       256 x 256 output tiles, weights dequantised to fp16 in LDS (group_size a multiple of 128; uses split_k and
                       m_rows16 = 4 or 8 for the tile height, 0 = chosen from M) */
     int prefetch;  /* k-chunks (4 KiB each) a wavefront keeps in flight: 1, 2 or 4 */

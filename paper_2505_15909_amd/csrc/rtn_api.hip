@@ -14,7 +14,8 @@ using rtn::LinearPlan;
 
 namespace {
 
-constexpr size_t kWorkspaceCap = (size_t)16 << 20;     // split-K partials never exceed this
+constexpr size_t kWorkspaceCap = (size_t)16 << 20;     // split-K partials never exceed this ...
+constexpr size_t kWorkspaceCapTall = (size_t)64 << 20; // ... except under the plan of the wide kernel's 128-row variant
 constexpr int kMaxSplitK = 16;
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -118,6 +119,26 @@ void wide_plan(int64_t M, int64_t N, int64_t K, int bits, LinearPlan* p) {
         }
 }
 
+// K splits of the wide kernel's 128-row variant (128 rows x 256 columns per workgroup, one workgroup per compute
+// unit): the lowest modelled time over 1, 2, 4, 8 splits that fit 64 MiB of partials.  A workgroup's full-K time is
+// its MFMA work at the 4.3 TFLOP/s one compute unit sustains in this kernel; a round of workgroups costs 9 us more
+// (start, prologue, epilogue), the reduce launch 4 us plus its traffic at 5 TB/s.  Fitted to sweeps over the 70B and
+// 405B shapes at 128-512 rows, where it picks the measured best split or one within 4 % of it.
+int tall_wide_split(int64_t M, int64_t N, int64_t K) {
+    const int64_t wgs = ((N + 255) / 256) * ((M + 127) / 128);
+    const double t1 = 2.0 * 128 * 256 * (double)K / 4.3e12, mn4 = (double)M * N * 4.0;
+    int best_s = 1;
+    double best = 1e30;
+    for (int s = 1; s <= 8; s *= 2) {
+        if (s > 1 && ((size_t)M * N * sizeof(float) * s > kWorkspaceCapTall || K / 128 / s < 4)) break;
+        const double rounds = (double)((wgs * s + 255) / 256);
+        double t = rounds * (t1 / s + 9e-6);
+        if (s > 1) t += 4e-6 + 2.0 * s * mn4 / 5e12;
+        if (t < best) { best = t; best_s = s; }
+    }
+    return best_s;
+}
+
 // force_path: 0 = choose the path, otherwise the default plan of that path.
 LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_t lds_limit, int force_path = 0,
                      int64_t steps_hint = 0) {
@@ -142,6 +163,21 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
         p.prefetch = 1; p.waves_n = 8; p.waves_k = 1; p.split_k = 1;
         p.m_rows16 = 0;                                        // tile height: chosen at launch
         p.m_blocks = (int)((M + 127) / 128);
+        return p;
+    }
+    // 128 rows and more, up to where the tile kernel takes over, on 4-bit matrices of 40 MB and more with more input
+    // than output columns (the down projections): the wide kernel's 128-row variant with K split until there is a
+    // workgroup per compute unit.  3-12 % faster than the 64-row variant on the 70B and 405B down matrices at 128-512
+    // rows; within +-7 % on their qkv and o matrices, slower on every 8B shape, and on 8-bit weights ahead on one
+    // matrix only, so those keep the 64-row variant.
+    const bool tall_wide = wide_wins && bits == 4 && M >= 128 && (M + 127) / 128 * 2 <= (M + 63) / 64 &&
+                           packed_bytes >= ((size_t)40 << 20) && K > N;
+    if (force_path == 0 && tall_wide) {
+        p.path = 3;
+        p.prefetch = 1; p.waves_n = 8; p.waves_k = 1; p.n_tiles16 = 2;
+        p.m_rows16 = 8;
+        p.m_blocks = (int)((M + 127) / 128);
+        p.split_k = tall_wide_split(M, N, K);
         return p;
     }
     if (force_path == 3 || (force_path == 0 && wide_wins)) {
@@ -323,7 +359,13 @@ size_t rtn_scales_nbytes(int64_t N, int64_t K, int group_size) {
 size_t rtn_workspace_nbytes(int64_t M, int64_t N, int64_t K, int bits, int group_size) {
     int64_t g;
     if (M <= 0 || check_problem(N, K, bits, group_size, &g) != RTN_OK) return 0;
-    return workspace_bound(M, N);
+    size_t bound = workspace_bound(M, N);
+    const LinearPlan p = auto_plan(M, N, K, bits, g, (size_t)device_max_lds());
+    if (p.split_k > 1) {                                        // the automatic plan's own need, where it is larger
+        const size_t need = ((size_t)M * (size_t)N * sizeof(float) * (size_t)p.split_k + 255) & ~(size_t)255;
+        if (need > bound) bound = need;
+    }
+    return bound;
 }
 
 rtn_status rtn_quantize(const void* dev_W, int64_t N, int64_t K, int bits, int group_size, int flags,
