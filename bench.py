@@ -84,7 +84,7 @@ def report(args, rtn, synth, torch, np, dev) -> int:
     shapes = {"8b": synth.LLAMA_8B, "70b": synth.LLAMA_70B, "405b": synth.LLAMA_405B}[args.report]
     std = {"8b": 0.02, "70b": 0.02, "405b": 0.01}[args.report]
     Ms = [int(x) for x in args.batches.split(",")]
-    ws = torch.empty(64 << 20, dtype=torch.uint8, device=dev)
+    ws = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
     tot = {M: 0.0 for M in Ms}
     totb = 0
     what = ("selective precision: qkv and gate_up int4 group 128, o and down int8 per-channel" if args.selective
@@ -209,7 +209,7 @@ def report_crossover(args, rtn, synth, torch, np, dev) -> int:
     bits = args.bits
     g = 128 if bits == 4 else 0
     Ms = [int(x) for x in args.batches.split(",")]
-    ws = torch.empty(128 << 20, dtype=torch.uint8, device=dev)      # room for the dense GEMM's split-K partials
+    ws = torch.empty(256 << 20, dtype=torch.uint8, device=dev)      # room for the split-K partials of either path
     print(f"# {args.report_crossover} shapes, int{bits}; us per call (HIP events, 6 back-to-back calls, best of 3; one weight copy, "
           f"so matrices under 256 MB are cache-resident): fused = rtn_linear; dual = rtn_linear_dense (dequantise to fp16 + "
           f"own dense GEMM); gemm = the dense GEMM alone on already dequantised weights; last column (reference): the same dequantise followed by torch.matmul (hipBLASLt)")

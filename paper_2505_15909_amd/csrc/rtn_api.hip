@@ -139,6 +139,32 @@ int tall_wide_split(int64_t M, int64_t N, int64_t K) {
     return best_s;
 }
 
+// Tile height (128 or 256 rows) and K split of the fused tile kernel: the pair with the lowest modelled time.  One
+// workgroup runs per compute unit, so a launch takes rounds of 256 workgroups; a workgroup advances one 64-column step
+// in 0.85 us with a 128-row tile and 1.40 us with a 256-row tile (packed weights) and costs 8 us besides; a split adds
+// the reduce launch and the partial sums' trip through the workspace at 4 TB/s.  Splits need not be powers of two: what
+// pays is a split that fills the last round (144 tiles: three splits of 72 tall tiles make one round of 216).  Fitted
+// to a sweep of splits 1-8 and both heights over the 8B, 70B and 405B shapes whose tiles fill their last round
+// to less than 85 %: the pick is within 1 % of the best measured pair on average, where one split and the height rule
+// of the launch were 6 % behind (405B qkv at 256 rows: 163 us against 219).
+constexpr size_t kWorkspaceCapTile = (size_t)256 << 20;
+void tile_plan_choose(int64_t M, int64_t N, int64_t K, int* rows16, int* split_k) {
+    const int64_t xb = (N + 255) / 256;
+    double best = 1e30;
+    *rows16 = 4; *split_k = 1;
+    for (int s = 1; s <= 8; ++s) {
+        if (s > 1 && ((size_t)M * N * sizeof(float) * s > kWorkspaceCapTile || K / 128 / s < 4)) break;
+        for (int h = 4; h <= 8; h += 4) {
+            if (h == 8 && M <= 128) continue;
+            const int64_t tiles = xb * ((M + 32 * h - 1) / (32 * h));
+            const double rounds = (double)((tiles * s + 255) / 256), steps = (double)((K / 64 + s - 1) / s);
+            double t = rounds * (steps * (h == 4 ? 0.85 : 1.40) + 8.0);
+            if (s > 1) t += 2.5 + (2.0 * s * M * N * 4.0 + 2.0 * M * N) / 4.0e6;
+            if (t < best) { best = t; *rows16 = h; *split_k = s; }
+        }
+    }
+}
+
 // force_path: 0 = choose the path, otherwise the default plan of that path.
 LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_t lds_limit, int force_path = 0,
                      int64_t steps_hint = 0) {
@@ -160,9 +186,9 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
                            (M + 127) / 128 * 2 <= (M + 63) / 64;
     if (force_path == 4 || (force_path == 0 && tile_wins)) {
         p.path = 4;
-        p.prefetch = 1; p.waves_n = 8; p.waves_k = 1; p.split_k = 1;
-        p.m_rows16 = 0;                                        // tile height: chosen at launch
-        p.m_blocks = (int)((M + 127) / 128);
+        p.prefetch = 1; p.waves_n = 8; p.waves_k = 1;
+        tile_plan_choose(M, N, K, &p.m_rows16, &p.split_k);
+        p.m_blocks = (int)((M + 32 * p.m_rows16 - 1) / (32 * p.m_rows16));
         return p;
     }
     // 128 rows and more, up to where the tile kernel takes over, on 4-bit matrices of 40 MB and more with more input
@@ -288,9 +314,8 @@ rtn_status resolve_plan(const LinearArgs& a, const rtn_linear_cfg* cfg, size_t w
             p.m_blocks = (int)((a.M + 16 * p.m_rows16 - 1) / (16 * p.m_rows16));
         }
         if (cfg->n_tiles16) p.n_tiles16 = cfg->n_tiles16;
-        if (p.path == 4 && !cfg->m_rows16) p.m_rows16 = 0;      // tile height: chosen at launch
+        if (p.path == 4 && !cfg->m_rows16 && cfg->split_k) p.m_rows16 = 0;     // a given split: height chosen at launch
     }
-    if (p.path == 4 && !cfg) p.m_rows16 = 0;
     const int64_t KC = a.K / chunk_k(a.bits);
     if (p.path < 1 || p.path > 4) return RTN_ERR_CONFIG;
     if (p.path >= 3) {
@@ -507,19 +532,23 @@ rtn_status rtn_quantize_from_host(const void* host_W, int64_t N, int64_t K, int 
     return ok ? RTN_OK : RTN_ERR_HIP;
 }
 
-// Split-K of the dense GEMM: only as far as needed to give every compute unit a workgroup, within the workspace.
-// K split of the dense GEMM: the candidate with the lowest modelled time.  A 128 x 256 tile advances one 64-column
-// step per ~1 us whether or not all compute units have a tile (measured: 59-62 us at K = 4096 for 24 to 192 tiles), so
-// the GEMM takes rounds x steps-per-split; a split adds the partials' round trip through the workspace (write and read
-// of split x M x N fp32 at ~4.5 TB/s) and the reduce launch.
+// K split of the dense GEMM: the candidate (1-8 splits, not only powers of two) with the lowest modelled time, as for
+// the fused tile kernel.  A 128 x 256 tile advances one 64-column step per ~1 us whether or not all compute units
+// have a tile (measured: 59-62 us at K = 4096 for 24 to 192 tiles), a 256-row tile takes 1.7 times as long (the
+// launch picks the height from the rounds of 256 workgroups each would take); a workgroup costs 8 us besides, and a
+// split adds the partials' round trip through the workspace (write and read of split x M x N fp32 at ~4.5 TB/s) and
+// the reduce launch.
 static int dense_split(int64_t M, int64_t N, int64_t K, size_t workspace_nbytes) {
-    const int64_t tiles = ((M + 127) / 128) * ((N + 255) / 256);
+    const int64_t xb = (N + 255) / 256;
     int best = 1;
     double best_t = 1e30;
-    for (int s = 1; s <= kMaxSplitK; s *= 2) {
+    for (int s = 1; s <= 8; ++s) {
         if (s > 1 && (K / 128 / s < 8 || (size_t)M * N * sizeof(float) * s > workspace_nbytes)) break;
-        const int64_t rounds = (tiles * s + 255) / 256;
-        double t = (double)rounds * ((double)K / 64.0 / s) * 1.0;
+        const double r_short = (double)((xb * ((M + 127) / 128) * s + 255) / 256);
+        const double r_tall = (double)((xb * ((M + 255) / 256) * s + 255) / 256);
+        const bool tall = M > 128 && 1.7 * r_tall < r_short;
+        const double steps = (double)((K / 64 + s - 1) / s);
+        double t = tall ? r_tall * (steps * 1.7 + 8.0) : r_short * (steps * 1.0 + 8.0);
         if (s > 1) t += 2.5 + (2.0 * s * M * N * 4.0 + 2.0 * M * N) / 4.5e6;
         if (t < best_t) {
             best_t = t;

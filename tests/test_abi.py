@@ -132,6 +132,13 @@ def test_bad_valid_combination_is_not_launched_without_gpu():
     assert rtn.rtn_linear_query(129, 16384, 53248, 4, 128)["m_rows16"] == 4      # 128-row padding would cost too much
     assert rtn.rtn_linear_query(128, 16384, 53248, 8, 0)["m_rows16"] == 4
     assert rtn.rtn_linear_query(128, 4096, 14336, 4, 128)["m_rows16"] == 4
+    # tile kernel: height and K split chosen together so that the last round of 256 workgroups is filled
+    # (72 column blocks x 1 tall row block x 3 splits = 216 workgroups instead of 144 short tiles in one round)
+    q = rtn.rtn_linear_query(256, 18432, 16384, 4, 128)
+    assert (q["path"], q["m_rows16"], q["split_k"]) == (4, 8, 3)
+    assert rtn.rtn_workspace_nbytes(256, 18432, 16384, 4, 128) == 256 * 18432 * 4 * 3
+    q = rtn.rtn_linear_query(4096, 28672, 4096, 4, 128)
+    assert (q["path"], q["split_k"]) == (4, 1)
     with pytest.raises(rtn.RtnError):
         rtn.rtn_linear_query(1, 4096, 4000, 4, 128)
 
@@ -288,7 +295,7 @@ def test_reciprocal_and_snap_arithmetic_rounds_like_the_exact_quotient():
 def test_every_automatic_plan_is_a_valid_configuration():
     """Host logic: for a spread of shapes (the paper's Llama shapes and random ones), every batch size and both
     precisions, the plan rtn_linear would choose passes the library's own validation when handed back explicitly,
-    fits the workspace the size helper promises (16 MiB; 64 MiB under the 128-row wide plan), and (no GPU here) only then fails at the launch itself."""
+    fits the workspace the size helper promises (16 MiB; 64 MiB under the 128-row wide plan, 256 MiB under the tile kernel's), and (no GPU here) only then fails at the launch itself."""
     rng = np.random.default_rng(7)
     shapes = [(4096, 6144), (4096, 4096), (4096, 28672), (14336, 4096), (8192, 10240), (8192, 57344), (28672, 8192),
               (16384, 18432), (16384, 106496), (53248, 16384)]
@@ -306,8 +313,11 @@ def test_every_automatic_plan_is_a_valid_configuration():
                 need = M * N * 4 * q["split_k"] if q["split_k"] > 1 else 0
                 assert need <= rtn._lib.rtn_workspace_nbytes(M, N, K, bits, g), (M, N, K, bits, g, q)
                 cfg = rtn.rtn_linear_cfg(**q)
-                assert need <= (64 << 20 if q["m_rows16"] == 8 and q["path"] == 3 else 16 << 20), (M, N, K, bits, g, q)
-                st = lib.rtn_linear_ex(FAKE, M, FAKE, FAKE, N, K, bits, g, FAKE, FAKE, 64 << 20, None, C.byref(cfg))
+                cap = 256 << 20 if q["path"] == 4 else (64 << 20 if q["m_rows16"] == 8 and q["path"] == 3 else 16 << 20)
+                assert need <= cap, (M, N, K, bits, g, q)
+                if q["path"] == 4:
+                    assert q["m_rows16"] in (4, 8) and (M > 128 or q["m_rows16"] == 4), q
+                st = lib.rtn_linear_ex(FAKE, M, FAKE, FAKE, N, K, bits, g, FAKE, FAKE, 256 << 20, None, C.byref(cfg))
                 assert st == 8, (st, M, N, K, bits, g, q)      # accepted by validation; the launch fails without a GPU
                 checked += 1
     assert checked > 3000

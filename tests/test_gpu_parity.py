@@ -443,7 +443,7 @@ FULL = [
     ("single_4096", "normal02", 4, 128, {"o": (4096, 4096)}, (1,), 256),
     ("llama8b_w4", "normal02", 4, 128, synth.LLAMA_8B, (1, 2, 4, 8, 16), 24),
     ("llama8b_w8", "normal02", 8, 0, synth.LLAMA_8B, (1, 4, 16, 64), 24),
-    ("llama70b_w4", "heavy", 4, 128, synth.LLAMA_70B, (1, 8, 32, 64, 128, 256), 12),
+    ("llama70b_w4", "heavy", 4, 128, synth.LLAMA_70B, (1, 8, 32, 64, 128, 256, 512, 768), 12),
 ]
 
 
@@ -475,7 +475,7 @@ def test_full_size_large_batch_fused_and_dual_path(rtn, M):
     """Prefill-sized inputs on the full 8B-shaped gate_up and down matrices (Section 5): the fused path (tile kernel
     where it has a full round of output tiles, wide kernel otherwise) and the dequantise-then-GEMM path, both against
     the oracle on a stripe of 16-row tiles."""
-    ws = torch.empty(64 << 20, dtype=torch.uint8, device=DEV)
+    ws = torch.empty(256 << 20, dtype=torch.uint8, device=DEV)
     for idx, mod in enumerate(("gate_up", "down")):
         K, N = synth.LLAMA_8B[mod]
         W_t = synth.normal_weight(N, K, 0.02, seed=idx, device=DEV)
