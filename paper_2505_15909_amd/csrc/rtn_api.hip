@@ -105,18 +105,29 @@ void wide_plan(int64_t M, int64_t N, int64_t K, int bits, LinearPlan* p) {
     if (smax > kMaxSplitK) smax = kMaxSplitK;
     if (smax > KS / 4) smax = KS / 4;
     if (smax < 1) smax = 1;
-    double best = 1e30;
+    // three splits (they fill the compute units where two leave a third idle and four start a second round) compete
+    // with the powers of two: 19-34 % faster on the 70B and 405B qkv matrices at 48-128 rows.  Other splits are taken
+    // only when the model puts them 5 % ahead: its small preferences for five or six on the 8B shapes cost 2-3 %.
+    double best = 1e30, best_any = 1e30;
+    LinearPlan any = *p;
     for (int wv = 4; wv <= 16; wv *= 2)
         for (int nbw = 1; nbw <= 4; nbw *= 2) {
             if (p->m_rows16 * nbw > 8 || (wv == 16 && nbw > 1)) continue;
-            for (int s = 1; s <= smax; s *= 2) {
+            for (int s = 1; s <= smax; ++s) {
                 const double t = wide_model_us(M, N, K, bits, p->m_rows16, wv, nbw, s);
-                if (t < best) {
+                if (((s & (s - 1)) == 0 || s == 3) && t < best) {
                     best = t;
                     p->waves_n = wv; p->n_tiles16 = nbw; p->split_k = s;
                 }
+                if (t < best_any) {
+                    best_any = t;
+                    any.waves_n = wv; any.n_tiles16 = nbw; any.split_k = s;
+                }
             }
         }
+    if (best_any < 0.95 * best) {
+        p->waves_n = any.waves_n; p->n_tiles16 = any.n_tiles16; p->split_k = any.split_k;
+    }
 }
 
 // K splits of the wide kernel's 128-row variant (128 rows x 256 columns per workgroup, one workgroup per compute
@@ -129,7 +140,7 @@ int tall_wide_split(int64_t M, int64_t N, int64_t K) {
     const double t1 = 2.0 * 128 * 256 * (double)K / 4.3e12, mn4 = (double)M * N * 4.0;
     int best_s = 1;
     double best = 1e30;
-    for (int s = 1; s <= 8; s *= 2) {
+    for (int s = 1; s <= 8; ++s) {
         if (s > 1 && ((size_t)M * N * sizeof(float) * s > kWorkspaceCapTall || K / 128 / s < 4)) break;
         const double rounds = (double)((wgs * s + 255) / 256);
         double t = rounds * (t1 / s + 9e-6);
@@ -232,11 +243,14 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
         } else if (rows == 3 && KC <= 32) {
             p.waves_n = 2; p.waves_k = 2; p.split_k = 4;
         } else {
-            // eight tile-rows share the staged rows; K is split across workgroups until there are 1.5 per compute unit
+            // eight tile-rows share the staged rows; K is split across workgroups to fill the compute units
             p.waves_n = 8; p.waves_k = 1; p.split_k = 1;
-            while (((NT + 7) / 8) * p.split_k < 384 && p.split_k * 2 <= 8 && KC / (p.split_k * 2) >= 4 &&
-                   (size_t)M * N * sizeof(float) * (p.split_k * 2) <= kWorkspaceCap)
-                p.split_k *= 2;
+            // (two of these workgroups share a compute unit: as many splits as keep the launch within one round of 512;
+            // three on the 405B qkv matrix, 144 workgroups each, are 9-14 % faster than four)
+            int64_t split = 512 / ((NT + 7) / 8);
+            split = split < 1 ? 1 : (split > 8 ? 8 : split);
+            while (split > 1 && (KC / split < 4 || (size_t)M * N * sizeof(float) * split > kWorkspaceCap)) --split;
+            p.split_k = (int)split;
         }
     } else
     // up to 4 rows on a moderately long K (K = 14336: 28 chunks) also stream best unsplit: 14 wavefronts x 2 chunks
@@ -285,8 +299,17 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
         // this kernel at 17-32 rows); K is split across workgroups only as far as needed to occupy the compute units
         p.waves_n = streams16 ? 16 : 8;
         p.waves_k = 1;
-        const int64_t wgs = ((NT + 15) / 16) * p.m_blocks, want = streams16 ? 140 : 256;
-        while (wgs * p.split_k < want && p.split_k * 2 <= (streams16 ? 8 : kMaxSplitK) && p.split_k * 2 <= KC &&
+        const int64_t wgs = ((NT + 15) / 16) * p.m_blocks, want = 256;
+        if (streams16) {
+            // one 16-wavefront workgroup runs per compute unit: as many splits as keep the launch within one round of
+            // 256 (72 workgroups x 3 on the 405B qkv matrix: 45 us against 55 with two splits, 61-65 with four);
+            // five to seven splits measured level with four
+            int64_t s = 256 / wgs;
+            s = s < 1 ? 1 : (s > 8 ? 8 : (s > 4 && s < 8 ? 4 : s));
+            while (s > 1 && (s > KC || (size_t)M * N * sizeof(float) * s > kWorkspaceCap)) --s;
+            p.split_k = (int)s;
+        } else
+        while (wgs * p.split_k < want && p.split_k * 2 <= kMaxSplitK && p.split_k * 2 <= KC &&
                (size_t)M * N * sizeof(float) * (p.split_k * 2) <= kWorkspaceCap)
             p.split_k *= 2;
     }
