@@ -78,8 +78,9 @@ int rtn_layout_version(void);
 /* Sizes in bytes of the buffers the caller must provide; 0 if the arguments are invalid.
  * qweight: N*K*bits/8.  scales: N*(K/g)*2.  workspace (rtn_linear, rtn_layer_forward):
  * fp32 split-K partial sums; an upper bound over every configuration the library may
- * choose for this problem; never more than 16 MiB up to 127 rows.  From 128 rows the
- * chosen plan may split K further to fill the compute units (never more than 256 MiB). */
+ * choose for this problem; never more than 16 MiB up to 63 rows.  From 64 rows the
+ * chosen plan may split K further to fill the compute units (never more than 64 MiB up
+ * to 127 rows, 256 MiB above). */
 size_t rtn_qweight_nbytes(int64_t N, int64_t K, int bits);
 size_t rtn_scales_nbytes(int64_t N, int64_t K, int group_size);
 size_t rtn_workspace_nbytes(int64_t M, int64_t N, int64_t K, int bits, int group_size);

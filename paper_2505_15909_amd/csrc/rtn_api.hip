@@ -15,7 +15,7 @@ using rtn::LinearPlan;
 namespace {
 
 constexpr size_t kWorkspaceCap = (size_t)16 << 20;     // split-K partials never exceed this ...
-constexpr size_t kWorkspaceCapTall = (size_t)64 << 20; // ... except under the plan of the wide kernel's 128-row variant
+constexpr size_t kWorkspaceCapTall = (size_t)64 << 20; // ... except under the wide kernel's plans from 64 rows (and the tile kernel's)
 constexpr int kMaxSplitK = 16;
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -101,7 +101,7 @@ void wide_plan(int64_t M, int64_t N, int64_t K, int bits, LinearPlan* p) {
     p->m_blocks = (int)((M + 16 * p->m_rows16 - 1) / (16 * p->m_rows16));
     p->prefetch = 1; p->waves_k = 1;
     const int64_t KS = K / 128;
-    int64_t smax = (int64_t)(kWorkspaceCap / ((size_t)M * N * sizeof(float)));
+    int64_t smax = (int64_t)((M >= 64 ? kWorkspaceCapTall : kWorkspaceCap) / ((size_t)M * N * sizeof(float)));
     if (smax > kMaxSplitK) smax = kMaxSplitK;
     if (smax > KS / 4) smax = KS / 4;
     if (smax < 1) smax = 1;
