@@ -434,6 +434,37 @@ def test_linear_split_k_graph_replays_match_direct_calls(rtn, M, cfg):
     H.assert_linear_close(_to_np(out_g), O.rtn_linear(_to_np(A_static), codes, scales, gg), f"graph replay M={M}")
 
 
+def test_linear_automatic_plans_on_large_random_shapes(rtn):
+    """What rtn_linear chooses by itself from 48 rows up on matrices large enough for every branch of its plan (wide
+    kernel with 1-8 K splits, its 128-row variant, tile kernel of either height with and without splits), with the
+    workspace rtn_workspace_nbytes asks for: a stripe of output columns (first and last tile-row, 96 random ones)
+    against the oracle on the unpacked codes."""
+    rng = np.random.default_rng(5)
+    seen = set()
+    for case in range(14):
+        bits = int(rng.choice([4, 4, 8]))
+        g = 128 if bits == 4 else int(rng.choice([0, 128]))
+        K = int(rng.choice([4096, 8192, 14336, 16384, 28672]))
+        N = int(rng.integers(8, 90)) * 256 + int(rng.choice([0, 16, 128]))
+        M = int(rng.choice([48, 64, 96, 128, 129, 160, 192, 256, 300, 384, 512, 640, 768, 1000, 1024]))
+        W_t = synth.normal_weight(N, K, 0.02, seed=case, device=DEV)
+        qw, sc = rtn.rtn_quantize(W_t, bits, g)
+        del W_t
+        A_t = synth.activation(M, K, seed=case + 7, device=DEV)
+        q = rtn.rtn_linear_query(M, N, K, bits, g)
+        need = M * N * 4 * q["split_k"] if q["split_k"] > 1 else 0
+        assert need <= rtn.rtn_workspace_nbytes(M, N, K, bits, g)
+        C = rtn.rtn_linear(A_t, qw, sc, bits, g)
+        torch.cuda.synchronize()
+        sel = np.unique(np.concatenate([np.arange(0, 16), np.arange(N - 16, N), rng.integers(0, N, 96)]))
+        codes = _to_np(rtn.rtn_unpack(qw, N, K, bits))[sel]
+        ref = O.rtn_linear(_to_np(A_t), codes, _to_np(sc)[sel], K if g == 0 else g)
+        H.assert_linear_close(_to_np(C)[:, sel], ref, f"case {case} bits={bits} g={g} M={M} N={N} K={K} plan={q}")
+        seen.add((q["path"], q["m_rows16"], q["split_k"] > 1))
+        del qw, sc, A_t, C
+    assert {p for p, _, _ in seen} == {3, 4} and any(r == 8 for _, r, _ in seen) and any(s for _, _, s in seen), seen
+
+
 # ----------------------------------------------------------------------------------------
 # the paper-shaped configurations at full size (rows of the weight matrix are independent, so the
 # oracle checks a stripe of 16-row tiles; the GPU runs the full shape in its default configuration)
