@@ -159,7 +159,7 @@ int tall_wide_split(int64_t M, int64_t N, int64_t K) {
 // to less than 85 %: the pick is within 1 % of the best measured pair on average, where one split and the height rule
 // of the launch were 6 % behind (405B qkv at 256 rows: 163 us against 219).
 constexpr size_t kWorkspaceCapTile = (size_t)256 << 20;
-void tile_plan_choose(int64_t M, int64_t N, int64_t K, int* rows16, int* split_k) {
+double tile_plan_choose(int64_t M, int64_t N, int64_t K, int* rows16, int* split_k) {
     const int64_t xb = (N + 255) / 256;
     double best = 1e30;
     *rows16 = 4; *split_k = 1;
@@ -174,6 +174,7 @@ void tile_plan_choose(int64_t M, int64_t N, int64_t K, int* rows16, int* split_k
             if (t < best) { best = t; *rows16 = h; *split_k = s; }
         }
     }
+    return best;
 }
 
 // force_path: 0 = choose the path, otherwise the default plan of that path.
@@ -195,20 +196,36 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
     // kernel's 64-row padding
     const bool tile_wins = g % 128 == 0 && M >= 128 && ((N + 255) / 256) * ((M + 127) / 128) >= 144 &&
                            (M + 127) / 128 * 2 <= (M + 63) / 64;
-    if (force_path == 4 || (force_path == 0 && tile_wins)) {
+    // Below 144 tiles the tile kernel can still win by splitting K (deep matrices: the wide kernel would split as well
+    // and re-reads its activations more often): taken when its modelled time is under 1.075 x the wide plan's (the
+    // two models are calibrated apart by about that much).  Measured on the 8B, 70B and 405B shapes at 128-1024
+    // rows: 5-27 % faster on the points this picks (8B down from 384 rows, 70B qkv at 256, 70B down from 256, 405B
+    // qkv at 128, 405B o and down from 192; 8B gate_up at 320 is 6 % slower).  Where the 128-row wide variant
+    // (below) applies under 192 rows it keeps the matrix.  8-bit weights: level on average (+12 % to -9 %), so they
+    // keep the 144-tile rule.
+    const bool tall_wide = wide_wins && bits == 4 && M >= 128 && (M + 127) / 128 * 2 <= (M + 63) / 64 &&
+                           packed_bytes >= ((size_t)40 << 20) && K > N;
+    bool tile_by_model = false;
+    if (force_path == 0 && !tile_wins && wide_wins && M >= 128 && bits == 4) {
+        LinearPlan w;
+        wide_plan(M, N, K, bits, &w);
+        int r16 = 4, sk = 1;
+        const double t_tile = tile_plan_choose(M, N, K, &r16, &sk);
+        const double t_wide = wide_model_us(M, N, K, bits, w.m_rows16, w.waves_n, w.n_tiles16, w.split_k);
+        tile_by_model = t_tile * 0.93 < t_wide && !(tall_wide && M < 192);
+    }
+    if (force_path == 4 || (force_path == 0 && (tile_wins || tile_by_model))) {
         p.path = 4;
         p.prefetch = 1; p.waves_n = 8; p.waves_k = 1;
         tile_plan_choose(M, N, K, &p.m_rows16, &p.split_k);
         p.m_blocks = (int)((M + 32 * p.m_rows16 - 1) / (32 * p.m_rows16));
         return p;
     }
-    // 128 rows and more, up to where the tile kernel takes over, on 4-bit matrices of 40 MB and more with more input
-    // than output columns (the down projections): the wide kernel's 128-row variant with K split until there is a
-    // workgroup per compute unit.  3-12 % faster than the 64-row variant on the 70B and 405B down matrices at 128-512
-    // rows; within +-7 % on their qkv and o matrices, slower on every 8B shape, and on 8-bit weights ahead on one
-    // matrix only, so those keep the 64-row variant.
-    const bool tall_wide = wide_wins && bits == 4 && M >= 128 && (M + 127) / 128 * 2 <= (M + 63) / 64 &&
-                           packed_bytes >= ((size_t)40 << 20) && K > N;
+    // 128 rows and more, where the tile kernel has not taken over (in practice 128 to 191 rows), on 4-bit matrices of
+    // 40 MB and more with more input than output columns (the down projections): the wide kernel's 128-row variant
+    // with K split until there is a workgroup per compute unit.  3-12 % faster than the 64-row variant on the 70B and
+    // 405B down matrices; within +-7 % on their qkv and o matrices, slower on every 8B shape, and on 8-bit weights
+    // ahead on one matrix only, so those keep the 64-row variant.
     if (force_path == 0 && tall_wide) {
         p.path = 3;
         p.prefetch = 1; p.waves_n = 8; p.waves_k = 1; p.n_tiles16 = 2;

@@ -129,7 +129,10 @@ def test_bad_valid_combination_is_not_launched_without_gpu():
     q = rtn.rtn_linear_query(128, 16384, 53248, 4, 128)
     assert (q["path"], q["m_rows16"], q["n_tiles16"], q["waves_n"], q["split_k"]) == (3, 8, 2, 8, 4)
     assert rtn.rtn_workspace_nbytes(128, 16384, 53248, 4, 128) == 128 * 16384 * 4 * 4
-    assert rtn.rtn_linear_query(129, 16384, 53248, 4, 128)["m_rows16"] == 4      # 128-row padding would cost too much
+    # one row more: the 128-row variant would pad to 256, and the tile kernel with K in four splits is modelled (and
+    # measured) ahead of the 64-row wide plan
+    q = rtn.rtn_linear_query(129, 16384, 53248, 4, 128)
+    assert (q["path"], q["m_rows16"], q["split_k"]) == (4, 8, 4)
     assert rtn.rtn_linear_query(128, 16384, 53248, 8, 0)["m_rows16"] == 4
     assert rtn.rtn_linear_query(128, 4096, 14336, 4, 128)["m_rows16"] == 4
     # tile kernel: height and K split chosen together so that the last round of 256 workgroups is filled
