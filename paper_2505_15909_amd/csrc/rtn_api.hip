@@ -316,7 +316,7 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
         // this kernel at 17-32 rows); K is split across workgroups only as far as needed to occupy the compute units
         p.waves_n = streams16 ? 16 : 8;
         p.waves_k = 1;
-        const int64_t wgs = ((NT + 15) / 16) * p.m_blocks, want = 256;
+        const int64_t wgs = ((NT + 15) / 16) * p.m_blocks;
         if (streams16) {
             // one 16-wavefront workgroup runs per compute unit: as many splits as keep the launch within one round of
             // 256 (72 workgroups x 3 on the 405B qkv matrix: 45 us against 55 with two splits, 61-65 with four);
@@ -325,10 +325,11 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
             s = s < 1 ? 1 : (s > 8 ? 8 : (s > 4 && s < 8 ? 4 : s));
             while (s > 1 && (s > KC || (size_t)M * N * sizeof(float) * s > kWorkspaceCap)) --s;
             p.split_k = (int)s;
-        } else
-        while (wgs * p.split_k < want && p.split_k * 2 <= kMaxSplitK && p.split_k * 2 <= KC &&
-               (size_t)M * N * sizeof(float) * (p.split_k * 2) <= kWorkspaceCap)
-            p.split_k *= 2;
+        } else {
+            while (wgs * p.split_k < 256 && p.split_k * 2 <= kMaxSplitK && p.split_k * 2 <= KC &&
+                   (size_t)M * N * sizeof(float) * (p.split_k * 2) <= kWorkspaceCap)
+                p.split_k *= 2;
+        }
     }
     while (p.waves_n > 1 && p.waves_n > NT) p.waves_n /= 2;
     LinearArgs a;
