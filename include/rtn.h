@@ -59,7 +59,7 @@ typedef enum {
     RTN_ERR_GROUP = 3,     /* group_size not supported for this K / bits */
     RTN_ERR_SHAPE = 4,     /* M, N or K not supported (see conventions) */
     RTN_ERR_ALIGN = 5,     /* a device pointer is not 16-byte aligned */
-    RTN_ERR_WORKSPACE = 6, /* workspace smaller than rtn_workspace_nbytes() */
+    RTN_ERR_WORKSPACE = 6, /* workspace too small for the plan (an explicit split_k, or the small-batch kernel's own) */
     RTN_ERR_CONFIG = 7,    /* explicit kernel configuration invalid for this problem */
     RTN_ERR_HIP = 8        /* the HIP runtime reported an error at launch */
 } rtn_status;
@@ -121,8 +121,9 @@ rtn_status rtn_quantize_from_host(const void* host_W, int64_t N, int64_t K, int 
  *   dev_qweight    in   packed codes from rtn_quantize
  *   dev_scales     in   fp16 [N, K/g]
  *   dev_C          out  fp16 [M, N]
- *   dev_workspace  scratch, >= rtn_workspace_nbytes(M, N, K, bits, g); contents undefined
- *                  before and after; calls that overlap in time need distinct workspaces
+ *   dev_workspace  scratch, rtn_workspace_nbytes(M, N, K, bits, g) bytes for the plan the library
+ *                  prefers (from 17 rows, with less or NULL it splits K less: slower, not an error); contents
+ *                  undefined before and after; calls that overlap in time need distinct workspaces
  */
 rtn_status rtn_linear(const void* dev_A, int64_t M, const void* dev_qweight, const void* dev_scales,
                       int64_t N, int64_t K, int bits, int group_size, void* dev_C,

@@ -368,6 +368,13 @@ rtn_status resolve_plan(const LinearArgs& a, const rtn_linear_cfg* cfg, size_t w
     }
     const int64_t KC = a.K / chunk_k(a.bits);
     if (p.path < 1 || p.path > 4) return RTN_ERR_CONFIG;
+    // wide and tile kernels: a split the caller did not ask for shrinks to what the workspace passed can hold (slower,
+    // not an error; the skinny kernel's plans tie the staged slice to the split, so there it stays an error)
+    if (p.path >= 3 && !(cfg && cfg->split_k) && p.split_k > 1) {
+        const size_t one = (size_t)a.M * a.N * sizeof(float);
+        const size_t fit = a.workspace ? workspace_nbytes / one : 0;
+        if ((size_t)p.split_k > fit) p.split_k = fit < 1 ? 1 : (int)fit;
+    }
     if (p.path >= 3) {
         const bool ok = p.path == 3 ? rtn::wide_plan_valid(a, p) : rtn::tile_plan_valid(a, p);
         if (!ok || p.split_k > kMaxSplitK) return RTN_ERR_CONFIG;

@@ -434,6 +434,25 @@ def test_linear_split_k_graph_replays_match_direct_calls(rtn, M, cfg):
     H.assert_linear_close(_to_np(out_g), O.rtn_linear(_to_np(A_static), codes, scales, gg), f"graph replay M={M}")
 
 
+def test_linear_automatic_split_shrinks_to_the_workspace_passed(rtn):
+    """From 17 rows the plan's K split is a preference: with a workspace too small for it (here none of the partial
+    sums fit) the call still succeeds, unsplit, and matches the oracle like the call with the full workspace."""
+    N, K, M = 4096, 4096, 64
+    codes, scales, qw, sc, gg = _oracle_operands(N, K, 4, 128, seed=41)
+    q = rtn.rtn_linear_query(M, N, K, 4, 128)
+    assert q["path"] == 3 and q["split_k"] > 1, q
+    A_t = synth.activation(M, K, seed=3, device=DEV)
+    ref = O.rtn_linear(_to_np(A_t), codes, scales, gg)
+    full = rtn.rtn_linear(A_t, qw, sc, 4, 128)
+    small = rtn.rtn_linear(A_t, qw, sc, 4, 128, workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
+    torch.cuda.synchronize()
+    H.assert_linear_close(_to_np(full), ref, "full workspace")
+    H.assert_linear_close(_to_np(small), ref, "256-byte workspace")
+    with pytest.raises(rtn.RtnError):       # an explicit split is not negotiable
+        rtn.rtn_linear(A_t, qw, sc, 4, 128, workspace=torch.empty(256, dtype=torch.uint8, device=DEV),
+                       cfg=dict(path=3, split_k=q["split_k"]))
+
+
 def test_linear_automatic_plans_on_large_random_shapes(rtn):
     """What rtn_linear chooses by itself from 48 rows up on matrices large enough for every branch of its plan (wide
     kernel with 1-8 K splits, its 128-row variant, tile kernel of either height with and without splits), with the
