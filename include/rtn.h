@@ -115,8 +115,10 @@ rtn_status rtn_quantize_from_host(const void* host_W, int64_t N, int64_t K, int 
  * token generation):  C[m, n] = fp16( sum_k A[m, k] * q[n, k] * S[n, k / g] ), products and
  * sums in fp32 (codes enter the matrix cores exactly; the scale multiplies fp32 group
  * partial sums).  Any M >= 1; the path (wavefront-level skinny kernel with split-K for
- * small M, wider MFMA tiles for larger M) is chosen from M, N, K.  Deterministic: the same
- * inputs give the same output bits (split-K partials are summed in a fixed order).
+ * small M, wider MFMA tiles for larger M) is chosen from M, N, K; from 128 rows a call may
+ * issue the tile kernel twice (full rounds of workgroups, then the last rows with K split).
+ * Deterministic: the same inputs with the same workspace size give the same output bits
+ * (split-K partials are summed in a fixed order).
  *   dev_A          in   fp16 [M, K]
  *   dev_qweight    in   packed codes from rtn_quantize
  *   dev_scales     in   fp16 [N, K/g]

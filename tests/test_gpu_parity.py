@@ -453,6 +453,27 @@ def test_linear_automatic_split_shrinks_to_the_workspace_passed(rtn):
                        cfg=dict(path=3, split_k=q["split_k"]))
 
 
+@pytest.mark.parametrize("M", [1024, 2048])
+def test_linear_tile_kernel_in_two_launches(rtn, M):
+    """The 405B-shaped qkv matrix at 1024 and 2048 rows: 72 column blocks make 288 / 576 tall tiles, a round and an
+    eighth (or a quarter) of 256, so rtn_linear runs the first 768 / 1792 rows as full rounds and the last 256 rows
+    as a launch of their own with K split.  Rows on both sides of the seam and a stripe of columns against the oracle."""
+    K, N = synth.LLAMA_405B["qkv"]
+    W_t = synth.normal_weight(N, K, 0.01, seed=77, device=DEV)
+    qw, sc = rtn.rtn_quantize(W_t, 4, 128)
+    del W_t
+    A_t = synth.activation(M, K, seed=M, device=DEV)
+    assert rtn.rtn_linear_query(M, N, K, 4, 128)["path"] == 4
+    C = rtn.rtn_linear(A_t, qw, sc, 4, 128)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(M)
+    cols = np.unique(np.concatenate([np.arange(0, 16), np.arange(N - 16, N), rng.integers(0, N, 64)]))
+    rows = np.unique(np.concatenate([np.arange(0, 4), np.arange(M - 260, M - 252), np.arange(M - 4, M), rng.integers(0, M, 48)]))
+    codes = _to_np(rtn.rtn_unpack(qw, N, K, 4))[cols]
+    ref = O.rtn_linear(_to_np(A_t)[rows], codes, _to_np(sc)[cols], 128)
+    H.assert_linear_close(_to_np(C)[np.ix_(rows, cols)], ref, f"two launches M={M}")
+
+
 def test_linear_automatic_plans_on_large_random_shapes(rtn):
     """What rtn_linear chooses by itself from 48 rows up on matrices large enough for every branch of its plan (wide
     kernel with 1-8 K splits, its 128-row variant, tile kernel of either height with and without splits), with the
