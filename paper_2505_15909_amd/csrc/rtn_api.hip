@@ -636,7 +636,7 @@ rtn_status rtn_quantize_from_host(const void* host_W, int64_t N, int64_t K, int 
 // launch picks the height from the rounds of 256 workgroups each would take); a workgroup costs 8 us besides, and a
 // split adds the partials' round trip through the workspace (write and read of split x M x N fp32 at ~4.5 TB/s) and
 // the reduce launch.
-static int dense_split(int64_t M, int64_t N, int64_t K, size_t workspace_nbytes) {
+static int dense_split(int64_t M, int64_t N, int64_t K, size_t workspace_nbytes, double* time_us = nullptr) {
     const int64_t xb = (N + 255) / 256;
     int best = 1;
     double best_t = 1e30;
@@ -653,7 +653,23 @@ static int dense_split(int64_t M, int64_t N, int64_t K, size_t workspace_nbytes)
             best = s;
         }
     }
+    if (time_us) *time_us = best_t;
     return best;
+}
+
+// The dense GEMM in two launches, as rtn_linear does with the fused tile kernel: the first rows (a multiple of 256) as
+// full rounds, the rest with the K split that fills its round; 0 where one launch is modelled within 7 % of that.
+static int64_t dense_two_launches(int64_t M, int64_t N, int64_t K, size_t workspace_nbytes) {
+    double single = 0, t1 = 0, t2 = 0;
+    dense_split(M, N, K, workspace_nbytes, &single);
+    double best = single * 0.93;
+    int64_t rows_first = 0;
+    for (int64_t r1 = 256; r1 < M; r1 += 256) {
+        dense_split(r1, N, K, workspace_nbytes, &t1);
+        dense_split(M - r1, N, K, workspace_nbytes, &t2);
+        if (t1 + t2 < best) { best = t1 + t2; rows_first = r1; }
+    }
+    return rows_first;
 }
 
 rtn_status rtn_gemm_fp16(const void* dev_A, int64_t M, const void* dev_W_fp16, int64_t N, int64_t K, void* dev_C,
@@ -662,6 +678,16 @@ rtn_status rtn_gemm_fp16(const void* dev_A, int64_t M, const void* dev_W_fp16, i
     if (M <= 0 || M > (1 << 20) || N <= 0 || N % 16 != 0 || K <= 0 || K % 128 != 0) return RTN_ERR_SHAPE;
     if ((uint64_t)K * 2 * 128 >= 0x7FFF0000ull) return RTN_ERR_SHAPE;          // one 128-row slab per buffer resource
     if (!aligned16(dev_A) || !aligned16(dev_W_fp16) || !aligned16(dev_C) || !aligned16(dev_workspace)) return RTN_ERR_ALIGN;
+    const int64_t rows_first = dev_workspace ? dense_two_launches(M, N, K, workspace_nbytes) : 0;
+    for (int part = 0; rows_first > 0 && part < 2; ++part) {
+        const int64_t r0 = part == 0 ? 0 : rows_first, rows = part == 0 ? rows_first : M - rows_first;
+        const int s = dense_split(rows, N, K, workspace_nbytes);
+        if (rtn::launch_gemm_fp16(static_cast<const char*>(dev_A) + (size_t)r0 * K * 2, dev_W_fp16,
+                                  static_cast<char*>(dev_C) + (size_t)r0 * N * 2, static_cast<float*>(dev_workspace),
+                                  rows, N, K, s, static_cast<hipStream_t>(stream)) != hipSuccess)
+            return RTN_ERR_HIP;
+    }
+    if (rows_first > 0) return RTN_OK;
     const int split = dev_workspace ? dense_split(M, N, K, workspace_nbytes) : 1;
     hipError_t e = rtn::launch_gemm_fp16(dev_A, dev_W_fp16, dev_C, static_cast<float*>(dev_workspace), M, N, K, split,
                                          static_cast<hipStream_t>(stream));
