@@ -192,6 +192,7 @@ double tile_plan_choose(int64_t M, int64_t N, int64_t K, int* rows16, int* split
 // 405B at 2048 rows 1044 us against 1236, at 1024 rows 565 against 641; 70B at 2048 rows 324 against 374; 8B at 4096
 // rows 208 against 232; no gain (and none modelled) where the tiles fill their rounds.
 int64_t tile_two_launches(int64_t M, int64_t N, int64_t K) {
+    if (M > 16384) return 0;                                   // many rounds: the last one no longer matters
     int r16, sk;
     const double single = tile_plan_choose(M, N, K, &r16, &sk);
     double best = single * 0.93;
@@ -660,6 +661,7 @@ static int dense_split(int64_t M, int64_t N, int64_t K, size_t workspace_nbytes,
 // The dense GEMM in two launches, as rtn_linear does with the fused tile kernel: the first rows (a multiple of 256) as
 // full rounds, the rest with the K split that fills its round; 0 where one launch is modelled within 7 % of that.
 static int64_t dense_two_launches(int64_t M, int64_t N, int64_t K, size_t workspace_nbytes) {
+    if (M > 16384) return 0;                                   // many rounds: the last one no longer matters
     double single = 0, t1 = 0, t2 = 0;
     dense_split(M, N, K, workspace_nbytes, &single);
     double best = single * 0.93;
