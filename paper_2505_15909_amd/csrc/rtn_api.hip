@@ -773,6 +773,9 @@ rtn_status rtn_linear_asym(const void* dev_A, int64_t M, const void* dev_qweight
         LinearPlan h;
         wide_plan(M, N, K, bits, &h);
         cfg.path = 3; cfg.prefetch = 1; cfg.waves_n = 8; cfg.waves_k = 1; cfg.split_k = h.split_k;
+        // as many of the plan's K splits as the workspace passed can hold
+        const size_t fit = dev_workspace ? workspace_nbytes / ((size_t)M * N * sizeof(float)) : 0;
+        if ((size_t)cfg.split_k > fit) cfg.split_k = fit < 1 ? 1 : (int)fit;
         cfg.m_rows16 = h.m_rows16; cfg.n_tiles16 = h.n_tiles16 > 2 ? 2 : h.n_tiles16;
         planned = resolve_plan(a, &cfg, workspace_nbytes, &p) == RTN_OK;
     }
