@@ -212,10 +212,12 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
     // more than 16 rows: the wide kernel, except at 17-32 rows on large matrices, where the skinny kernel's pure
     // weight streaming still wins.  4 bit: from 40 MB with rows of 8192 columns and more, 16 wavefronts side by side
     // (6-20 % faster on the 70B and 405B shapes except the 70B o matrix; the wide kernel wins on every 8B shape).
-    // 8 bit: above 256 MB, 8 wavefronts (the 16-wavefront shape is faster on some of those matrices, slower on others).
+    // 8 bit: above 256 MB, the same 16-wavefront shape (with K split to one round of workgroups it is 15-20 % faster
+    // than 8 wavefronts on the 70B gate_up and 405B qkv matrices and level on the 405B gate_up and down matrices).
     const size_t packed_bytes = (size_t)N * K * bits / 8;
-    const bool streams16 = M <= 32 && bits == 4 && packed_bytes >= ((size_t)40 << 20) && K >= 8192;
-    const bool streams_at_32 = streams16 || (M <= 32 && packed_bytes > ((size_t)256 << 20));
+    const bool streams16 = M <= 32 && ((bits == 4 && packed_bytes >= ((size_t)40 << 20) && K >= 8192) ||
+                                       packed_bytes > ((size_t)256 << 20));
+    const bool streams_at_32 = streams16;
     const bool wide_wins = g % 128 == 0 && M > 16 && !streams_at_32;
     // 128 rows and more, and enough 128 x 256 output tiles to fill 9/16 of the compute units without splitting K:
     // the tile kernel (measured against the wide kernel on the 8B, 70B and 405B shapes at M = 128 ... 4096: it wins
