@@ -24,6 +24,10 @@
  *     otherwise g must be 32, 64, 128, 256, 512 or a multiple of 512 dividing K for 4-bit and 32, 64,
  *     128, 256 or a multiple of 256 dividing K for 8-bit (the paper uses 128 and per-channel; the
  *     smaller groups of Section 2.2's discussion run on the skinny kernel at every M).
+ *   - Size limits of the GEMM entry points (the kernels address each tensor with 32-bit byte offsets): packed
+ *     weights N*K*bits/8 and activations M*K*2 must each stay below 0x7FFF0000 bytes (2 GiB - 64 KiB), else
+ *     RTN_ERR_SHAPE; M <= 2^20; N <= 2^30; K < 2^23 (group indices come from a multiply-high division that is
+ *     exact below that).
  *   - Scales are fp16 [N, K/g] row-major (group j of row n covers columns j*g .. j*g+g-1):
  *     the sub-channel grouping of Section 2.2.
  *
@@ -158,6 +162,14 @@ rtn_status rtn_linear_ex(const void* dev_A, int64_t M, const void* dev_qweight, 
 /* Reports the configuration rtn_linear would use (host only, launches nothing). */
 rtn_status rtn_linear_query(int64_t M, int64_t N, int64_t K, int bits, int group_size, rtn_linear_cfg* out);
 
+/* Host-only checks, nothing is launched and no pointer is needed.  rtn_problem_status: the status every entry point
+ * gives for this (N, K, bits, group_size) before it looks at anything else.  rtn_linear_validate: the status
+ * rtn_linear_ex would give for this problem, configuration (NULL = automatic) and workspace size once its pointers
+ * have passed (shape, group, configuration and workspace checks; RTN_OK means the launch would be issued). */
+rtn_status rtn_problem_status(int64_t N, int64_t K, int bits, int group_size);
+rtn_status rtn_linear_validate(int64_t M, int64_t N, int64_t K, int bits, int group_size, size_t workspace_nbytes,
+                               const rtn_linear_cfg* cfg);
+
 /* Test / debug hook: packed codes -> int8 [N, K] row-major (the inverse of the layout). */
 rtn_status rtn_unpack(const void* dev_qweight, int64_t N, int64_t K, int bits, void* dev_codes_i8, void* stream);
 
@@ -249,7 +261,7 @@ rtn_status rtn_grouped_forward(const rtn_module* mods, int n_mods, void* dev_wor
  * is 4 bit.  Returns 4 or 8, or -1 on invalid arguments.  Host only. */
 int rtn_plan_bits(int layer, int n_layers, int module_id, int policy, int X, unsigned module_mask);
 
-/* Average bits per weight of such a plan (Section 4.3: "effectively quantized into 5 bit");
+/* Average bits per weight of such a plan (Section 4.3: a quarter / a half of the layers at 8 bit average 5 / 6 bits);
  * module_params[i] = weights of module i+1 in one layer.  Returns -1 on invalid arguments. */
 double rtn_plan_effective_bits(int n_layers, const int64_t module_params[4], int policy, int X,
                                unsigned module_mask);

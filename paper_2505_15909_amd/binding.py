@@ -38,7 +38,7 @@ class rtn_module(C.Structure):
 def _load() -> C.CDLL:
     path = _build.LIB_PATH
     if not os.path.exists(path):
-        _build.build_library()
+        raise ImportError(f"{path} is not built: run `python paper_2505_15909_amd/build.py` (or __graft_entry__.build()) first")
     lib = C.CDLL(path)
     vp, i64, ci, sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
     lib.rtn_status_str.restype = C.c_char_p
@@ -82,6 +82,10 @@ def _load() -> C.CDLL:
     lib.rtn_linear_asym.argtypes = [vp, i64, vp, vp, vp, i64, i64, ci, ci, vp, vp, sz, vp]
     lib.rtn_grouped_forward.restype = ci
     lib.rtn_grouped_forward.argtypes = [C.POINTER(rtn_module), ci, vp, sz, vp]
+    lib.rtn_problem_status.restype = ci
+    lib.rtn_problem_status.argtypes = [i64, i64, ci, ci]
+    lib.rtn_linear_validate.restype = ci
+    lib.rtn_linear_validate.argtypes = [i64, i64, i64, ci, ci, sz, C.POINTER(rtn_linear_cfg)]
     lib.rtn_plan_bits.restype = ci
     lib.rtn_plan_bits.argtypes = [ci, ci, ci, ci, ci, C.c_uint]
     lib.rtn_plan_effective_bits.restype = C.c_double
@@ -92,7 +96,7 @@ def _load() -> C.CDLL:
 _lib = _load()
 EXPORTS = ["rtn_status_str", "rtn_layout_version", "rtn_qweight_nbytes", "rtn_scales_nbytes",
            "rtn_workspace_nbytes", "rtn_quantize", "rtn_quantize_host_staging_nbytes", "rtn_quantize_from_host", "rtn_linear", "rtn_linear_ex", "rtn_linear_query",
-           "rtn_unpack", "rtn_dequantize", "rtn_gemm_fp16", "rtn_dense_weight_nbytes", "rtn_linear_dense",
+           "rtn_problem_status", "rtn_linear_validate", "rtn_unpack", "rtn_dequantize", "rtn_gemm_fp16", "rtn_dense_weight_nbytes", "rtn_linear_dense",
            "rtn_quantize_asym", "rtn_dequantize_asym", "rtn_linear_asym",
            "rtn_layer_forward", "rtn_grouped_forward", "rtn_plan_bits", "rtn_plan_effective_bits"]
 
@@ -140,7 +144,7 @@ def rtn_quantize(W: torch.Tensor, bits: int, group_size: int, flags: int = RTN_S
         nb = _lib.rtn_qweight_nbytes(N, K, bits)
         ns = _lib.rtn_scales_nbytes(N, K, g)
         if nb == 0 or ns == 0:
-            _check(_lib.rtn_quantize(W.data_ptr(), N, K, bits, group_size, flags, 1, 1, None), "rtn_quantize")
+            _check(_lib.rtn_problem_status(N, K, bits, group_size) or 4, "rtn_quantize")
         qweight = torch.empty(nb, dtype=torch.uint8, device=W.device)
         scales = torch.empty((N, K // g), dtype=torch.float16, device=W.device)
     else:
@@ -181,6 +185,16 @@ def rtn_linear_query(M, N, K, bits, group_size) -> dict:
     c = rtn_linear_cfg()
     _check(_lib.rtn_linear_query(M, N, K, bits, group_size, C.byref(c)), "rtn_linear_query")
     return {k: getattr(c, k) for k, _ in rtn_linear_cfg._fields_}
+
+
+def rtn_problem_status(N, K, bits, group_size) -> int:
+    return _lib.rtn_problem_status(N, K, bits, group_size)
+
+
+def rtn_linear_validate(M, N, K, bits, group_size, workspace_nbytes, cfg=None) -> int:
+    """Host only: the status rtn_linear_ex would return for this problem and configuration (0 = it would launch)."""
+    c = make_cfg(cfg)
+    return _lib.rtn_linear_validate(M, N, K, bits, group_size, workspace_nbytes, None if c is None else C.byref(c))
 
 
 def rtn_unpack(qweight: torch.Tensor, N: int, K: int, bits: int) -> torch.Tensor:

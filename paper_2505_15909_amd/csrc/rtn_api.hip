@@ -28,7 +28,9 @@ int tile_k(int bits) { return bits == 4 ? 128 : 64; }
 rtn_status check_problem(int64_t N, int64_t K, int bits, int group_size, int64_t* g_out) {
     if (bits != 4 && bits != 8) return RTN_ERR_BITS;
     if (N <= 0 || K <= 0 || N % 16 != 0 || K % chunk_k(bits) != 0) return RTN_ERR_SHAPE;
-    if (N > (int64_t)1 << 30 || K > (int64_t)1 << 30) return RTN_ERR_SHAPE;
+    // K < 2^23: the kernels divide k-step and chunk indices by the group length with a multiply-high by
+    // floor(2^32 / d) + 1, exact while index * d < 2^32
+    if (N > (int64_t)1 << 30 || K >= (int64_t)1 << 23) return RTN_ERR_SHAPE;
     int64_t g = (group_size <= 0) ? K : group_size;
     if (g > K || K % g != 0) return RTN_ERR_GROUP;
     const int ck = chunk_k(bits), tk = tile_k(bits);
@@ -539,6 +541,27 @@ rtn_status rtn_linear(const void* dev_A, int64_t M, const void* dev_qweight, con
                          workspace_nbytes, stream, nullptr);
 }
 
+rtn_status rtn_problem_status(int64_t N, int64_t K, int bits, int group_size) {
+    int64_t g;
+    return check_problem(N, K, bits, group_size, &g);
+}
+
+rtn_status rtn_linear_validate(int64_t M, int64_t N, int64_t K, int bits, int group_size, size_t workspace_nbytes,
+                               const rtn_linear_cfg* cfg) {
+    int64_t g;
+    rtn_status st = check_problem(N, K, bits, group_size, &g);
+    if (st != RTN_OK) return st;
+    if (M <= 0 || M > (1 << 20)) return RTN_ERR_SHAPE;
+    LinearArgs a;
+    a.A = nullptr; a.qweight = nullptr; a.scales = nullptr; a.C = nullptr;
+    // only "is there a workspace" matters to the plan checks; nothing is launched and the address is never used
+    static float workspace_stand_in;
+    a.workspace = workspace_nbytes > 0 ? &workspace_stand_in : nullptr;
+    a.M = M; a.N = N; a.K = K; a.g = g; a.bits = bits;
+    LinearPlan p;
+    return resolve_plan(a, cfg, workspace_nbytes, &p);
+}
+
 rtn_status rtn_linear_query(int64_t M, int64_t N, int64_t K, int bits, int group_size, rtn_linear_cfg* out) {
     if (!out) return RTN_ERR_NULL;
     int64_t g;
@@ -596,13 +619,15 @@ rtn_status rtn_quantize_from_host(const void* host_W, int64_t N, int64_t K, int 
     const float qmax = (float)((1 << (bits - 1)) - 1);
     const float divisor = (flags == RTN_SCALE_EQ2) ? qmax + 0.5f : qmax;
     const size_t shard_bytes = (size_t)rows_per_shard * K * 2;
-    hipEvent_t copied[2], consumed[2], start;
-    bool ok = hipEventCreateWithFlags(&start, hipEventDisableTiming) == hipSuccess;
-    for (int i = 0; i < 2 && ok; ++i) {
-        ok = hipEventCreateWithFlags(&copied[i], hipEventDisableTiming) == hipSuccess &&
-             hipEventCreateWithFlags(&consumed[i], hipEventDisableTiming) == hipSuccess;
+    hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};   // start, copied[0..1], consumed[0..1]
+    bool ok = true;
+    for (int i = 0; i < 5 && ok; ++i) ok = hipEventCreateWithFlags(&ev[i], hipEventDisableTiming) == hipSuccess;
+    if (!ok) {                                                  // destroy what was created before the failure
+        for (int i = 0; i < 5; ++i)
+            if (ev[i]) (void)hipEventDestroy(ev[i]);
+        return RTN_ERR_HIP;
     }
-    if (!ok) return RTN_ERR_HIP;
+    hipEvent_t start = ev[0], *copied = &ev[1], *consumed = &ev[3];
     // the copy stream starts after whatever the caller queued on `stream` before this call (the staging buffer
     // may still be in use there)
     ok = hipEventRecord(start, qs) == hipSuccess && hipStreamWaitEvent(cs, start, 0) == hipSuccess;

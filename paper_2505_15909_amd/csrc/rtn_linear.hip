@@ -9,10 +9,14 @@
 // of the workgroup's K range.  Per chunk it issues four 16-byte-per-lane loads (1 KiB per
 // wavefront each, fully coalesced), unpacks the codes in registers to exact fp16 integers and
 // feeds them as the B operand of v_mfma_f32_16x16x32_f16.  The A operand is the activation
-// block, zero-padded to 16 rows, staged per workgroup in LDS (padded rows, one shared all-zero
-// row for the padding lanes; in one stage when the slice fits, else in stages of SC chunks per
-// wavefront whose global loads are issued one stage ahead) and read 16 bytes per lane right
-// before each MFMA.
+// block staged per workgroup in LDS (padded rows) and read 16 bytes per lane right before each
+// MFMA; lanes of batch rows beyond M read the last valid row (output rows never mix in a matrix
+// product, and those rows are not stored).  When the slice fits one stage it goes from global memory
+// straight into LDS (buffer_load ... lds: no registers, no LDS store instructions, every address
+// wave-uniform arithmetic), all of it requested before the first weight load; a workgroup one
+// wavefront wide along N stages per wavefront and needs no barrier before the main loop.  Larger
+// slices are staged through registers in stages of SC chunks per wavefront whose global loads are
+// issued one stage ahead.
 // Scales multiply the fp32 partial sum of each group (exact codes into the matrix cores, one
 // fp32 multiply-add per group and output), never the individual weights.  The WK partial
 // results of a tile-row are summed through LDS in a fixed order; an optional global split-K
@@ -26,7 +30,8 @@
 // every path, which lets the compiler wait with exact vmcnt values instead of draining the
 // queue, and NB register buffers rotate so that NB-1 chunks are in flight while one is
 // consumed.  The activation loads are issued before the weight loads so that staging does
-// not wait behind the (longer) HBM latency of the weights.
+// not wait behind the (longer) HBM latency of the weights: loads complete in order, so waiting
+// until only the weight loads issued after them are outstanding means the staged rows have landed.
 //
 // MFMA operand maps (16x16x32 f16): a-operand lane l = row l % 16, k-slot l / 16 (8 halves);
 // b-operand lane l = column l % 16, same k-slot; result lane l, register e = row 4 (l/16) + e,
@@ -118,6 +123,11 @@ __device__ __forceinline__ typename ScaleVec<NGC>::raw_t load_scales(__amdgpu_bu
     }
 }
 
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+
 // MULTI = false: the workgroup's whole activation slice is staged once, before the main loop.
 // MULTI = true: it is staged sc chunks per wavefront at a time, one stage ahead, one round per stage.
 // MB: 16-row activation blocks per wavefront (batch rows per workgroup = 16 MB); every unpacked weight
@@ -162,10 +172,10 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& p, const int bx,
     // ---- activation staging --------------------------------------------------------------------
     // A stage holds, for every row and every K-wavefront w, the sc chunks that wavefront w consumes
     // in this stage: LDS [row][w][sc * CK] (+ pad).  Thread t moves pieces t, t + nthreads, ...; a
-    // piece is 16 bytes: piece -> (row, w, octet).  Rows >= Mb (the shared zero row) and columns past
-    // a wavefront's share are loaded out of range, i.e. as zeros, without memory traffic.
+    // piece is 16 bytes: piece -> (row, w, octet).  Rows >= Mb and columns past a wavefront's share are
+    // loaded out of range, i.e. as zeros, without memory traffic (register path of the staged mode).
     half_t* lds_a = reinterpret_cast<half_t*>(lds_bytes);
-    const int rows_staged = Mb < MROWS ? Mb + 1 : MROWS;               // + the shared zero row
+    const int rows_staged = Mb;
     constexpr int CK8_SHIFT = (BITS == 4) ? 6 : 5;                     // log2(CK / 8)
     const int seg_shift = p.sc_shift + CK8_SHIFT;                     // log2(pieces per wavefront segment)
     u32x4_t stg[kStagePieces];
@@ -208,17 +218,45 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& p, const int bx,
             wbuf[j][c] = __builtin_amdgcn_raw_buffer_load_b128(rw, wo + c * 1024, 0, 2 /* nt: read-once stream */);
     };
 
-    stage_load(0, 0);                     // activation loads first: the oldest loads in flight
+    constexpr int LPC = ((NGC == 16) ? 2 : 1) * (ZP ? 2 : 1) + kChunkTiles;   // loads per fetch()
+    if constexpr (MULTI) {
+        stage_load(0, 0);                     // activation loads first: the oldest loads in flight
 #pragma unroll
-    for (int j = 0; j < NB; ++j) fetch(j, cw0 + j);
-    stage_store();
-    if constexpr (!MULTI) {
-        for (int r = 1; r < p.stage_rounds; ++r) {                    // rest of a large single stage
-            stage_load(0, r);
-            stage_store();
+        for (int j = 0; j < NB; ++j) fetch(j, cw0 + j);
+        stage_store();
+    } else {
+        // The whole slice goes global -> LDS directly (buffer_load ... lds, 16 bytes per lane, no registers): one
+        // instruction moves a run = one k-chunk of one staged row (64 lanes x 16 bytes at 4 bit, 32 lanes at 8 bit).
+        // Runs are dealt to the wavefronts by (column run, row) so that every address is wave-uniform arithmetic.
+        constexpr int RP = GM::CK / 8;
+        const int nwaves = nthreads >> 6;
+        const int rpr = p.WK << p.sc_shift;                           // runs per staged row
+        int col0, col_step, row0, row_step, col_end = rpr;
+        if (p.WN == 1) {
+            // every wavefront has a K-slice of its own: it stages just that (no other wavefront reads it, no barrier)
+            col0 = wk << p.sc_shift; col_step = 1; col_end = col0 + p.sc; row0 = 0; row_step = 1;
+        } else if (rpr >= nwaves) { col0 = wave; col_step = nwaves; row0 = 0; row_step = 1; }
+        else { col0 = (wk << p.sc_shift) + (wn & (p.sc - 1)); col_step = rpr; row0 = wn >> p.sc_shift; row_step = p.WN >> p.sc_shift; }
+        if (RP == 64 || lane < RP) {
+            const uint32_t lane_off = lane * 16;
+            for (int col = col0; col < col_end; col += col_step) {
+                const int w = col >> p.sc_shift, j = col & (p.sc - 1);
+                const int c0 = min(cb0 + w * p.per, cb1), c1 = min(c0 + p.per, cb1);
+                const int c = c0 + j;
+                if (c < c1) {
+                    for (int row = row0; row < Mb; row += row_step) {
+                        const uint32_t soff = ((uint32_t)(m0 + row) * (uint32_t)p.K + (uint32_t)c * GM::CK) * 2u;
+                        const uint32_t ldsoff = (uint32_t)(row * p.lds_stride + col * GM::CK) * 2u;
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (__attribute__((address_space(3))) void*)(lds_bytes + ldsoff), 16, lane_off, soff, 0, 0);
+                    }
+                }
+            }
         }
+#pragma unroll
+        for (int j = 0; j < NB; ++j) fetch(j, cw0 + j);
+        wait_vmcnt<NB * LPC>();               // the staging loads are older than the NB chunks just requested
     }
-    __syncthreads();
+    if (MULTI || p.WN > 1) __syncthreads();
 
     // ---- main loop -------------------------------------------------------------------------------
     float4_t acc[MB];
@@ -226,7 +264,7 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& p, const int bx,
 #pragma unroll
     for (int b = 0; b < MB; ++b) {
         acc[b] = (float4_t){0.f, 0.f, 0.f, 0.f};
-        arow[b] = lds_a + min(b * 16 + nl, Mb) * p.lds_stride + ((wk << p.sc_shift) * GM::CK) + kq * 8;
+        arow[b] = lds_a + min(b * 16 + nl, Mb - 1) * p.lds_stride + ((wk << p.sc_shift) * GM::CK) + kq * 8;
     }
     const half_t* adot = lds_a + ((wk << p.sc_shift) * GM::CK) + kq * 8;   // DOT: row 0 of this k-slot
     (void)adot;
@@ -416,7 +454,7 @@ static StageGeom stage_geometry(const LinearArgs& a, const LinearPlan& p) {
     StageGeom g;
     g.per = (blk + p.waves_k - 1) / p.waves_k;
     const int mrows = 16 * p.m_rows16;                               // batch rows per workgroup
-    g.rows = (int)(a.M < mrows ? a.M + 1 : mrows);
+    g.rows = (int)(a.M < mrows ? a.M : mrows);
     const int nthreads = 64 * p.waves_n * p.waves_k;
     const size_t red = p.waves_k > 1 ? (size_t)(p.waves_k - 1) * p.waves_n * p.m_rows16 * 1024 : 0;
     auto bytes_of = [&](int sc) { return (size_t)g.rows * ((size_t)p.waves_k * sc * ck + kLdsPadHalves) * 2; };
