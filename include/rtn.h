@@ -170,6 +170,18 @@ rtn_status rtn_problem_status(int64_t N, int64_t K, int bits, int group_size);
 rtn_status rtn_linear_validate(int64_t M, int64_t N, int64_t K, int bits, int group_size, size_t workspace_nbytes,
                                const rtn_linear_cfg* cfg);
 
+/* rtn_linear for callers that cannot allocate device memory or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation.  Same arguments, results and plan as rtn_linear with a
+ * workspace of rtn_workspace_nbytes() bytes, but the split-K partial sums go to a fixed 16 MiB device array inside
+ * the library (one copy per GPU, held until the process ends) instead of a caller's buffer; the call allocates and
+ * frees nothing.  Problems whose rtn_workspace_nbytes() exceeds 16 MiB (only possible from 64 rows) are refused
+ * with RTN_ERR_WORKSPACE: use rtn_linear with a workspace for those.  All calls on one GPU share that array, so
+ * calls that overlap in time on one GPU (different streams, concurrently replayed graphs) race; calls ordered on a
+ * stream are safe.  The first call on a device looks up the array's address (hipGetSymbolAddress); make it before
+ * capturing a graph. */
+rtn_status rtn_linear_noalloc(const void* dev_A, int64_t M, const void* dev_qweight, const void* dev_scales,
+                              int64_t N, int64_t K, int bits, int group_size, void* dev_C, void* stream);
+
 /* Test / debug hook: packed codes -> int8 [N, K] row-major (the inverse of the layout). */
 rtn_status rtn_unpack(const void* dev_qweight, int64_t N, int64_t K, int bits, void* dev_codes_i8, void* stream);
 

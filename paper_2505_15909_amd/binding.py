@@ -86,6 +86,8 @@ def _load() -> C.CDLL:
     lib.rtn_problem_status.argtypes = [i64, i64, ci, ci]
     lib.rtn_linear_validate.restype = ci
     lib.rtn_linear_validate.argtypes = [i64, i64, i64, ci, ci, sz, C.POINTER(rtn_linear_cfg)]
+    lib.rtn_linear_noalloc.restype = ci
+    lib.rtn_linear_noalloc.argtypes = [vp, i64, vp, vp, i64, i64, ci, ci, vp, vp]
     lib.rtn_plan_bits.restype = ci
     lib.rtn_plan_bits.argtypes = [ci, ci, ci, ci, ci, C.c_uint]
     lib.rtn_plan_effective_bits.restype = C.c_double
@@ -96,7 +98,7 @@ def _load() -> C.CDLL:
 _lib = _load()
 EXPORTS = ["rtn_status_str", "rtn_layout_version", "rtn_qweight_nbytes", "rtn_scales_nbytes",
            "rtn_workspace_nbytes", "rtn_quantize", "rtn_quantize_host_staging_nbytes", "rtn_quantize_from_host", "rtn_linear", "rtn_linear_ex", "rtn_linear_query",
-           "rtn_problem_status", "rtn_linear_validate", "rtn_unpack", "rtn_dequantize", "rtn_gemm_fp16", "rtn_dense_weight_nbytes", "rtn_linear_dense",
+           "rtn_problem_status", "rtn_linear_validate", "rtn_linear_noalloc", "rtn_unpack", "rtn_dequantize", "rtn_gemm_fp16", "rtn_dense_weight_nbytes", "rtn_linear_dense",
            "rtn_quantize_asym", "rtn_dequantize_asym", "rtn_linear_asym",
            "rtn_layer_forward", "rtn_grouped_forward", "rtn_plan_bits", "rtn_plan_effective_bits"]
 
@@ -195,6 +197,17 @@ def rtn_linear_validate(M, N, K, bits, group_size, workspace_nbytes, cfg=None) -
     """Host only: the status rtn_linear_ex would return for this problem and configuration (0 = it would launch)."""
     c = make_cfg(cfg)
     return _lib.rtn_linear_validate(M, N, K, bits, group_size, workspace_nbytes, None if c is None else C.byref(c))
+
+
+def rtn_linear_noalloc(A: torch.Tensor, qweight: torch.Tensor, scales: torch.Tensor, bits: int, group_size: int,
+                       out: torch.Tensor) -> torch.Tensor:
+    """rtn_linear without a workspace argument: split-K partials go to the library's fixed device array."""
+    _dev_fp16(A, "A")
+    M, K = A.shape
+    N = scales.shape[0]
+    _check(_lib.rtn_linear_noalloc(A.data_ptr(), M, qweight.data_ptr(), scales.data_ptr(), N, K, bits, group_size,
+                                   out.data_ptr(), _stream()), "rtn_linear_noalloc")
+    return out
 
 
 def rtn_unpack(qweight: torch.Tensor, N: int, K: int, bits: int) -> torch.Tensor:

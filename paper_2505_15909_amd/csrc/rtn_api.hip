@@ -5,6 +5,7 @@
 #include <vector>
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 
 #include <stdlib.h>
 #include <string.h>
@@ -426,6 +427,30 @@ rtn_status resolve_plan(const LinearArgs& a, const rtn_linear_cfg* cfg, size_t w
     return RTN_OK;
 }
 
+// ---- split-K partial sums for the entry point that allocates nothing ----------------------------------------------
+// A fixed device array takes the place of the caller's workspace.  Every GPU the library runs on holds its own copy
+// (at its own address) until the process ends.  In host code the array's name is only a handle for the runtime: the
+// device address is looked up once per device, with that device current, and kept; kernels and everything else
+// only ever see that address.
+constexpr size_t kScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+rtn_status scratch_for_current_device(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return RTN_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return RTN_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return RTN_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -560,6 +585,21 @@ rtn_status rtn_linear_validate(int64_t M, int64_t N, int64_t K, int bits, int gr
     a.M = M; a.N = N; a.K = K; a.g = g; a.bits = bits;
     LinearPlan p;
     return resolve_plan(a, cfg, workspace_nbytes, &p);
+}
+
+rtn_status rtn_linear_noalloc(const void* dev_A, int64_t M, const void* dev_qweight, const void* dev_scales,
+                              int64_t N, int64_t K, int bits, int group_size, void* dev_C, void* stream) {
+    if (!dev_A || !dev_qweight || !dev_scales || !dev_C) return RTN_ERR_NULL;
+    int64_t g;
+    rtn_status st = check_problem(N, K, bits, group_size, &g);
+    if (st != RTN_OK) return st;
+    if (M <= 0 || M > (1 << 20)) return RTN_ERR_SHAPE;
+    if (rtn_workspace_nbytes(M, N, K, bits, group_size) > kScratchBytes) return RTN_ERR_WORKSPACE;
+    void* ptr = nullptr;
+    st = scratch_for_current_device(&ptr);
+    if (st != RTN_OK) return st;
+    return rtn_linear_ex(dev_A, M, dev_qweight, dev_scales, N, K, bits, group_size, dev_C, ptr, kScratchBytes, stream,
+                         nullptr);
 }
 
 rtn_status rtn_linear_query(int64_t M, int64_t N, int64_t K, int bits, int group_size, rtn_linear_cfg* out) {
