@@ -232,7 +232,7 @@ rtn_status rtn_layer_forward(const rtn_module* mods, int n_mods, void* dev_works
  * subtracted from the result of Int()).  The paper gives no more than that; this library
  * takes, per group of g columns of a row:
  *   [alpha, beta] = [min(min w, 0), max(max w, 0)]      (zero is always a level)
- *   S = fp16((beta - alpha) / (2^b - 1)), difference and quotient rounded to fp32 first
+ *   S = fp16((beta - alpha) / (2^b - 1)), the exact quotient rounded once (as for the symmetric scale)
  *   Z = clamp(rne(alpha / S), -(2^b - 1), 0) + 2^(b-1)  (alpha goes to the lowest code)
  *   q = clamp(rne(w / S) - Z, -2^(b-1), 2^(b-1) - 1)    (ties on w / S, before Z)
  * and the dequantised weight is S * (q + Z).  S == 0 gives Z = 2^(b-1), q = -2^(b-1).

@@ -15,8 +15,8 @@ what the paper's method computes:
 * ``rtn_dequantize`` / ``rtn_linear`` -- the weight-only W4A16 / W8A16 linear layer
   of Section 2.3 and Section 5: C = A (q * S)^T, as a float64 GEMM on the
   dequantised weights.
-* ``pack_gfx950``                    -- the byte image of the packed weights ("the
-  specific interleaved data layout", Section 5) for this library's gfx950 layout,
+* ``pack_gfx950``                    -- the byte image of the packed weights (Section 5:
+  the kernel wants its own interleaved layout) for this library's gfx950 layout,
   written from the layout's written specification, so packed bytes can be compared.
 * ``plan_bits`` / ``effective_bits`` -- the selective-precision bookkeeping of
   Section 4 (horizontal, vertical, hybrid selection).
@@ -40,9 +40,8 @@ R7  Groups run along the input dimension K of each output row.
 R8  Asymmetric variant (Section 2.2 only says that it subtracts an integer zero point Z
     from the result of Int()).  Taken here: the group's range [alpha, beta] =
     [min(min r, 0), max(max r, 0)] always contains zero, so that zero is reproduced
-    exactly and Z fits the code range; S = fp16 of (beta - alpha) / (2^b - 1) with the
-    difference and the quotient each rounded to fp32 first (the precision the kernel
-    computes the scale in -- the difference of two fp16 values need not fit fp32);
+    exactly and Z fits the code range; S = fp16 of the exact (beta - alpha) / (2^b - 1),
+    rounded once, as R4 has it for the symmetric scale;
     Z = clamp(rne(alpha / S), -(2^b - 1), 0) + 2^(b-1), which sends alpha to the lowest
     code; q = clamp(rne(r / S) - Z) (the tie rule applies to r / S, before Z is
     subtracted); dequantised value S * (q + Z).  S == 0: Z = 2^(b-1), q = -2^(b-1),
@@ -155,6 +154,7 @@ def rtn_quantize_asym(W: np.ndarray, bits: int, group_size: int):
     W: fp16 [N, K].  Returns (codes int8 [N, K], scales fp16 [N, K // g], zeros int16 [N, K // g])
     with dequantised weights S * (q + Z).
 
+    S is the exact quotient (beta - alpha) / (2^b - 1) rounded once to fp16 (argument next to the computation).
     alpha / S and w / S are exact real quotients rounded once to an integer: as in the
     symmetric case both operands carry 11-bit significands, so the float64 quotient is
     either an exact tie or far from one, and np.rint rounds the exact quotient half to even.
@@ -173,11 +173,12 @@ def rtn_quantize_asym(W: np.ndarray, bits: int, group_size: int):
     Wg = W.reshape(N, K // g, g)
     alpha = np.minimum(Wg.min(axis=2), np.float16(0))            # fp16, <= 0
     beta = np.maximum(Wg.max(axis=2), np.float16(0))             # fp16, >= 0
-    with np.errstate(over="ignore"):                             # a range beyond fp16 gives an infinite scale: rejected below
-        width = beta.astype(np.float32) - alpha.astype(np.float32)   # one fp32 rounding
-        scales = (width / np.float32(levels)).astype(np.float16)     # fp32 quotient, then fp16
-    if not np.all(np.isfinite(scales)):
-        raise ValueError("group range overflows the fp16 scale")
+    # beta - alpha is exact in float64 (two fp16 values span at most 41 bits).  The float64 quotient is within 2^-53
+    # relative of the exact one, and an exact quotient that is not itself a midpoint between two fp16 values is at least
+    # 2^-42 relative away from every such midpoint (beta - alpha and midpoint * (2^b - 1) are both multiples of 2^-25,
+    # and beta - alpha < 2^18), so rounding the float64 quotient to fp16 is the single rounding of the exact quotient.
+    width = beta.astype(np.float64) - alpha.astype(np.float64)
+    scales = (width / np.float64(levels)).astype(np.float16)     # at most 131008 / 15: always finite
     s64 = scales.astype(np.float64)
     with np.errstate(divide="ignore", invalid="ignore"):
         t = np.rint(alpha.astype(np.float64) / s64)              # code of alpha before the shift, <= 0
@@ -230,8 +231,8 @@ def rtn_linear_bruteforce(A, codes, scales, group_size):
 
 
 # --------------------------------------------------------------------------------------
-# Packed byte image (Section 5: the kernel "expects a specific interleaved data layout";
-# weights are reshuffled once at load).  Written from the layout's specification:
+# Packed byte image (Section 5: the kernel wants its own interleaved layout, and the
+# weights are reshuffled into it once at load).  Written from the layout's specification:
 #
 #   The code matrix is cut into tiles of 16 output rows x TK input columns, TK = 128 for
 #   4-bit and 64 for 8-bit; a tile is 1024 bytes; tiles are stored row-tile-major

@@ -401,7 +401,7 @@ hipError_t launch_quantize(const void* W, int64_t N, int64_t K, int bits, int64_
 // ---------------------------------------------------------------------------------------
 // Asymmetric variant (the remark after Eq. 1 in Section 2.2: an integer zero point Z is subtracted from the
 // result of Int()).  Per group: [alpha, beta] = [min(min w, 0), max(max w, 0)];
-//   S = fp16( fp32_div( fp32(beta - alpha), 2^b - 1 ) )
+//   S = fp16( (beta - alpha) / (2^b - 1) ), the exact quotient rounded once (exact_quotient_fp16 below)
 //   T = clamp( rint( fp32_div(alpha, S) ), -(2^b - 1), 0 ),   Z = T + 2^(b-1)   (stored as fp16, an exact integer)
 //   stored code u = clamp( rint(w / S) - T, 0, 2^b - 1 )      (= q + 2^(b-1) with q = clamp(rint(w / S) - Z))
 // and the dequantised weight is S (q + Z) = S (u + T).  rint(w / S) comes from the same two-step rounding as in the
@@ -441,12 +441,24 @@ __device__ __forceinline__ void row_range(uint32_t mn2, uint32_t mx2, float* alp
     *beta = hi;
 }
 
+// fp16(x / d), the exact quotient rounded once (x = beta - alpha: a difference of two fp16 values, exact in fp64 but
+// not in fp32; d = 2^b - 1).  The IEEE fp64 quotient differs from the exact one by at most 2^-53 relative, while an
+// exact quotient that is not itself an fp16 midpoint lies at least 2^-42 relative from any (x and midpoint * d are
+// both multiples of 2^-25 and x < 2^18), so rounding the fp64 quotient to fp16 equals rounding the exact one.  fp64 ->
+// fp16 in one rounding: truncate to fp32 and set the last bit if anything was cut off (round to odd, 24 bits >= 11 +
+// 2), then the hardware's fp32 -> fp16 round-to-nearest-even.
+__device__ __forceinline__ half_t exact_quotient_fp16(double x, double d) {
+    const double q = x / d;                                          // IEEE fp64 division
+    float f = __double2float_rz(q);
+    if ((double)f != q) f = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, f) | 1u);
+    return (half_t)f;
+}
+
 template <int BITS>
 __device__ __forceinline__ AsymGroup asym_group(float alpha, float beta, half_t* s_out, half_t* z_out) {
     constexpr float LEVELS = (float)((1 << BITS) - 1);
     constexpr float C = 1536.0f;
-    const float width = beta - alpha;                                // one fp32 rounding
-    const half_t s16 = (half_t)(width / LEVELS);                     // IEEE divide, then fp16 RNE
+    const half_t s16 = exact_quotient_fp16((double)beta - (double)alpha, (double)LEVELS);
     const float s = (float)s16;
     float t = (s == 0.0f) ? 0.0f : rintf(alpha / s);                 // IEEE divide
     t = fminf(fmaxf(t, -LEVELS), 0.0f);

@@ -10,7 +10,7 @@ Run:  python tests/golden/derive_worked_examples.py  > tests/golden/rtn_worked_e
 
 The second form derives examples of the asymmetric variant (the remark after Eq. 1: an integer zero point is subtracted
 from the result of Int()) under this library's reading: range [alpha, beta] = [min(min w, 0), max(max w, 0)];
-S = fp16(fp32(fp32(beta - alpha) / (2^b - 1))); Z = clamp(rne(alpha / S), -(2^b - 1), 0) + 2^(b-1);
+S = fp16((beta - alpha) / (2^b - 1)), the exact quotient rounded once; Z = clamp(rne(alpha / S), -(2^b - 1), 0) + 2^(b-1);
 q = clamp(rne(w / S) - Z); all-zero scale: Z = 2^(b-1), q = -2^(b-1).
 """
 from fractions import Fraction as F
@@ -71,24 +71,13 @@ def example(name, decimals, bits, divisor: F):
           f"scale_bits=0x{sb:04X} q={','.join(str(v) for v in q)}")
 
 
-def round_to_fp32(x: F) -> F:
-    """Round-to-nearest-even of a non-negative rational to fp32 (24 significant bits, smallest quantum 2^-149)."""
-    if x == 0:
-        return F(0)
-    e = x.numerator.bit_length() - x.denominator.bit_length()
-    if F(2) ** e > x:
-        e -= 1
-    quantum = F(2) ** max(e - 23, -149)
-    return rne_int(x / quantum) * quantum
-
-
 def example_asym(name, decimals, bits):
     wb = [decimal_to_half_bits(d) for d in decimals]
     w = [half_bits_to_fraction(h) for h in wb]
     levels = (1 << bits) - 1
     lo, hi = -(1 << (bits - 1)), (1 << (bits - 1)) - 1
     alpha, beta = min(min(w), F(0)), max(max(w), F(0))
-    sb = round_to_half_bits(round_to_fp32(round_to_fp32(beta - alpha) / levels))
+    sb = round_to_half_bits((beta - alpha) / levels)
     s = half_bits_to_fraction(sb)
     t = 0 if s == 0 else max(-levels, min(0, rne_int(alpha / s)))
     z = t - lo
@@ -110,6 +99,9 @@ def main_asym():
     example_asym("zeros4", ["0", "-0", "0", "0"], 4)
     example_asym("tiny4", ["0.00000005960464477539", "0.00000011920928955078", "-0.00000023841857910156", "0"], 4)
     example_asym("wide_range8", ["60000", "-60000", "1", "-1", "30000.5", "0.25", "-12345", "7"], 8)
+    # ranges whose width needs more than 24 bits: a difference or quotient first rounded to fp32 gives another scale
+    example_asym("single_rounding4", ["1.6328125", "-0.000030457973480224609375", "0.5", "0"], 4)
+    example_asym("single_rounding8", ["3.23046875", "-0.000026762485504150390625", "1.25", "0"], 8)
 
 
 if __name__ == "__main__":

@@ -706,7 +706,7 @@ def test_asym_quantize_bit_exact(rtn, bits, g, N, K, shift):
 @pytest.mark.parametrize("bits,g", [(4, 128), (8, 64), (4, 32), (8, 32), (4, 512)])
 def test_asym_quantize_adversarial(rtn, bits, g):
     """One-sided groups, all-zero groups, constant groups, exact ties with odd and even shifts, subnormal scales,
-    the largest fp16 range, and a range whose width does not fit fp32."""
+    the largest fp16 range, and a range whose width does not fit fp32 (the scale is still the exact quotient rounded once)."""
     N, K = 64, 1024
     rng = np.random.default_rng(23)
     W = (rng.standard_normal((N, K)) * 0.02 + 0.004).astype(np.float16)
@@ -728,7 +728,7 @@ def test_asym_quantize_adversarial(rtn, bits, g):
         W[r, :g] = (rng.integers(-a // 3, a + 1, size=g) * 2.0 ** -24).astype(np.float16)
         W[r, 0] = np.float16(a * 2.0 ** -24)
         W[r, 1] = np.float16(-(a // 3) * 2.0 ** -24)
-    hb, ha = {4: (16008, 33279), 8: (17014, 33217)}[bits]          # fp32 rounding of beta - alpha moves the scale
+    hb, ha = {4: (16008, 33279), 8: (17014, 33217)}[bits]          # an fp32 intermediate would move the scale: the kernel must round the exact quotient once
     W[36, :g] = 0
     W[36, 0] = np.array([hb], dtype=np.uint16).view(np.float16)[0]
     W[36, 1] = np.array([ha], dtype=np.uint16).view(np.float16)[0]

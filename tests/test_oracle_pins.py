@@ -345,21 +345,21 @@ def test_asym_matches_exact_rationals(bits):
     W[7, :g] = np.float16(1.0) + np.float16(2.0 ** -10) * np.arange(g)     # far from zero, narrow spread
     W[7, g] = np.float16(-2.0 ** -20) * np.float16(1.0 + 2.0 ** -10)     # beta - alpha does not fit fp32
     W[7, g + 1] = np.float16(1.0)
-    # a (beta, alpha) pair where rounding beta - alpha to fp32 moves the fp16 scale (found by search over fp16 pairs)
+    # a (beta, alpha) pair on which an fp32 intermediate (difference and quotient rounded to 24 bits first) would give
+    # a different fp16 scale than the single rounding of the exact quotient: a lower-precision shortcut fails here
     hb, ha = {4: (16008, 33279), 8: (17014, 33217)}[bits]
     W[5, g:] = 0
     W[5, g] = np.array([hb], dtype=np.uint16).view(np.float16)[0]
     W[5, g + 1] = np.array([ha], dtype=np.uint16).view(np.float16)[0]
     codes, scales, zeros = O.rtn_quantize_asym(W, bits, g)
     exact = (F(float(W[5, g])) - F(float(W[5, g + 1]))) / levels
-    assert _frac(scales[5, 1]) != _round_binary(exact, 11, -24)       # the fp32 steps are visible in this group
+    via_fp32 = _round_binary(_round_binary(_round_binary(F(float(W[5, g])) - F(float(W[5, g + 1])), 24, -149) / levels, 24, -149), 11, -24)
+    assert via_fp32 != _round_binary(exact, 11, -24)                  # the planted pair does tell the two apart
     for n in range(W.shape[0]):
         for j in range(2):
             grp = [_frac(v) for v in W[n, j * g:(j + 1) * g]]
             alpha, beta = min(min(grp), F(0)), max(max(grp), F(0))
-            width32 = _round_binary(beta - alpha, 24, -149)
-            s32 = _round_binary(width32 / levels, 24, -149)
-            s = _round_binary(s32, 11, -24)
+            s = _round_binary((beta - alpha) / levels, 11, -24)        # the exact quotient, rounded once
             assert _frac(scales[n, j]) == s, (n, j)
             t = 0 if s == 0 else max(-levels, min(0, _rne(alpha / s)))
             assert int(zeros[n, j]) == t - lo, (n, j)
