@@ -36,9 +36,21 @@ HBM_PEAK_GBS = 8000.0
 BATCHES = (1, 2, 4, 8, 16)
 BITS, GROUP = 4, 128
 CACHE_BYTES = 256e6
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# very command, scaled by a copy kernel of known size (FETCH_SIZE x 1.997, WRITE_SIZE x 1.000).
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 29034971   # profiles/skinny_mfma_llama8b_w4a16_hbm_traffic.txt
+# HBM bytes per launch of the dominant kernel come from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this very
+# command, scaled by a copy kernel of known size; the committed summary of those runs carries the figure on a line
+# "traffic_bytes_per_launch: <n>", which is read at run time (null if the summary is not there).
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "skinny_mfma_llama8b_w4a16_hbm_traffic.txt")
+W8_BATCHES = (1, 4, 16, 64)
+
+
+def _measured_traffic():
+    try:
+        for line in open(TRAFFIC_PROFILE):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(float(line.split(":", 1)[1].split()[0]))
+    except OSError:
+        pass
+    return None
 
 
 def _time_linear(rtn, torch, np, A, qws, sc, bits, g, cfg, ws, reps=3, graph=True):
@@ -79,6 +91,75 @@ def _time_linear(rtn, torch, np, A, qws, sc, bits, g, cfg, ws, reps=3, graph=Tru
     return float(np.median(ts))
 
 
+def _read_ceiling_us(rtn, torch, np, nbytes, pool, sink, kib_options=(4, 8, 16)):
+    """Microseconds a plain read kernel (rtn_bench_read_stream) takes per launch on nbytes, under the protocol of the
+    linear launches: HIP-graph replay of back-to-back launches that rotate over distinct regions of `pool` (>= 600 MB in
+    total, or the pool), median of 5 replays; the best of the KiB-per-wavefront settings tried."""
+    nbytes = (int(nbytes) + 1023) // 1024 * 1024
+    copies = max(1, min(int(pool.numel() // nbytes), max(2, int(np.ceil(600e6 / nbytes)))))
+    views = [pool[c * nbytes:(c + 1) * nbytes] for c in range(copies)]
+    reps = 3
+    best = None
+    for kib in kib_options:
+        def issue():
+            for _ in range(reps):
+                for v in views:
+                    rtn.rtn_bench_read_stream(v, nbytes, kib, sink)
+        issue()
+        torch.cuda.synchronize()
+        cg = torch.cuda.CUDAGraph()
+        st = torch.cuda.Stream()
+        with torch.cuda.stream(st):
+            with torch.cuda.graph(cg, stream=st):
+                issue()
+        cg.replay()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            cg.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e3 / (reps * copies))
+        t = float(np.median(ts))
+        best = t if best is None else min(best, t)
+    return best
+
+
+def _ceiling_pool(torch, dev):
+    pool = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    pool.fill_(1)
+    return pool, torch.zeros(16, dtype=torch.uint8, device=dev)
+
+
+def report_ceiling(args, rtn, synth, torch, np, dev) -> int:
+    """The read-stream ceiling: a plain 16-byte-per-lane read kernel timed on buffers of exactly the packed size (codes +
+    scales) of every matrix of every workload, and on 512 MB, under the same graph-replay protocol as the linear launches."""
+    pool, sink = _ceiling_pool(torch, dev)
+    print("# plain read kernel (rtn_bench_read_stream): us per launch, HIP-graph replay, launches rotate over >= 600 MB of a 1 GiB "
+          "buffer; best of 4 / 8 / 16 KiB per wavefront; sizes = packed codes + scales of each matrix")
+    t512 = _read_ceiling_us(rtn, torch, np, 512e6, pool, sink)
+    print(f"512 MB: {t512:8.2f} us  {512e6 / t512 / 1e3:7.0f} GB/s  {512e6 / t512 / 80e3:5.1f} % of 8 TB/s")
+    for fam, shapes in (("8b", synth.LLAMA_8B), ("70b", synth.LLAMA_70B), ("405b", synth.LLAMA_405B)):
+        for label, bits_of in (("int4 group 128", lambda n: 4), ("int8 per-channel", lambda n: 8),
+                               ("selective (o, down int8 per-channel; qkv, gate_up int4 group 128)", lambda n: 8 if n in ("o", "down") else 4)):
+            if label.startswith("selective") and fam != "405b":
+                continue
+            tot_b, tot_t = 0.0, 0.0
+            for name, (K, N) in shapes.items():
+                bits = bits_of(name)
+                nbytes = N * K * bits // 8 + (N * (K // 128) * 2 if bits == 4 else N * 2)
+                t = _read_ceiling_us(rtn, torch, np, nbytes, pool, sink)
+                tot_b += nbytes
+                tot_t += t
+                print(f"{fam:5s} {label:18.18s} {name:8s} {K:6d}->{N:6d}  {nbytes / 1e6:8.2f} MB  {t:8.2f} us  {nbytes / t / 1e3:7.0f} GB/s  "
+                      f"{nbytes / t / 80e3:5.1f} % of 8 TB/s", flush=True)
+            print(f"{fam:5s} {label}: layer set {tot_b / 1e6:.1f} MB in {tot_t:.2f} us = {tot_b / tot_t / 1e3:.0f} GB/s = "
+                  f"{tot_b / tot_t / 80e3:.1f} % of 8 TB/s: the ceiling of four dependent weight-streaming launches on these sizes", flush=True)
+    return 0
+
+
 def report(args, rtn, synth, torch, np, dev) -> int:
     """Per (matrix, M): launch time, weight-stream GB/s, % of the 8 TB/s HBM peak, useful TFLOP/s; and per layer set."""
     shapes = {"8b": synth.LLAMA_8B, "70b": synth.LLAMA_70B, "405b": synth.LLAMA_405B}[args.report]
@@ -87,6 +168,8 @@ def report(args, rtn, synth, torch, np, dev) -> int:
     ws = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
     tot = {M: 0.0 for M in Ms}
     totb = 0
+    ceil_t = 0.0
+    pool, sink = _ceiling_pool(torch, dev)
     what = ("selective precision: qkv and gate_up int4 group 128, o and down int8 per-channel" if args.selective
             else f"int{args.bits} {'group 128' if args.bits == 4 else 'per-channel'}")
     print(f"# {args.report} shapes, {what}; launches rotate over >= 600 MB of "
@@ -99,6 +182,7 @@ def report(args, rtn, synth, torch, np, dev) -> int:
         del W
         nbytes = qw.numel() + sc.numel() * 2
         totb += nbytes
+        ceil_t += _read_ceiling_us(rtn, torch, np, nbytes, pool, sink)
         L = max(2, int(np.ceil(600e6 / nbytes)))
         qws = [qw] + [qw.clone() for _ in range(L - 1)]
         for M in Ms:
@@ -127,7 +211,7 @@ def report(args, rtn, synth, torch, np, dev) -> int:
         del qws, qw
     for M in Ms:
         print(f"layer set M={M:3d}: {tot[M]:8.2f} us  {totb / tot[M] / 1e3:7.0f} GB/s  {totb / tot[M] / 80e3:5.1f} % of 8 TB/s"
-              f"  ({totb / tot[M] / 70.5e3:5.1f} % of the 7.05 TB/s a plain read kernel reaches on this chip)")
+              f"  ({100.0 * ceil_t / tot[M]:5.1f} % of what a plain read kernel reaches on buffers of these four sizes: {ceil_t:.2f} us)")
     return 0
 
 
@@ -325,6 +409,8 @@ def main() -> int:
                     help="instead of the JSON line, time the load-time pipeline from pinned host memory per matrix")
     ap.add_argument("--report-crossover", choices=["8b", "70b", "405b"], default=None,
                     help="instead of the JSON line, print fused kernels vs dequantise + dense GEMM over --batches")
+    ap.add_argument("--report-ceiling", action="store_true",
+                    help="instead of the JSON line, time a plain read kernel on buffers of every workload matrix's packed size and on 512 MB")
     ap.add_argument("--report-grouped", action="store_true",
                     help="instead of the JSON line, time expert-like independent modules serially and through the grouped call")
     ap.add_argument("--bits", type=int, default=4, help="--report only: 4 (group 128) or 8 (per-channel)")
@@ -358,6 +444,8 @@ def main() -> int:
         return report_load(args, rtn, synth, torch, np, dev)
     if args.report_grouped:
         return report_grouped(args, rtn, synth, torch, np, dev)
+    if args.report_ceiling:
+        return report_ceiling(args, rtn, synth, torch, np, dev)
     modules = list(synth.LLAMA_8B.items())
 
     # ---- set-up: synthetic fp16 weights, load-time quantise (timed separately) ---------------
@@ -476,10 +564,40 @@ def main() -> int:
     del hold
     achieved = algo_bytes / n_launch / (launch_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": _measured_traffic(),
                 "kernel": "rtn::skinny_mfma_kernel<4,4,1,*,1> (fused int4 g128 dequantise-GEMM; a launch = one rtn_linear)",
                 "launches": n_launch, "avg_launch_us": round(launch_us, 3),
                 "algorithmic_bytes_per_launch": round(algo_bytes / n_launch, 1)}
+
+    # ---- read-stream ceiling: a plain read kernel on buffers of the four matrices' packed sizes, same protocol ----
+    pool, sink = _ceiling_pool(torch, dev)
+    ceil_us = [_read_ceiling_us(rtn, torch, np, q.numel() + s.numel() * 2, pool, sink) for q, s in packed]
+    t512 = _read_ceiling_us(rtn, torch, np, 512e6, pool, sink)
+    del pool
+    read_ceiling_gbs = layer_bytes / sum(ceil_us) / 1e3
+    roofline["read_ceiling"] = {"layer_set_GB/s": round(read_ceiling_gbs, 1), "layer_set_us": round(sum(ceil_us), 2),
+                                "per_matrix_us": [round(t, 2) for t in ceil_us], "stream_512MB_GB/s": round(512e6 / t512 / 1e3, 1),
+                                "kernel": "rtn::read_stream_kernel (16 bytes per lane, nothing else), graph replay, rotating buffers"}
+
+    # ---- the other precision the metric names: the same layer at W8A16 (int8, per-channel scales), M = 1, 4, 16, 64 ----
+    w8 = {}
+    w8_layer_bytes = 0
+    w8_times = {M: 0.0 for M in W8_BATCHES}
+    ws_big = torch.empty(64 << 20, dtype=torch.uint8, device=dev)
+    for i, (name, (K, N)) in enumerate(modules):
+        w = synth.normal_weight(N, K, 0.02, seed=i, device=dev)
+        q8, s8 = rtn.rtn_quantize(w, 8, 0)
+        del w
+        nb8 = q8.numel() + s8.numel() * 2
+        w8_layer_bytes += nb8
+        q8s = [q8] + [q8.clone() for _ in range(max(2, int(np.ceil(600e6 / nb8))) - 1)]
+        for M in W8_BATCHES:
+            A8 = synth.activation(M, K, seed=100 + M, device=dev)
+            w8_times[M] += _time_linear(rtn, torch, np, A8, q8s, s8, 8, 0, None, ws_big)
+        del q8s, q8
+    for M in W8_BATCHES:
+        w8[f"M{M}"] = {"layer_set_us": round(w8_times[M], 2), "GB/s": round(w8_layer_bytes / w8_times[M] / 1e3, 1),
+                       "pct_hbm_peak": round(w8_layer_bytes / w8_times[M] / 80e3, 2)}
 
     # ---- CPU oracle timed beside it (bounded sample of the same workload) ------------------------
     cpu = None
@@ -521,6 +639,11 @@ def main() -> int:
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "tflops": round(flops / (ms_per_step * 1e-3) / 1e12, 3),
         "weight_bytes_per_step": int(step_weight_bytes),
+        "read_ceiling_gbs": round(read_ceiling_gbs, 1),
+        "value_over_read_ceiling": round(value / read_ceiling_gbs, 4),
+        "extra": {"w8a16_llama8b_int8_per_channel_layer_set": w8,
+                  "w8a16_note": "same four modules, symmetric RTN int8 with per-output-channel scales; per-matrix HIP-graph replay over "
+                                ">= 600 MB of rotating packed copies, layer set = sum of the four"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "quantize": {"GB/s": round(q_bytes / (q_ms * 1e-3) / 1e9, 1), "ms_per_layer": round(q_ms, 4),

@@ -266,6 +266,14 @@ rtn_status rtn_linear_asym(const void* dev_A, int64_t M, const void* dev_qweight
 rtn_status rtn_grouped_forward(const rtn_module* mods, int n_mods, void* dev_workspace,
                                size_t workspace_nbytes, void* stream);
 
+/* Measurement hook (Section 1: token generation is bound by the weight bytes that must be read): a plain read
+ * kernel that streams dev_buf once, 16 bytes per lane and load, kib_per_wavefront (1..64) consecutive KiB per
+ * wavefront, and computes nothing.  Its time on a buffer the size of a packed weight matrix is the read-stream ceiling
+ * that the fused kernels are reported against, beside the published HBM peak.  nbytes a multiple of 1024; dev_buf
+ * 16-byte aligned; dev_sink: 4 bytes of device memory (never written for any real data). */
+rtn_status rtn_bench_read_stream(const void* dev_buf, size_t nbytes, int kib_per_wavefront, void* dev_sink,
+                                 void* stream);
+
 /* Hybrid selection rule of Section 4.3: bits of module `module_id` (1 = QKV projection,
  * 2 = attention output projection, 3 and 4 = feed-forward, numbering of Section 4.2) of
  * 0-based `layer` when X layers chosen by `policy` (first / last / middle, Section 4.1)

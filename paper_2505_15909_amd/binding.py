@@ -88,6 +88,8 @@ def _load() -> C.CDLL:
     lib.rtn_linear_validate.argtypes = [i64, i64, i64, ci, ci, sz, C.POINTER(rtn_linear_cfg)]
     lib.rtn_linear_noalloc.restype = ci
     lib.rtn_linear_noalloc.argtypes = [vp, i64, vp, vp, i64, i64, ci, ci, vp, vp]
+    lib.rtn_bench_read_stream.restype = ci
+    lib.rtn_bench_read_stream.argtypes = [vp, sz, ci, vp, vp]
     lib.rtn_plan_bits.restype = ci
     lib.rtn_plan_bits.argtypes = [ci, ci, ci, ci, ci, C.c_uint]
     lib.rtn_plan_effective_bits.restype = C.c_double
@@ -100,7 +102,7 @@ EXPORTS = ["rtn_status_str", "rtn_layout_version", "rtn_qweight_nbytes", "rtn_sc
            "rtn_workspace_nbytes", "rtn_quantize", "rtn_quantize_host_staging_nbytes", "rtn_quantize_from_host", "rtn_linear", "rtn_linear_ex", "rtn_linear_query",
            "rtn_problem_status", "rtn_linear_validate", "rtn_linear_noalloc", "rtn_unpack", "rtn_dequantize", "rtn_gemm_fp16", "rtn_dense_weight_nbytes", "rtn_linear_dense",
            "rtn_quantize_asym", "rtn_dequantize_asym", "rtn_linear_asym",
-           "rtn_layer_forward", "rtn_grouped_forward", "rtn_plan_bits", "rtn_plan_effective_bits"]
+           "rtn_layer_forward", "rtn_grouped_forward", "rtn_bench_read_stream", "rtn_plan_bits", "rtn_plan_effective_bits"]
 
 
 def _check(status: int, what: str):
@@ -208,6 +210,12 @@ def rtn_linear_noalloc(A: torch.Tensor, qweight: torch.Tensor, scales: torch.Ten
     _check(_lib.rtn_linear_noalloc(A.data_ptr(), M, qweight.data_ptr(), scales.data_ptr(), N, K, bits, group_size,
                                    out.data_ptr(), _stream()), "rtn_linear_noalloc")
     return out
+
+
+def rtn_bench_read_stream(buf: torch.Tensor, nbytes: int, kib_per_wavefront: int, sink: torch.Tensor):
+    """Measurement hook: streams the first nbytes of buf once with a plain read kernel."""
+    _check(_lib.rtn_bench_read_stream(buf.data_ptr(), nbytes, kib_per_wavefront, sink.data_ptr(), _stream()),
+           "rtn_bench_read_stream")
 
 
 def rtn_unpack(qweight: torch.Tensor, N: int, K: int, bits: int) -> torch.Tensor:

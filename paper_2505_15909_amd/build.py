@@ -7,7 +7,7 @@ import subprocess
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "librtn_gfx950.so")
-SOURCES = ["rtn_api.hip", "rtn_quantize.hip", "rtn_linear.hip", "rtn_linear_wide.hip", "rtn_gemm_tile.hip"]
+SOURCES = ["rtn_api.hip", "rtn_quantize.hip", "rtn_linear.hip", "rtn_linear_wide.hip", "rtn_gemm_tile.hip", "rtn_bench.hip"]
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
     # no packed-fp32 instruction selection: some packed fp32 forms have given wrong results on this platform

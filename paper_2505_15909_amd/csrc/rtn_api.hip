@@ -456,7 +456,7 @@ rtn_status scratch_for_current_device(void** out) {
 extern "C" {
 
 const char* rtn_status_str(rtn_status s) {
-    switch (s) {
+    switch (static_cast<int>(s)) {             // callers from C or a foreign-function interface may pass any integer
         case RTN_OK: return "ok";
         case RTN_ERR_NULL: return "null pointer";
         case RTN_ERR_BITS: return "bits must be 4 or 8";
@@ -607,7 +607,9 @@ rtn_status rtn_linear_query(int64_t M, int64_t N, int64_t K, int bits, int group
     int64_t g;
     rtn_status st = check_problem(N, K, bits, group_size, &g);
     if (st != RTN_OK) return st;
-    if (M <= 0) return RTN_ERR_SHAPE;
+    if (M <= 0 || M > (1 << 20)) return RTN_ERR_SHAPE;
+    if ((uint64_t)N * K * bits / 8 >= 0x7FFF0000ull || (uint64_t)M * K * 2 >= 0x7FFF0000ull)
+        return RTN_ERR_SHAPE;                                   // what rtn_linear refuses (32-bit buffer offsets)
     LinearPlan p = auto_plan(M, N, K, bits, g, (size_t)device_max_lds());
     out->path = p.path; out->prefetch = p.prefetch; out->waves_n = p.waves_n;
     out->waves_k = p.waves_k; out->split_k = p.split_k; out->m_rows16 = p.m_rows16;

@@ -506,14 +506,16 @@ def test_linear_automatic_plans_on_large_random_shapes(rtn):
 
 
 # ----------------------------------------------------------------------------------------
-# the paper-shaped configurations at full size (rows of the weight matrix are independent, so the
-# oracle checks a stripe of 16-row tiles; the GPU runs the full shape in its default configuration)
+# the paper-shaped configurations at full size: the 8B-shaped ones are compared against the oracle in full; for the
+# larger ones the oracle checks a stripe of 16-row tiles (rows of the weight matrix are independent); the GPU always
+# runs the full shape in its default configuration
 # ----------------------------------------------------------------------------------------
 FULL = [
     # name, dist, bits, g, modules, Ms, stripe tiles
-    ("single_4096", "normal02", 4, 128, {"o": (4096, 4096)}, (1,), 256),
-    ("llama8b_w4", "normal02", 4, 128, synth.LLAMA_8B, (1, 2, 4, 8, 16), 24),
-    ("llama8b_w8", "normal02", 8, 0, synth.LLAMA_8B, (1, 4, 16, 64), 24),
+    # (the 8B-shaped configurations are compared in full: every tile-row of every matrix)
+    ("single_4096", "normal02", 4, 128, {"o": (4096, 4096)}, (1,), 1 << 30),
+    ("llama8b_w4", "normal02", 4, 128, synth.LLAMA_8B, (1, 2, 4, 8, 16), 1 << 30),
+    ("llama8b_w8", "normal02", 8, 0, synth.LLAMA_8B, (1, 4, 16, 64), 1 << 30),
     ("llama70b_w4", "heavy", 4, 128, synth.LLAMA_70B, (1, 8, 32, 64, 128, 256, 512, 768), 12),
 ]
 
@@ -537,8 +539,10 @@ def test_full_size_quantize_and_linear(rtn, case):
             C = rtn.rtn_linear(A_t, qw, sc, bits, g)
             torch.cuda.synchronize()
             ref = O.rtn_linear(_to_np(A_t), codes, scales, gg)
-            H.assert_linear_close(_to_np(C)[:, rows], ref, f"{name} {mod} M={M}")
-            print(f"{name} {mod} M={M} ok", flush=True)
+            allow = "llama70b_down" if (name, mod) == ("llama70b_w4", "down") else None
+            fro, mx = H.assert_linear_close(_to_np(C)[:, rows], ref, f"{name} {mod} M={M}", allow=allow)
+            print(f"{name} {mod} M={M}: {len(rows)} of {N} output columns compared, rel Frobenius {fro:.2e}, max abs {mx:.2e}, "
+                  f"|C_ref| up to {float(np.max(np.abs(ref))):.1f}{' (fp16-output allowance)' if allow else ''}", flush=True)
 
 
 @pytest.mark.parametrize("M", [512, 1500])

@@ -64,7 +64,8 @@ def test_eq2_identity():
 
 @pytest.mark.parametrize("bits,rule", [(4, "qmax"), (8, "qmax"), (4, "eq2"), (8, "eq2")])
 def test_scale_is_single_rounding_of_exact_quotient_all_fp16(bits, rule):
-    """Every positive finite fp16 amax: stored scale == RNE_fp16(exact amax / D)."""
+    """Stored scale == RNE_fp16(exact amax / D) with exact rationals, on all 2048 smallest fp16 values and every 7th
+    above them (the exhaustive check of all 31 743 values, in integer arithmetic, is in tests/test_exhaustive_pins.py)."""
     D = F(O.scale_divisor(bits, rule))
     halves = np.arange(1, 0x7C00, dtype=np.uint16).view(np.float16)
     got = O.rtn_scale(halves, bits, rule).view(np.uint16)
