@@ -18,6 +18,7 @@ def test_planning_and_validation_are_clean_under_asan_and_ubsan(tmp_path):
     objs = [os.path.join(PKG, "_build", f) for f in ("rtn_quantize.o", "rtn_linear.o", "rtn_linear_wide.o", "rtn_gemm_tile.o", "rtn_bench.o")]
     if not all(os.path.exists(o) for o in objs):
         pytest.skip("library objects not built (run __graft_entry__.build() first)")
+    # sanitizers on the host pass only: every -fsanitize= option directly follows -Xarch_host
     san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=undefined",
            "-Xarch_host", "-fno-omit-frame-pointer"]
     common = ["-O1", "-g", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -26,10 +27,9 @@ def test_planning_and_validation_are_clean_under_asan_and_ubsan(tmp_path):
     exe = str(tmp_path / "plan_sanitize_driver")
     subprocess.run([hipcc, *common, *san, "-c", "-o", api_o, os.path.join(PKG, "csrc", "rtn_api.hip")], check=True, cwd=os.path.join(PKG, "csrc"),
                    capture_output=True, timeout=600)
-    subprocess.run([hipcc, "-O1", "-g", "-std=c++17", "-x", "c++", "-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined",
-                    "-c", "-o", drv_o, os.path.join(ROOT, "tests", "host", "plan_sanitize_driver.cpp")], check=True, capture_output=True, timeout=600)
-    subprocess.run([hipcc, "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-o", exe, drv_o, api_o, *objs], check=True,
-                   capture_output=True, timeout=600)
+    subprocess.run([hipcc, *common, *san, "-x", "hip", "-c", "-o", drv_o, os.path.join(ROOT, "tests", "host", "plan_sanitize_driver.cpp")],
+                   check=True, capture_output=True, timeout=600)
+    subprocess.run([hipcc, "--offload-arch=gfx950", *san, "-o", exe, drv_o, api_o, *objs], check=True, capture_output=True, timeout=600)
     env = dict(os.environ)
     # leaks are not what is tested here (the HIP runtime keeps its own allocations until exit); everything else aborts;
     # a library preloaded ahead of the sanitizer runtime is tolerated
