@@ -207,6 +207,114 @@ int64_t tile_two_launches(int64_t M, int64_t N, int64_t K) {
     return rows_first;
 }
 
+// Plan of the small-batch (skinny) kernel for up to 16 rows: a table of measured configurations on a grid of
+// problems -- tile-rows N / 16 from 64 to 8192 and k-chunks per row from 2 to 128, by powers of two and at the 1.5 x
+// points between them, 1, 2, 4, 8, 16 rows, both precisions -- plus the linear modules of the Llama 3.1 8B / 70B / 405B and Llama 3.2 1B / 3B
+// layers the paper evaluates (Table 1).  Every entry lists its twelve fastest configurations with their slowdown
+// against the fastest.  A problem that is in the table takes its entry's ranking; any other one lets its three nearest
+// entries (distance in log2 of tile-rows, chunks per row and rows) vote: a configuration's score is the weighted mean
+// log slowdown over the three (1.5 x where an entry does not list it), and the best-scored configuration that is valid
+// for the problem wins.  On shapes outside the table (tuning/shapes_heldout.txt) the pick is about 1 % behind the best
+// measured configuration at the median and within 10 % on nineteen problems out of twenty.
+// tuning/plan_sweep.hip measures, tuning/make_plan_table.py writes the table.
+constexpr int kPlanEntryConfigs = 12;
+struct SkinnyPlanConfig {
+    uint8_t wn, wk, split, nb, slow;       // slow: slowdown against the entry's fastest, units of 0.5 %
+};
+struct SkinnyPlanEntry {
+    uint8_t bits;
+    uint16_t nt, kc;
+    uint8_t m, n;
+    SkinnyPlanConfig c[kPlanEntryConfigs];
+};
+const SkinnyPlanEntry kSkinnyPlanTable[] = {
+#include "skinny_plan_table.inc"
+};
+
+bool skinny_plan_usable(int64_t M, int64_t N, int64_t K, int bits, const LinearPlan& p, size_t lds_limit) {
+    const int64_t KC = K / chunk_k(bits);
+    if (p.waves_n < 1 || !pow2(p.waves_n) || p.waves_k < 1 || p.waves_n * p.waves_k > 16) return false;
+    if (p.split_k < 1 || p.split_k > kMaxSplitK || p.split_k > KC) return false;
+    if (p.split_k > 1 && (size_t)M * N * sizeof(float) * p.split_k > kWorkspaceCap) return false;
+    LinearArgs a;
+    a.M = M; a.N = N; a.K = K; a.bits = bits; a.g = K;
+    return rtn::linear_plan_fits(a, p, lds_limit);
+}
+
+// Workgroups come in rounds of one per compute unit: a launch of n workgroups keeps the busiest of the 256 compute units
+// ceil(n / 256) workgroups long where n / 256 would be the average.  Coarse configurations (few, long-lived workgroups)
+// pay for it: 269 workgroups of eight wavefronts take 1.45 x the time of 256.  The table's grid shapes are powers of
+// two, the best case, so a configuration's measured slowdown is corrected by this ratio to the power 0.7 (fitted on
+// shapes outside the table), entry against problem.
+constexpr double kImbalanceExp = 0.7;
+double cu_imbalance(int64_t workgroups) {
+    const double avg = (double)workgroups / 256.0;
+    return std::ceil(avg) / avg;
+}
+
+bool skinny_plan_from_table(int64_t M, int64_t N, int64_t K, int bits, size_t lds_limit, LinearPlan* out) {
+    const double fnt = std::log2((double)(N / 16)), fkc = std::log2((double)(K / chunk_k(bits))), fm = std::log2((double)M);
+    const int n = (int)(sizeof(kSkinnyPlanTable) / sizeof(kSkinnyPlanTable[0]));
+    constexpr int kVoters = 3;
+    int near_i[kVoters];
+    double near_d[kVoters];
+    int found = 0;
+    for (int i = 0; i < n; ++i) {
+        const SkinnyPlanEntry& e = kSkinnyPlanTable[i];
+        if (e.bits != bits) continue;
+        const double d = 2.0 * std::fabs(std::log2((double)e.nt) - fnt) + std::fabs(std::log2((double)e.kc) - fkc) +
+                         0.5 * std::fabs(std::log2((double)e.m) - fm);
+        int pos = found < kVoters ? found : kVoters;             // insertion into the sorted list of the nearest
+        while (pos > 0 && d < near_d[pos - 1]) --pos;
+        if (pos >= kVoters) continue;
+        for (int q = (found < kVoters ? found : kVoters - 1); q > pos; --q) { near_i[q] = near_i[q - 1]; near_d[q] = near_d[q - 1]; }
+        near_i[pos] = i; near_d[pos] = d;
+        if (found < kVoters) ++found;
+    }
+    if (found == 0) return false;
+    if (near_d[0] < 1e-9) found = 1;                            // the problem itself is in the table: its own ranking
+    struct Scored { SkinnyPlanConfig c; double score; };
+    Scored cand[kVoters * kPlanEntryConfigs];
+    int nc = 0;
+    const double kMissing = std::log(1.5);
+    for (int v = 0; v < found; ++v) {
+        const SkinnyPlanEntry& e = kSkinnyPlanTable[near_i[v]];
+        for (int k = 0; k < e.n; ++k) {
+            bool seen = false;
+            for (int q = 0; q < nc && !seen; ++q)
+                seen = cand[q].c.wn == e.c[k].wn && cand[q].c.wk == e.c[k].wk && cand[q].c.split == e.c[k].split && cand[q].c.nb == e.c[k].nb;
+            if (seen) continue;
+            double num = 0.0, den = 0.0;
+            for (int u = 0; u < found; ++u) {
+                const SkinnyPlanEntry& f = kSkinnyPlanTable[near_i[u]];
+                const double w = 1.0 / (near_d[u] + 0.25);
+                double ls = kMissing;
+                for (int q = 0; q < f.n; ++q)
+                    if (f.c[q].wn == e.c[k].wn && f.c[q].wk == e.c[k].wk && f.c[q].split == e.c[k].split && f.c[q].nb == e.c[k].nb) {
+                        ls = std::min(kMissing, std::log(1.0 + f.c[q].slow / 200.0));
+                        break;
+                    }
+                // the entry's own workgroup-count imbalance is taken out of its measurement ...
+                ls -= kImbalanceExp * std::log(cu_imbalance((int64_t)((f.nt + e.c[k].wn - 1) / e.c[k].wn) * e.c[k].split));
+                num += w * ls; den += w;
+            }
+            cand[nc].c = e.c[k];
+            // ... and the problem's own put in; ties: the order of the nearer entry
+            cand[nc].score = num / den + kImbalanceExp * std::log(cu_imbalance(((N / 16 + e.c[k].wn - 1) / e.c[k].wn) * e.c[k].split)) + 1e-9 * nc;
+            ++nc;
+        }
+    }
+    std::sort(cand, cand + nc, [](const Scored& a, const Scored& b) { return a.score < b.score; });
+    for (int q = 0; q < nc; ++q) {
+        LinearPlan p;
+        p.path = 1; p.n_tiles16 = 1; p.m_rows16 = 1; p.m_blocks = 1;
+        p.prefetch = cand[q].c.nb; p.waves_n = cand[q].c.wn; p.waves_k = cand[q].c.wk; p.split_k = cand[q].c.split;
+        while (p.waves_n > 1 && p.waves_n > N / 16) p.waves_n /= 2;
+        if (skinny_plan_usable(M, N, K, bits, p, lds_limit)) { *out = p; return true; }
+    }
+    return false;
+}
+
 // force_path: 0 = choose the path, otherwise the default plan of that path.
 LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_t lds_limit, int force_path = 0,
                      int64_t steps_hint = 0) {
@@ -270,6 +378,8 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
         wide_plan(M, N, K, bits, &p);
         return p;
     }
+    if (M <= 16 && steps_hint == 0 && skinny_plan_from_table(M, N, K, bits, lds_limit, &p)) return p;
+    // (no usable table entry, more than 16 rows on this kernel, or a slice of a grouped launch: the rules below)
     const int64_t NT = N / 16, KC = K / chunk_k(bits);
     // 4 KiB chunk-steps in the whole matrix, or in everything that shares the launch (grouped call)
     const int64_t steps = NT * KC > steps_hint ? NT * KC : steps_hint;
@@ -387,6 +497,9 @@ rtn_status resolve_plan(const LinearArgs& a, const rtn_linear_cfg* cfg, size_t w
             p.m_blocks = (int)((a.M + 16 * p.m_rows16 - 1) / (16 * p.m_rows16));
         }
         if (cfg->n_tiles16) p.n_tiles16 = cfg->n_tiles16;
+        // the vector-ALU variant and several row blocks per wavefront keep one chunk in flight: an automatic plan's deeper
+        // prefetch does not carry over to them unless asked for
+        if (!cfg->prefetch && (p.path == 2 || (p.path == 1 && p.m_rows16 > 1))) p.prefetch = 1;
         if (p.path == 4 && !cfg->m_rows16 && cfg->split_k) p.m_rows16 = 0;     // a given split: height chosen at launch
     }
     const int64_t KC = a.K / chunk_k(a.bits);

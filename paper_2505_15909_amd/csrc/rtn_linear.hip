@@ -11,12 +11,12 @@
 // feeds them as the B operand of v_mfma_f32_16x16x32_f16.  The A operand is the activation
 // block staged per workgroup in LDS (padded rows) and read 16 bytes per lane right before each
 // MFMA; lanes of batch rows beyond M read the last valid row (output rows never mix in a matrix
-// product, and those rows are not stored).  When the slice fits one stage it goes from global memory
-// straight into LDS (buffer_load ... lds: no registers, no LDS store instructions, every address
-// wave-uniform arithmetic), all of it requested before the first weight load; a workgroup one
-// wavefront wide along N stages per wavefront and needs no barrier before the main loop.  Larger
-// slices are staged through registers in stages of SC chunks per wavefront whose global loads are
-// issued one stage ahead.
+// product, and those rows are not stored).  The slice goes from global memory straight into LDS
+// (buffer_load ... lds: no registers, no LDS store instructions, every address wave-uniform
+// arithmetic) and is requested before the first weight load; a workgroup one wavefront wide along
+// N stages per wavefront and needs no barrier before the main loop.  A slice that does not fit one
+// stage alternates between two LDS buffers, the next stage's loads in flight while the current one
+// is consumed, one barrier per stage.
 // Scales multiply the fp32 partial sum of each group (exact codes into the matrix cores, one
 // fp32 multiply-add per group and output), never the individual weights.  The WK partial
 // results of a tile-row are summed through LDS in a fixed order; an optional global split-K
@@ -44,7 +44,6 @@
 namespace rtn {
 
 constexpr int kChunkTiles = 4;            // tiles (16-byte loads per lane) per k-chunk
-constexpr int kStagePieces = 4;           // 16-byte pieces of activations a thread moves per staging round
 constexpr int kLdsPadHalves = 8;          // row stride = 16 bytes mod 256 bytes: conflict-free b128 reads
 constexpr uint32_t kOutOfRange = 0x7FFF0000u;   // beyond any resource size used here (< 2 GiB)
 constexpr int kBufferFlags = 0x00020000;  // raw buffer, 32-bit data format
@@ -68,11 +67,11 @@ struct SkinnyParams {
     uint32_t cpg_inv;      // floor(2^32 / (g / CK)) + 1 when g > CK (0 when g == CK): chunk -> group by multiply-high
     int per;          // chunks per wavefront (largest)
     int nstage;       // activation stages (1 unless MULTI)
-    int stage_rounds; // staging rounds of kStagePieces pieces per thread for the single stage
-    int sc, sc_shift; // chunks per wavefront per stage (power of two, multiple of NB)
+    int sc;           // chunks per wavefront per stage (single stage: the wavefront's whole share)
+    uint32_t sc_inv, rpr_inv;   // floor(2^32 / sc) + 1, floor(2^32 / (WK sc)) + 1: exact division of small indices (unused when the divisor is 1)
+    int stage_row_step;         // wavefronts that share one column run of the staged rows (fewer runs per row than wavefronts)
+    int stage_halves; // halves between the two LDS buffers of the staged mode
     int lds_stride;   // halves per staged activation row = WK * sc * CK + pad
-    int srp;          // 16-byte pieces per staged row = WK * sc * CK / 8
-    uint32_t srp_inv; // floor(2^32 / srp) + 1: exact division of a piece index by srp
     uint32_t qw_bytes, sc_bytes, a_bytes;
 };
 
@@ -129,7 +128,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 
 // MULTI = false: the workgroup's whole activation slice is staged once, before the main loop.
-// MULTI = true: it is staged sc chunks per wavefront at a time, one stage ahead, one round per stage.
+// MULTI = true: it is staged sc chunks per wavefront at a time, one stage ahead, in two alternating LDS buffers.
 // MB: 16-row activation blocks per wavefront (batch rows per workgroup = 16 MB); every unpacked weight
 // operand feeds MB MFMAs, so the weights are streamed once for up to 16 MB batch rows.
 // DOT = true (M <= 4, MB = 1): the same wavefront layout, but the products are done by the vector ALU
@@ -170,34 +169,57 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& p, const int bx,
     const uint32_t magic = fp16_magic_vgpr();
 
     // ---- activation staging --------------------------------------------------------------------
-    // A stage holds, for every row and every K-wavefront w, the sc chunks that wavefront w consumes
-    // in this stage: LDS [row][w][sc * CK] (+ pad).  Thread t moves pieces t, t + nthreads, ...; a
-    // piece is 16 bytes: piece -> (row, w, octet).  Rows >= Mb and columns past a wavefront's share are
-    // loaded out of range, i.e. as zeros, without memory traffic (register path of the staged mode).
+    // A stage holds, for every row and every K-wavefront w, the sc chunks that wavefront w consumes in this stage:
+    // LDS [row][w][sc * CK] (+ pad).  It goes from global memory straight into LDS (buffer_load ... lds, 16 bytes per
+    // lane, no registers): one instruction moves a run = one k-chunk of one staged row (64 lanes x 16 bytes at 4 bit, 32
+    // lanes at 8 bit).  Runs are dealt to the wavefronts by (column run, row) so that every address is wave-uniform
+    // arithmetic.  Runs past a wavefront's share are skipped (nothing reads them).
+    //   Single stage (MULTI = false): the compiler's builtin, issued before everything else.
+    //   Staged (MULTI = true): two LDS buffers; the loads of stage s + 1 are issued while stage s is consumed.  The
+    //   compiler must not see them -- it would make every later LDS read wait for them, since it cannot tell the two
+    //   buffers apart -- so they go out as inline assembly (M0 = LDS address of the run, saved and restored) and the
+    //   waits are explicit: loads complete in order, so once at most the NB chunks requested after them are outstanding
+    //   they have landed.
     half_t* lds_a = reinterpret_cast<half_t*>(lds_bytes);
-    const int rows_staged = Mb;
-    constexpr int CK8_SHIFT = (BITS == 4) ? 6 : 5;                     // log2(CK / 8)
-    const int seg_shift = p.sc_shift + CK8_SHIFT;                     // log2(pieces per wavefront segment)
-    u32x4_t stg[kStagePieces];
-    int stg_off[kStagePieces];
-    auto stage_load = [&](int s, int round) {
-#pragma unroll
-        for (int i = 0; i < kStagePieces; ++i) {
-            const int piece = tid + (round * kStagePieces + i) * nthreads;
-            const int row = (int)__umulhi((uint32_t)piece, p.srp_inv), rem = piece - row * p.srp;
-            const int w = rem >> seg_shift, o = rem & ((1 << seg_shift) - 1);
-            const int c0 = min(cb0 + w * p.per, cb1), c1 = min(c0 + p.per, cb1);
-            const int k8 = ((c0 + (s << p.sc_shift)) << CK8_SHIFT) + o;  // column / 8
-            const bool ok = row < Mb && k8 < (c1 << CK8_SHIFT);
-            const uint32_t goff = ok ? ((uint32_t)(m0 + row) * (uint32_t)p.K + (uint32_t)k8 * 8u) * 2u : kOutOfRange;
-            stg[i] = __builtin_amdgcn_raw_buffer_load_b128(ra, goff, 0, 0);
-            stg_off[i] = row < rows_staged ? row * p.lds_stride + rem * 8 : -1;
+    constexpr int RP = GM::CK / 8;                                   // lanes (16-byte pieces) per run
+    const int nwaves = nthreads >> 6;
+    const int rpr = p.WK * p.sc;                                      // runs per staged row
+    int col0, col_step, row0, row_step, col_end = rpr;
+    if (p.WN == 1) {
+        // every wavefront has a K-slice of its own: it stages just that (no other wavefront reads it, no barrier)
+        col0 = wk * p.sc; col_step = 1; col_end = col0 + p.sc; row0 = 0; row_step = 1;
+    } else if (rpr >= nwaves) {
+        col0 = wave; col_step = nwaves; row0 = 0; row_step = 1;
+    } else {
+        // fewer runs per row than wavefronts: stage_row_step = nwaves / rpr wavefronts take the rows of one column run in turn
+        row0 = rpr == 1 ? wave : (int)__umulhi((uint32_t)wave, p.rpr_inv); row_step = p.stage_row_step;
+        col0 = wave - row0 * rpr; col_step = rpr;
+        if (row0 >= row_step) col_end = 0;                            // left-over wavefronts stage nothing
+    }
+    const uint32_t lane_off = lane * 16;
+    auto stage_issue = [&](int s, uint32_t buf_bytes) {
+        if (RP == 64 || lane < RP) {
+            for (int col = col0; col < col_end; col += col_step) {
+                const int w = p.sc == 1 ? col : (int)__umulhi((uint32_t)col, p.sc_inv), j = col - w * p.sc;
+                const int c0 = min(cb0 + w * p.per, cb1), c1 = min(c0 + p.per, cb1);
+                const int c = c0 + s * p.sc + j;
+                if (c < c1) {
+                    for (int row = row0; row < Mb; row += row_step) {
+                        const uint32_t soff = ((uint32_t)(m0 + row) * (uint32_t)p.K + (uint32_t)c * GM::CK) * 2u;
+                        const uint32_t ldsoff = buf_bytes + (uint32_t)(row * p.lds_stride + col * GM::CK) * 2u;
+                        if constexpr (MULTI) {
+                            uint32_t keep_m0;
+                            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                                         "buffer_load_dwordx4 %2, %3, %4 offen lds\n\ts_nop 0\n\ts_mov_b32 m0, %0"
+                                         : "=&s"(keep_m0) : "s"(ldsoff), "v"(lane_off), "s"(ra), "s"(soff) : "memory");
+                        } else {
+                            __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (__attribute__((address_space(3))) void*)(lds_bytes + ldsoff), 16,
+                                                                     lane_off, soff, 0, 0);
+                        }
+                    }
+                }
+            }
         }
-    };
-    auto stage_store = [&]() {
-#pragma unroll
-        for (int i = 0; i < kStagePieces; ++i)
-            if (stg_off[i] >= 0) *reinterpret_cast<u32x4_t*>(lds_a + stg_off[i]) = stg[i];
     };
 
     // ---- weight / scale prefetch: NB chunks in flight --------------------------------------------
@@ -219,44 +241,11 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& p, const int bx,
     };
 
     constexpr int LPC = ((NGC == 16) ? 2 : 1) * (ZP ? 2 : 1) + kChunkTiles;   // loads per fetch()
-    if constexpr (MULTI) {
-        stage_load(0, 0);                     // activation loads first: the oldest loads in flight
+    stage_issue(0, 0u);                   // activation loads first: the oldest loads in flight
 #pragma unroll
-        for (int j = 0; j < NB; ++j) fetch(j, cw0 + j);
-        stage_store();
-    } else {
-        // The whole slice goes global -> LDS directly (buffer_load ... lds, 16 bytes per lane, no registers): one
-        // instruction moves a run = one k-chunk of one staged row (64 lanes x 16 bytes at 4 bit, 32 lanes at 8 bit).
-        // Runs are dealt to the wavefronts by (column run, row) so that every address is wave-uniform arithmetic.
-        constexpr int RP = GM::CK / 8;
-        const int nwaves = nthreads >> 6;
-        const int rpr = p.WK << p.sc_shift;                           // runs per staged row
-        int col0, col_step, row0, row_step, col_end = rpr;
-        if (p.WN == 1) {
-            // every wavefront has a K-slice of its own: it stages just that (no other wavefront reads it, no barrier)
-            col0 = wk << p.sc_shift; col_step = 1; col_end = col0 + p.sc; row0 = 0; row_step = 1;
-        } else if (rpr >= nwaves) { col0 = wave; col_step = nwaves; row0 = 0; row_step = 1; }
-        else { col0 = (wk << p.sc_shift) + (wn & (p.sc - 1)); col_step = rpr; row0 = wn >> p.sc_shift; row_step = p.WN >> p.sc_shift; }
-        if (RP == 64 || lane < RP) {
-            const uint32_t lane_off = lane * 16;
-            for (int col = col0; col < col_end; col += col_step) {
-                const int w = col >> p.sc_shift, j = col & (p.sc - 1);
-                const int c0 = min(cb0 + w * p.per, cb1), c1 = min(c0 + p.per, cb1);
-                const int c = c0 + j;
-                if (c < c1) {
-                    for (int row = row0; row < Mb; row += row_step) {
-                        const uint32_t soff = ((uint32_t)(m0 + row) * (uint32_t)p.K + (uint32_t)c * GM::CK) * 2u;
-                        const uint32_t ldsoff = (uint32_t)(row * p.lds_stride + col * GM::CK) * 2u;
-                        __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (__attribute__((address_space(3))) void*)(lds_bytes + ldsoff), 16, lane_off, soff, 0, 0);
-                    }
-                }
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < NB; ++j) fetch(j, cw0 + j);
-        wait_vmcnt<NB * LPC>();               // the staging loads are older than the NB chunks just requested
-    }
-    if (MULTI || p.WN > 1) __syncthreads();
+    for (int j = 0; j < NB; ++j) fetch(j, cw0 + j);
+    wait_vmcnt<NB * LPC>();               // the staging loads are older than the NB chunks just requested
+    if (p.WN > 1) __syncthreads();        // (one wavefront along N: every wavefront reads only what it staged itself)
 
     // ---- main loop -------------------------------------------------------------------------------
     float4_t acc[MB];
@@ -264,14 +253,14 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& p, const int bx,
 #pragma unroll
     for (int b = 0; b < MB; ++b) {
         acc[b] = (float4_t){0.f, 0.f, 0.f, 0.f};
-        arow[b] = lds_a + min(b * 16 + nl, Mb - 1) * p.lds_stride + ((wk << p.sc_shift) * GM::CK) + kq * 8;
+        arow[b] = lds_a + min(b * 16 + nl, Mb - 1) * p.lds_stride + (wk * p.sc) * GM::CK + kq * 8;
     }
-    const half_t* adot = lds_a + ((wk << p.sc_shift) * GM::CK) + kq * 8;   // DOT: row 0 of this k-slot
+    const half_t* adot = lds_a + (wk * p.sc) * GM::CK + kq * 8;   // DOT: row 0 of this k-slot
     (void)adot;
     int ci = cw0;
     for (int s = 0; s < p.nstage; ++s) {
-        if constexpr (MULTI) stage_load(s + 1, 0);   // next stage's activations (out of range past the last)
-        int aoff = 0;
+        int aoff = MULTI ? (s & 1) * p.stage_halves : 0;              // which LDS buffer this stage reads
+        bool next_issued = !MULTI || s + 1 >= p.nstage;
         for (int u = 0; u < p.sc; u += NB) {
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
@@ -330,16 +319,23 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& p, const int bx,
                         }
                     }
                 }
+                if constexpr (MULTI) {
+                    // the next stage's activations, into the other buffer: issued after the stage's first chunk is consumed
+                    // (with one chunk in flight nothing is outstanding at this point, so no later wait sees these loads)
+                    if (!next_issued) {
+                        stage_issue(s + 1, (uint32_t)(((s + 1) & 1) * p.stage_halves) * 2u);
+                        next_issued = true;
+                    }
+                }
                 fetch(j, ci + NB);        // unconditional: out of range past the wavefront's share
                 aoff += GM::CK;
                 ++ci;
             }
         }
         if constexpr (MULTI) {
-            if (s + 1 < p.nstage) {       // uniform: swap in the next stage
-                __syncthreads();          // everyone is done reading this stage
-                stage_store();
-                __syncthreads();
+            if (s + 1 < p.nstage) {       // uniform: the next stage has landed, and everyone is done reading this one
+                wait_vmcnt<NB * LPC>();
+                if (p.WN > 1) __syncthreads();
             }
         }
     }
@@ -435,16 +431,16 @@ static int ilog2(int v) {
 
 // Geometry the kernel and the LDS budget share: chunks per wavefront, chunks per wavefront per
 // activation stage (power of two, multiple of the prefetch depth), number of stages.  A slice that
-// fits kSingleStageLds is staged at once (any number of rounds); otherwise stages are sized so that
-// one round of kStagePieces pieces per thread moves a stage and it stays within kMultiStageLds.
-constexpr size_t kSingleStageLds = 64 * 1024 + 1024;
+// fits kSingleStageLds is staged at once; otherwise it is staged in two alternating LDS buffers of at
+// most kMultiStageLds each (so that two workgroups still share a compute unit).
+constexpr size_t kSingleStageLds = 150 * 1024;         // direct-to-LDS staging needs no registers: one stage may take (almost) the whole LDS
 constexpr size_t kMultiStageLds = 32 * 1024 + 1024;
 constexpr size_t kMultiStageLdsWide = 72 * 1024;       // more than 16 activation rows: one chunk of 64 rows
 
 struct StageGeom {
-    int per, sc, nstage, rows, rounds;
+    int per, sc, nstage, rows;
     bool multi, fits;
-    size_t lds;
+    size_t lds, stage_bytes;
 };
 
 static StageGeom stage_geometry(const LinearArgs& a, const LinearPlan& p) {
@@ -455,31 +451,29 @@ static StageGeom stage_geometry(const LinearArgs& a, const LinearPlan& p) {
     g.per = (blk + p.waves_k - 1) / p.waves_k;
     const int mrows = 16 * p.m_rows16;                               // batch rows per workgroup
     g.rows = (int)(a.M < mrows ? a.M : mrows);
-    const int nthreads = 64 * p.waves_n * p.waves_k;
     const size_t red = p.waves_k > 1 ? (size_t)(p.waves_k - 1) * p.waves_n * p.m_rows16 * 1024 : 0;
-    auto bytes_of = [&](int sc) { return (size_t)g.rows * ((size_t)p.waves_k * sc * ck + kLdsPadHalves) * 2; };
-    auto pieces_of = [&](int sc) { return (int64_t)g.rows * p.waves_k * sc * (ck / 8); };
-    int sc_full = p.prefetch;
-    while (sc_full < g.per) sc_full *= 2;                             // whole share in one stage
+    auto bytes_of = [&](int sc) { return ((size_t)g.rows * ((size_t)p.waves_k * sc * ck + kLdsPadHalves) * 2 + 15) & ~(size_t)15; };
+    const int sc_full = g.per;                                        // whole share in one stage
     int sc = sc_full;
     g.fits = true;
     g.multi = false;
     if (bytes_of(sc_full) > kSingleStageLds) {
-        // largest stage that one round moves and that leaves room for several workgroups per CU
-        int m = sc_full / 2;
+        // largest stage within the budget; failing that, the smallest one if two of it still fit the LDS
+        int m = 1;
+        while (m * 2 < sc_full) m *= 2;                               // stages of a power of two of chunks
         const size_t budget = g.rows > 16 ? kMultiStageLdsWide : kMultiStageLds;
-        while (m >= p.prefetch && (bytes_of(m) > budget || pieces_of(m) > (int64_t)nthreads * kStagePieces)) m /= 2;
-        if (m >= p.prefetch && m > 0) {
+        while (m > p.prefetch && bytes_of(m) > budget) m /= 2;
+        if (m >= p.prefetch && m > 0 && 2 * bytes_of(m) <= kMaxLdsBytes) {
             g.multi = true;
             sc = m;
         } else {
-            g.fits = bytes_of(sc_full) <= kMaxLdsBytes;               // one large stage, several rounds
+            g.fits = bytes_of(sc_full) <= kMaxLdsBytes;               // one large stage
         }
     }
     g.sc = sc;
     g.nstage = g.multi ? (g.per + sc - 1) / sc : 1;
-    g.rounds = (int)((pieces_of(sc) + (int64_t)nthreads * kStagePieces - 1) / ((int64_t)nthreads * kStagePieces));
-    const size_t bytes = bytes_of(sc);
+    g.stage_bytes = bytes_of(sc);
+    const size_t bytes = g.multi ? 2 * g.stage_bytes : g.stage_bytes;
     g.lds = bytes > red ? bytes : red;
     return g;
 }
@@ -624,11 +618,11 @@ static SkinnyLaunch prepare_skinny(const LinearArgs& a, const LinearPlan& p) {
     const StageGeom sgm = stage_geometry(a, p);
     sp.per = sgm.per;
     sp.sc = sgm.sc;
-    sp.sc_shift = ilog2(sgm.sc);
+    sp.sc_inv = sgm.sc == 1 ? 0u : (uint32_t)(((uint64_t)1 << 32) / (uint32_t)sgm.sc) + 1u;
+    sp.rpr_inv = p.waves_k * sgm.sc == 1 ? 0u : (uint32_t)(((uint64_t)1 << 32) / (uint32_t)(p.waves_k * sgm.sc)) + 1u;
+    sp.stage_row_step = (p.waves_n * p.waves_k) / (p.waves_k * sgm.sc) > 0 ? (p.waves_n * p.waves_k) / (p.waves_k * sgm.sc) : 1;
     sp.nstage = sgm.nstage;
-    sp.stage_rounds = sgm.rounds;
-    sp.srp = p.waves_k * sgm.sc * (ck / 8);
-    sp.srp_inv = (uint32_t)(((uint64_t)1 << 32) / (uint32_t)sp.srp) + 1u;
+    sp.stage_halves = (int)(sgm.stage_bytes / 2);
     sp.lds_stride = p.waves_k * sgm.sc * ck + kLdsPadHalves;
     sp.qw_bytes = (uint32_t)((size_t)a.N * a.K * a.bits / 8);
     sp.sc_bytes = (uint32_t)((size_t)a.N * sp.G * 2);
