@@ -41,6 +41,7 @@ CACHE_BYTES = 256e6
 # "traffic_bytes_per_launch: <n>", which is read at run time (null if the summary is not there).
 TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "skinny_mfma_llama8b_w4a16_hbm_traffic.txt")
 W8_BATCHES = (1, 4, 16, 64)
+WARM_MS = float(os.environ.get("RTN_BENCH_WARM_MS", "200"))      # untimed work before each event-bracketed measurement
 
 
 def _measured_traffic():
@@ -51,6 +52,32 @@ def _measured_traffic():
     except OSError:
         pass
     return None
+
+
+def _bracket_us(torch, np, run, samples):
+    """Microseconds one run() takes on the GPU: a pair of events brackets enough back-to-back runs for about 4 ms of work,
+    so that the fixed cost of the first submission (some 10 us, which the bracket cannot avoid) stays under half a percent;
+    median of `samples` brackets."""
+    run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    run()
+    e1.record()
+    torch.cuda.synchronize()
+    once_ms = max(e0.elapsed_time(e1), 1e-3)
+    rounds = int(min(64, max(1, np.ceil(4.0 / once_ms))))
+    for _ in range(int(min(256, np.ceil(WARM_MS / once_ms)))):      # clocks settle before anything is timed
+        run()
+    ts = []
+    for _ in range(samples):
+        e0.record()
+        for _ in range(rounds):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1) * 1e3 / rounds)
+    return float(np.median(ts))
 
 
 def _time_linear(rtn, torch, np, A, qws, sc, bits, g, cfg, ws, reps=3, graph=True):
@@ -78,17 +105,7 @@ def _time_linear(rtn, torch, np, A, qws, sc, bits, g, cfg, ws, reps=3, graph=Tru
     else:
         run = issue
     n = reps * len(qws)
-    run()
-    torch.cuda.synchronize()
-    ts = []
-    for _ in range(5 if graph else 1):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        run()
-        e1.record()
-        torch.cuda.synchronize()
-        ts.append(e0.elapsed_time(e1) * 1e3 / n)
-    return float(np.median(ts))
+    return _bracket_us(torch, np, run, 5 if graph else 1) / n
 
 
 def _read_ceiling_us(rtn, torch, np, nbytes, pool, sink, kib_options=(4, 8, 16)):
@@ -96,6 +113,8 @@ def _read_ceiling_us(rtn, torch, np, nbytes, pool, sink, kib_options=(4, 8, 16))
     linear launches: HIP-graph replay of back-to-back launches that rotate over distinct regions of `pool` (>= 600 MB in
     total, or the pool), median of 5 replays; the best of the KiB-per-wavefront settings tried."""
     nbytes = (int(nbytes) + 1023) // 1024 * 1024
+    if nbytes > pool.numel():
+        raise ValueError(f"read ceiling: {nbytes} bytes asked of a pool of {pool.numel()}")
     copies = max(1, min(int(pool.numel() // nbytes), max(2, int(np.ceil(600e6 / nbytes)))))
     views = [pool[c * nbytes:(c + 1) * nbytes] for c in range(copies)]
     reps = 3
@@ -112,23 +131,13 @@ def _read_ceiling_us(rtn, torch, np, nbytes, pool, sink, kib_options=(4, 8, 16))
         with torch.cuda.stream(st):
             with torch.cuda.graph(cg, stream=st):
                 issue()
-        cg.replay()
-        torch.cuda.synchronize()
-        ts = []
-        for _ in range(5):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            cg.replay()
-            e1.record()
-            torch.cuda.synchronize()
-            ts.append(e0.elapsed_time(e1) * 1e3 / (reps * copies))
-        t = float(np.median(ts))
+        t = _bracket_us(torch, np, cg.replay, 5) / (reps * copies)
         best = t if best is None else min(best, t)
     return best
 
 
-def _ceiling_pool(torch, dev):
-    pool = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+def _ceiling_pool(torch, dev, nbytes=1 << 30):
+    pool = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     pool.fill_(1)
     return pool, torch.zeros(16, dtype=torch.uint8, device=dev)
 
@@ -136,7 +145,7 @@ def _ceiling_pool(torch, dev):
 def report_ceiling(args, rtn, synth, torch, np, dev) -> int:
     """The read-stream ceiling: a plain 16-byte-per-lane read kernel timed on buffers of exactly the packed size (codes +
     scales) of every matrix of every workload, and on 512 MB, under the same graph-replay protocol as the linear launches."""
-    pool, sink = _ceiling_pool(torch, dev)
+    pool, sink = _ceiling_pool(torch, dev, 2 << 30)        # the largest matrix here (405B gate_up at 8 bit) is 1.75 GB
     print("# plain read kernel (rtn_bench_read_stream): us per launch, HIP-graph replay, launches rotate over >= 600 MB of a 1 GiB "
           "buffer; best of 4 / 8 / 16 KiB per wavefront; sizes = packed codes + scales of each matrix")
     t512 = _read_ceiling_us(rtn, torch, np, 512e6, pool, sink)
@@ -169,7 +178,8 @@ def report(args, rtn, synth, torch, np, dev) -> int:
     tot = {M: 0.0 for M in Ms}
     totb = 0
     ceil_t = 0.0
-    pool, sink = _ceiling_pool(torch, dev)
+    largest = max(N * K for K, N in shapes.values()) + (2 << 20)          # an int8 matrix plus its scales
+    pool, sink = _ceiling_pool(torch, dev, max(1 << 30, (largest + 1023) // 1024 * 1024))
     what = ("selective precision: qkv and gate_up int4 group 128, o and down int8 per-channel" if args.selective
             else f"int{args.bits} {'group 128' if args.bits == 4 else 'per-channel'}")
     print(f"# {args.report} shapes, {what}; launches rotate over >= 600 MB of "
@@ -397,10 +407,12 @@ def report_grouped(args, rtn, synth, torch, np, dev) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=60)
-    ap.add_argument("--warmup", type=int, default=12)
+    ap.add_argument("--steps", type=int, default=3000)
+    ap.add_argument("--warmup", type=int, default=2000)
     ap.add_argument("--no-graph", action="store_true", help="launch every step directly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="time the int4 layer set alone: no read-stream ceiling, no W8A16 layer set, no CPU baseline (for profiler runs)")
     ap.add_argument("--report", choices=["8b", "70b", "405b"], default=None,
                     help="instead of the JSON line, print a per-matrix, per-M table for that model's shapes")
     ap.add_argument("--report-quantize", choices=["8b", "70b", "405b"], default=None,
@@ -570,12 +582,14 @@ def main() -> int:
                 "algorithmic_bytes_per_launch": round(algo_bytes / n_launch, 1)}
 
     # ---- read-stream ceiling: a plain read kernel on buffers of the four matrices' packed sizes, same protocol ----
-    pool, sink = _ceiling_pool(torch, dev)
-    ceil_us = [_read_ceiling_us(rtn, torch, np, q.numel() + s.numel() * 2, pool, sink) for q, s in packed]
-    t512 = _read_ceiling_us(rtn, torch, np, 512e6, pool, sink)
-    del pool
-    read_ceiling_gbs = layer_bytes / sum(ceil_us) / 1e3
-    roofline["read_ceiling"] = {"layer_set_GB/s": round(read_ceiling_gbs, 1), "layer_set_us": round(sum(ceil_us), 2),
+    read_ceiling_gbs = None
+    if not args.headline_only:
+        pool, sink = _ceiling_pool(torch, dev)
+        ceil_us = [_read_ceiling_us(rtn, torch, np, q.numel() + s.numel() * 2, pool, sink) for q, s in packed]
+        t512 = _read_ceiling_us(rtn, torch, np, 512e6, pool, sink)
+        del pool
+        read_ceiling_gbs = layer_bytes / sum(ceil_us) / 1e3
+        roofline["read_ceiling"] = {"layer_set_GB/s": round(read_ceiling_gbs, 1), "layer_set_us": round(sum(ceil_us), 2),
                                 "per_matrix_us": [round(t, 2) for t in ceil_us], "stream_512MB_GB/s": round(512e6 / t512 / 1e3, 1),
                                 "kernel": "rtn::read_stream_kernel (16 bytes per lane, nothing else), graph replay, rotating buffers"}
 
@@ -584,7 +598,7 @@ def main() -> int:
     w8_layer_bytes = 0
     w8_times = {M: 0.0 for M in W8_BATCHES}
     ws_big = torch.empty(64 << 20, dtype=torch.uint8, device=dev)
-    for i, (name, (K, N)) in enumerate(modules):
+    for i, (name, (K, N)) in enumerate(() if args.headline_only else modules):
         w = synth.normal_weight(N, K, 0.02, seed=i, device=dev)
         q8, s8 = rtn.rtn_quantize(w, 8, 0)
         del w
@@ -595,13 +609,13 @@ def main() -> int:
             A8 = synth.activation(M, K, seed=100 + M, device=dev)
             w8_times[M] += _time_linear(rtn, torch, np, A8, q8s, s8, 8, 0, None, ws_big)
         del q8s, q8
-    for M in W8_BATCHES:
+    for M in () if args.headline_only else W8_BATCHES:
         w8[f"M{M}"] = {"layer_set_us": round(w8_times[M], 2), "GB/s": round(w8_layer_bytes / w8_times[M] / 1e3, 1),
                        "pct_hbm_peak": round(w8_layer_bytes / w8_times[M] / 80e3, 2)}
 
     # ---- CPU oracle timed beside it (bounded sample of the same workload) ------------------------
     cpu = None
-    if not args.no_cpu_baseline:
+    if not (args.no_cpu_baseline or args.headline_only):
         from oracle import rtn_oracle as O
         try:
             from threadpoolctl import threadpool_info
@@ -639,9 +653,9 @@ def main() -> int:
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "tflops": round(flops / (ms_per_step * 1e-3) / 1e12, 3),
         "weight_bytes_per_step": int(step_weight_bytes),
-        "read_ceiling_gbs": round(read_ceiling_gbs, 1),
-        "value_over_read_ceiling": round(value / read_ceiling_gbs, 4),
-        "extra": {"w8a16_llama8b_int8_per_channel_layer_set": w8,
+        "read_ceiling_gbs": round(read_ceiling_gbs, 1) if read_ceiling_gbs else None,
+        "value_over_read_ceiling": round(value / read_ceiling_gbs, 4) if read_ceiling_gbs else None,
+        "extra": {"w8a16_llama8b_int8_per_channel_layer_set": w8 or None,
                   "w8a16_note": "same four modules, symmetric RTN int8 with per-output-channel scales; per-matrix HIP-graph replay over "
                                 ">= 600 MB of rotating packed copies, layer set = sum of the four"},
         "roofline": roofline,

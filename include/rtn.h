@@ -146,7 +146,7 @@ typedef struct {
                       256 x 256 output tiles, weights dequantised to fp16 in LDS (group_size a multiple of 128; uses split_k and
                       m_rows16 = 4 or 8 for the tile height, 0 = chosen from M) */
     int prefetch;  /* k-chunks (4 KiB each) a wavefront keeps in flight: 1, 2 or 4 */
-    int waves_n;   /* wavefronts of a workgroup along N (share the staged activations): 1, 2, 4, 8, 16 (a power of two) */
+    int waves_n;   /* wavefronts of a workgroup along N (share the staged activations): 1 .. 16 */
     int waves_k;   /* wavefronts of a workgroup along K (in-workgroup split-K): 1 .. 16; waves_n * waves_k <= 16 */
     int split_k;   /* workgroups along K (global split-K, reduced through the workspace) */
     int m_rows16;  /* 16-row activation blocks each wavefront multiplies per weight tile: 1, 2 or 4 (path 3: 2, 3, 4, 8) */

@@ -214,6 +214,8 @@ def rtn_linear_noalloc(A: torch.Tensor, qweight: torch.Tensor, scales: torch.Ten
 
 def rtn_bench_read_stream(buf: torch.Tensor, nbytes: int, kib_per_wavefront: int, sink: torch.Tensor):
     """Measurement hook: streams the first nbytes of buf once with a plain read kernel."""
+    if buf.numel() * buf.element_size() < nbytes or sink.numel() * sink.element_size() < 4:
+        raise ValueError(f"rtn_bench_read_stream: buffer of {buf.numel() * buf.element_size()} bytes, asked to read {nbytes}")
     _check(_lib.rtn_bench_read_stream(buf.data_ptr(), nbytes, kib_per_wavefront, sink.data_ptr(), _stream()),
            "rtn_bench_read_stream")
 

@@ -233,7 +233,7 @@ const SkinnyPlanEntry kSkinnyPlanTable[] = {
 
 bool skinny_plan_usable(int64_t M, int64_t N, int64_t K, int bits, const LinearPlan& p, size_t lds_limit) {
     const int64_t KC = K / chunk_k(bits);
-    if (p.waves_n < 1 || !pow2(p.waves_n) || p.waves_k < 1 || p.waves_n * p.waves_k > 16) return false;
+    if (p.waves_n < 1 || p.waves_k < 1 || p.waves_n * p.waves_k > 16) return false;
     if (p.split_k < 1 || p.split_k > kMaxSplitK || p.split_k > KC) return false;
     if (p.split_k > 1 && (size_t)M * N * sizeof(float) * p.split_k > kWorkspaceCap) return false;
     LinearArgs a;
@@ -247,6 +247,7 @@ bool skinny_plan_usable(int64_t M, int64_t N, int64_t K, int bits, const LinearP
 // two, the best case, so a configuration's measured slowdown is corrected by this ratio to the power 0.7 (fitted on
 // shapes outside the table), entry against problem.
 constexpr double kImbalanceExp = 0.7;
+constexpr double kWidthStep = 0.3;      // log-time per octave of workgroup width away from a voted configuration
 double cu_imbalance(int64_t workgroups) {
     const double avg = (double)workgroups / 256.0;
     return std::ceil(avg) / avg;
@@ -273,16 +274,22 @@ bool skinny_plan_from_table(int64_t M, int64_t N, int64_t K, int bits, size_t ld
     }
     if (found == 0) return false;
     if (near_d[0] < 1e-9) found = 1;                            // the problem itself is in the table: its own ranking
-    struct Scored { SkinnyPlanConfig c; double score; };
-    Scored cand[kVoters * kPlanEntryConfigs];
-    int nc = 0;
+    struct Scored { SkinnyPlanConfig c; double base, score; };
+    std::vector<Scored> cand;
+    cand.reserve(kVoters * kPlanEntryConfigs * 8);
     const double kMissing = std::log(1.5);
+    const int64_t NT = N / 16;
+    auto same = [](const SkinnyPlanConfig& a, const SkinnyPlanConfig& b) {
+        return a.wn == b.wn && a.wk == b.wk && a.split == b.split && a.nb == b.nb;
+    };
+    auto imbalance_of = [](int64_t nt, const SkinnyPlanConfig& c) {
+        return std::log(cu_imbalance(((nt + c.wn - 1) / c.wn) * c.split));
+    };
     for (int v = 0; v < found; ++v) {
         const SkinnyPlanEntry& e = kSkinnyPlanTable[near_i[v]];
         for (int k = 0; k < e.n; ++k) {
             bool seen = false;
-            for (int q = 0; q < nc && !seen; ++q)
-                seen = cand[q].c.wn == e.c[k].wn && cand[q].c.wk == e.c[k].wk && cand[q].c.split == e.c[k].split && cand[q].c.nb == e.c[k].nb;
+            for (size_t q = 0; q < cand.size() && !seen; ++q) seen = same(cand[q].c, e.c[k]);
             if (seen) continue;
             double num = 0.0, den = 0.0;
             for (int u = 0; u < found; ++u) {
@@ -290,21 +297,46 @@ bool skinny_plan_from_table(int64_t M, int64_t N, int64_t K, int bits, size_t ld
                 const double w = 1.0 / (near_d[u] + 0.25);
                 double ls = kMissing;
                 for (int q = 0; q < f.n; ++q)
-                    if (f.c[q].wn == e.c[k].wn && f.c[q].wk == e.c[k].wk && f.c[q].split == e.c[k].split && f.c[q].nb == e.c[k].nb) {
+                    if (same(f.c[q], e.c[k])) {
                         ls = std::min(kMissing, std::log(1.0 + f.c[q].slow / 200.0));
                         break;
                     }
                 // the entry's own workgroup-count imbalance is taken out of its measurement ...
-                ls -= kImbalanceExp * std::log(cu_imbalance((int64_t)((f.nt + e.c[k].wn - 1) / e.c[k].wn) * e.c[k].split));
+                ls -= kImbalanceExp * imbalance_of(f.nt, e.c[k]);
                 num += w * ls; den += w;
             }
-            cand[nc].c = e.c[k];
             // ... and the problem's own put in; ties: the order of the nearer entry
-            cand[nc].score = num / den + kImbalanceExp * std::log(cu_imbalance(((N / 16 + e.c[k].wn - 1) / e.c[k].wn) * e.c[k].split)) + 1e-9 * nc;
-            ++nc;
+            const double base = num / den;
+            cand.push_back({e.c[k], base, base + kImbalanceExp * imbalance_of(NT, e.c[k]) + 1e-9 * (double)cand.size()});
         }
     }
-    std::sort(cand, cand + nc, [](const Scored& a, const Scored& b) { return a.score < b.score; });
+    // Workgroup width follows the problem, not the table: a voted configuration one or two wavefronts deep along K also
+    // stands for its neighbours with any other number of wavefronts along N (1 .. 16 / waves_k), scored as itself with
+    // the neighbour's workgroup-count imbalance and kWidthStep per octave of width moved.  The table's grid has powers
+    // of two of tile-rows, where powers of two of wavefronts always divide evenly; a matrix of, say, 2153 tile-rows
+    // is served 25-35 % faster at 16 rows by nine wavefronts (240 workgroups) than by eight (270, a second round on
+    // fourteen compute units).  Not applied when the problem itself is in the table.
+    if (found > 1) {
+        const size_t voted = cand.size();
+        for (size_t q = 0; q < voted; ++q) {
+            const SkinnyPlanConfig c = cand[q].c;
+            if (c.wk > 2 || c.split > 4 || (c.wk == 1 && c.nb == 1 && c.split > 1) || (c.wk == 2 && c.split > 2)) continue;
+            for (int w2 = 1; w2 <= 16 / c.wk; ++w2) {
+                if (w2 == c.wn || w2 > NT) continue;
+                SkinnyPlanConfig c2 = c;
+                c2.wn = (uint8_t)w2;
+                const double sc = cand[q].base + kImbalanceExp * imbalance_of(NT, c2) +
+                                  kWidthStep * std::fabs(std::log2((double)w2 / c.wn)) + 1e-6;
+                size_t at = 0;
+                while (at < cand.size() && !same(cand[at].c, c2)) ++at;
+                if (at < voted) continue;                            // voted on directly
+                if (at == cand.size()) cand.push_back({c2, cand[q].base, sc});
+                else if (sc < cand[at].score) cand[at].score = sc;
+            }
+        }
+    }
+    const int nc = (int)cand.size();
+    std::sort(cand.begin(), cand.end(), [](const Scored& a, const Scored& b) { return a.score < b.score; });
     for (int q = 0; q < nc; ++q) {
         LinearPlan p;
         p.path = 1; p.n_tiles16 = 1; p.m_rows16 = 1; p.m_blocks = 1;
@@ -378,7 +410,30 @@ LinearPlan auto_plan(int64_t M, int64_t N, int64_t K, int bits, int64_t g, size_
         wide_plan(M, N, K, bits, &p);
         return p;
     }
-    if (M <= 16 && steps_hint == 0 && skinny_plan_from_table(M, N, K, bits, lds_limit, &p)) return p;
+    if (M <= 16 && steps_hint == 0) {
+        // the table lookup costs tens of microseconds of host time (logarithms over ~800 entries): remembered per problem
+        struct Key { int64_t M, N, K; int bits; size_t lds; };
+        struct Memo { Key k; LinearPlan p; bool ok; };
+        static std::mutex memo_mutex;
+        static std::vector<Memo> memo;
+        {
+            std::lock_guard<std::mutex> lock(memo_mutex);
+            for (const Memo& m : memo)
+                if (m.k.M == M && m.k.N == N && m.k.K == K && m.k.bits == bits && m.k.lds == lds_limit) {
+                    if (m.ok) return m.p;
+                    goto rules;
+                }
+        }
+        {
+            const bool ok = skinny_plan_from_table(M, N, K, bits, lds_limit, &p);
+            std::lock_guard<std::mutex> lock(memo_mutex);
+            if (memo.size() >= 4096) memo.clear();              // a serving process sees a handful of shapes; bound it anyway
+            memo.push_back({{M, N, K, bits, lds_limit}, p, ok});
+            if (ok) return p;
+        }
+    }
+rules:
+    p.n_tiles16 = 1;
     // (no usable table entry, more than 16 rows on this kernel, or a slice of a grouped launch: the rules below)
     const int64_t NT = N / 16, KC = K / chunk_k(bits);
     // 4 KiB chunk-steps in the whole matrix, or in everything that shares the launch (grouped call)
@@ -527,7 +582,7 @@ rtn_status resolve_plan(const LinearArgs& a, const rtn_linear_cfg* cfg, size_t w
     if (p.prefetch != 1 && p.prefetch != 2 && p.prefetch != 4) return RTN_ERR_CONFIG;
     if (p.m_rows16 != 1 && p.m_rows16 != 2 && p.m_rows16 != 4) return RTN_ERR_CONFIG;
     if (p.m_rows16 > 1 && p.prefetch != 1) return RTN_ERR_CONFIG;
-    if (!pow2(p.waves_n) || p.waves_k < 1 || p.waves_n * p.waves_k > 16) return RTN_ERR_CONFIG;
+    if (p.waves_n < 1 || p.waves_k < 1 || p.waves_n * p.waves_k > 16) return RTN_ERR_CONFIG;
     if (p.split_k < 1 || p.split_k > kMaxSplitK || p.split_k > KC) return RTN_ERR_CONFIG;
     if (!rtn::linear_plan_fits(a, p, lds_limit)) return RTN_ERR_CONFIG;
     if ((uint64_t)a.N * a.K * a.bits / 8 >= 0x7FFF0000ull || (uint64_t)a.M * a.K * 2 >= 0x7FFF0000ull)

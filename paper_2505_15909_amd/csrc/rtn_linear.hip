@@ -61,7 +61,8 @@ struct SkinnyParams {
     int NT;           // N / 16
     int KL;           // tiles per row
     int KC;           // chunks per row
-    int WN, WK, wn_shift, wk_shift;   // wave = wk * WN + wn
+    int WN, WK;            // wave = wk * WN + wn; any WN x WK <= 16
+    uint32_t wn_inv;       // floor(2^32 / WN) + 1: wave -> wk by multiply-high (unused when WN == 1)
     int split_k;
     int kc_base, kc_rem;   // workgroup sg covers chunks [sg*kc_base + min(sg, kc_rem), ...): KC split evenly
     uint32_t cpg_inv;      // floor(2^32 / (g / CK)) + 1 when g > CK (0 when g == CK): chunk -> group by multiply-high
@@ -146,7 +147,7 @@ __device__ __forceinline__ void skinny_body(const SkinnyParams& p, const int bx,
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform, kept scalar
-    const int wn = wave & (p.WN - 1), wk = wave >> p.wn_shift;
+    const int wk = p.WN == 1 ? wave : (int)__umulhi((uint32_t)wave, p.wn_inv), wn = wave - wk * p.WN;   // scalar
     const int nl = lane & 15, kq = lane >> 4;
     const int nthreads = blockDim.x;
 
@@ -423,12 +424,6 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     *reinterpret_cast<half4_t*>(C + i) = h;
 }
 
-static int ilog2(int v) {
-    int s = 0;
-    while ((1 << s) < v) ++s;
-    return s;
-}
-
 // Geometry the kernel and the LDS budget share: chunks per wavefront, chunks per wavefront per
 // activation stage (power of two, multiple of the prefetch depth), number of stages.  A slice that
 // fits kSingleStageLds is staged at once; otherwise it is staged in two alternating LDS buffers of at
@@ -606,8 +601,7 @@ static SkinnyLaunch prepare_skinny(const LinearArgs& a, const LinearPlan& p) {
     sp.KL = (int)(a.K / tk);
     sp.KC = (int)(a.K / ck);
     sp.WN = p.waves_n; sp.WK = p.waves_k;
-    sp.wn_shift = ilog2(p.waves_n);
-    sp.wk_shift = ilog2(p.waves_k);
+    sp.wn_inv = p.waves_n == 1 ? 0u : (uint32_t)(((uint64_t)1 << 32) / (uint32_t)p.waves_n) + 1u;
     sp.split_k = p.split_k;
     sp.kc_base = sp.KC / p.split_k;
     sp.kc_rem = sp.KC % p.split_k;

@@ -148,7 +148,9 @@ def _oracle_operands(N, K, bits, g, seed, dist="normal02"):
 CFGS = [dict(prefetch=nb, waves_n=wn, waves_k=wk, split_k=sk)
         for nb, wn, wk, sk in [(1, 1, 1, 1), (1, 1, 4, 1), (2, 1, 2, 2), (1, 2, 2, 1), (2, 2, 1, 3), (2, 1, 1, 1),
                                (1, 4, 1, 1), (2, 4, 2, 2), (2, 4, 1, 1), (1, 1, 8, 1), (1, 8, 1, 2), (2, 2, 4, 4),
-                               (1, 1, 16, 1), (2, 16, 1, 1), (1, 2, 8, 1), (2, 8, 2, 1), (1, 1, 3, 1), (1, 2, 7, 1), (2, 1, 5, 2)]]
+                               (1, 1, 16, 1), (2, 16, 1, 1), (1, 2, 8, 1), (2, 8, 2, 1), (1, 1, 3, 1), (1, 2, 7, 1), (2, 1, 5, 2),
+                               # any number of wavefronts along N, not only powers of two
+                               (2, 3, 1, 1), (1, 7, 1, 1), (2, 13, 1, 2), (2, 5, 3, 1), (1, 3, 5, 2), (2, 6, 2, 3), (2, 15, 1, 1)]]
 
 
 @pytest.mark.parametrize("bits,g", [(4, 32), (4, 64), (4, 128), (4, 256), (4, 512), (4, 0), (8, 32), (8, 64), (8, 128),
