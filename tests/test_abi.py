@@ -366,6 +366,22 @@ def test_plans_of_untuned_shapes_fill_the_compute_units_evenly():
         assert (q["waves_n"], q["waves_k"], q["split_k"], q["prefetch"]) == best[(bits, K, N, M)], (bits, K, N, M, q)
 
 
+def test_size_limits_are_refused_on_the_host():
+    """The kernels address every tensor with 32-bit byte offsets: a packed weight tensor or an activation tensor of
+    2 GiB - 64 KiB or more, more than 2^20 rows, or 2^23 columns and more are refused with RTN_ERR_SHAPE before anything
+    is launched; one step inside each limit passes.  Host-only validation entry point: no pointers, no launch."""
+    def status(M, N, K, bits, g):
+        return lib.rtn_linear_validate(M, N, K, bits, g, 256 << 20, None)
+    assert status(1, 65536, 65536, 4, 128) == 4 and status(1, 65536, 65536 - 512, 4, 128) == 0       # 2 GiB of int4 codes
+    assert status(1, 32768, 65536, 8, 0) == 4 and status(1, 32768, 65536 - 256, 8, 0) == 0           # 2 GiB of int8 codes
+    assert status(1, 16, 1 << 23, 4, 128) == 4 and status(1, 16, (1 << 23) - 512, 4, 128) == 0       # columns
+    assert status((1 << 20) + 1, 16, 512, 4, 128) == 4 and status(1 << 20, 16, 512, 4, 128) == 0     # rows
+    assert status(40000, 16, 32768, 4, 128) == 4                                                     # activations of 2.4 GiB
+    with pytest.raises(rtn.RtnError) as e:
+        rtn.rtn_linear_query(1, 65536, 65536, 4, 128)
+    assert e.value.status == 4
+
+
 def test_bench_refuses_more_than_one_gpu():
     """This build measures one GPU; asking the benchmark for more exits with a message before touching a device."""
     import subprocess
