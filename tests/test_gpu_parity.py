@@ -509,6 +509,46 @@ def test_linear_automatic_plans_on_large_random_shapes(rtn):
     assert {p for p, _, _ in seen} == {3, 4} and any(r == 8 for _, r, _ in seen) and any(s for _, _, s in seen), seen
 
 
+def test_linear_automatic_plans_at_small_batches_on_irregular_shapes(rtn):
+    """What rtn_linear chooses by itself at 1-16 rows on shapes outside its measured plan table (the held-out files of
+    the tuning folder: tile-row counts such as 2153 or 2763, for which the plan takes workgroups of 9, 11, 13 ... wavefronts
+    and K splits): a stripe of output columns (first and last tile-row, 96 random ones) against the oracle on the
+    unpacked codes, and run-to-run bit reproducibility."""
+    tuning = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2505_15909_amd", "tuning")
+    shapes = []
+    for name in ("shapes_heldout.txt", "shapes_heldout2.txt"):
+        for line in open(os.path.join(tuning, name)):
+            _, K, N = line.split()
+            shapes.append((int(K), int(N)))
+    rng = np.random.default_rng(11)
+    widths = set()
+    ws = torch.empty(16 << 20, dtype=torch.uint8, device=DEV)
+    for case, (K, N) in enumerate(shapes):
+        bits = 4 if case % 3 else 8
+        if K % (512 if bits == 4 else 256):
+            bits = 8
+        g = 128 if bits == 4 else 0
+        W_t = synth.normal_weight(N, K, 0.02, seed=case, device=DEV)
+        qw, sc = rtn.rtn_quantize(W_t, bits, g)
+        del W_t
+        sel = np.unique(np.concatenate([np.arange(0, 16), np.arange(N - 16, N), rng.integers(0, N, 96)]))
+        codes = _to_np(rtn.rtn_unpack(qw, N, K, bits))[sel]
+        scales = _to_np(sc)[sel]
+        for M in (1, 6, 16):
+            A_t = synth.activation(M, K, seed=case + 7 * M, device=DEV)
+            q = rtn.rtn_linear_query(M, N, K, bits, g)
+            assert q["path"] == 1
+            widths.add(q["waves_n"])
+            C = rtn.rtn_linear(A_t, qw, sc, bits, g, workspace=ws)
+            C2 = rtn.rtn_linear(A_t, qw, sc, bits, g, workspace=ws)
+            torch.cuda.synchronize()
+            assert torch.equal(C, C2)
+            ref = O.rtn_linear(_to_np(A_t), codes, scales, K if g == 0 else g)
+            H.assert_linear_close(_to_np(C)[:, sel], ref, f"case {case} bits={bits} M={M} N={N} K={K} plan={q}")
+        del qw, sc
+    assert any(w not in (1, 2, 4, 8, 16) for w in widths), widths      # the odd widths are exercised
+
+
 # ----------------------------------------------------------------------------------------
 # the paper-shaped configurations at full size: the 8B-shaped ones are compared against the oracle in full; for the
 # larger ones the oracle checks a stripe of 16-row tiles (rows of the weight matrix are independent); the GPU always
