@@ -430,9 +430,10 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 }
 
 // Geometry the kernel and the LDS budget share: chunks per wavefront, chunks per wavefront per
-// activation stage (power of two, multiple of the prefetch depth), number of stages.  A slice that
-// fits kSingleStageLds is staged at once; otherwise it is staged in two alternating LDS buffers of at
-// most kMultiStageLds each (so that two workgroups still share a compute unit).
+// activation stage, number of stages.  A slice that fits kSingleStageLds is staged at once (a
+// wavefront's exact share); otherwise it is staged a power of two of chunks at a time (at least the
+// prefetch depth) in two alternating LDS buffers of at most kMultiStageLds each (so that two
+// workgroups still share a compute unit).
 constexpr size_t kSingleStageLds = 150 * 1024;         // direct-to-LDS staging needs no registers: one stage may take (almost) the whole LDS
 constexpr size_t kMultiStageLds = 32 * 1024 + 1024;
 constexpr size_t kMultiStageLdsWide = 72 * 1024;       // more than 16 activation rows: one chunk of 64 rows
