@@ -109,7 +109,7 @@ def _time_linear(rtn, torch, np, A, qws, sc, bits, g, cfg, ws, reps=3, graph=Tru
     return _bracket_us(torch, np, run, 5 if graph else 1) / n
 
 
-def _read_ceiling_us(rtn, torch, np, nbytes, pool, sink, kib_options=(4, 8, 16)):
+def _read_ceiling_us(rtn, torch, np, nbytes, pool, sink, kib_options=(2, 4, 8)):
     """Microseconds a plain read kernel (rtn_bench_read_stream) takes per launch on nbytes, under the protocol of the
     linear launches: HIP-graph replay of back-to-back launches that rotate over distinct regions of `pool` (>= 600 MB in
     total, or the pool), median of 5 replays; the best of the KiB-per-wavefront settings tried."""
@@ -148,7 +148,7 @@ def report_ceiling(args, rtn, synth, torch, np, dev) -> int:
     scales) of every matrix of every workload, and on 512 MB, under the same graph-replay protocol as the linear launches."""
     pool, sink = _ceiling_pool(torch, dev, 2 << 30)        # the largest matrix here (405B gate_up at 8 bit) is 1.75 GB
     print("# plain read kernel (rtn_bench_read_stream): us per launch, HIP-graph replay, launches rotate over >= 600 MB of a 1 GiB "
-          "buffer; best of 4 / 8 / 16 KiB per wavefront; sizes = packed codes + scales of each matrix")
+          "buffer; best of 2 / 4 / 8 KiB per wavefront; sizes = packed codes + scales of each matrix")
     t512 = _read_ceiling_us(rtn, torch, np, 512e6, pool, sink)
     print(f"512 MB: {t512:8.2f} us  {512e6 / t512 / 1e3:7.0f} GB/s  {512e6 / t512 / 80e3:5.1f} % of 8 TB/s")
     for fam, shapes in (("8b", synth.LLAMA_8B), ("70b", synth.LLAMA_70B), ("405b", synth.LLAMA_405B)):
