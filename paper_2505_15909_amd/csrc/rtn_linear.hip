@@ -417,13 +417,38 @@ __global__ __launch_bounds__(1024) void skinny_grouped_kernel(const GroupedParam
     skinny_body<BITS, NGC, 1, MULTI, 1, false>(gp.p[g], b - gp.first_block[g], 0, 0);
 }
 
-// Sums the split-K partials in a fixed order and rounds once to fp16.
+// Sums the split-K partials in a fixed order (s = 0, 1, 2, ...) and rounds once to fp16.  The partials of a batch of up
+// to eight splits are requested together and summed as they arrive: a loop of load-wait-add takes one memory round trip
+// per split (4 us for four splits of a 16 x 4096 output, against 1.5 us for the whole kernel this way).
+// S > 0: exactly S splits (S <= 8), fully unrolled.  S = 0: any number, in batches of eight.
+template <int S>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ ws, half_t* __restrict__ C,
                                                             int64_t MN, int split_k) {
     const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
     if (i >= MN) return;                                  // MN is a multiple of 16
-    float4_t v = *reinterpret_cast<const float4_t*>(ws + i);
-    for (int s = 1; s < split_k; ++s) v += *reinterpret_cast<const float4_t*>(ws + (int64_t)s * MN + i);
+    const float* src = ws + i;
+    float4_t v;
+    if constexpr (S > 0) {
+        float4_t part[S];
+#pragma unroll
+        for (int s = 0; s < S; ++s) part[s] = *reinterpret_cast<const float4_t*>(src + (int64_t)s * MN);
+        v = part[0];
+#pragma unroll
+        for (int s = 1; s < S; ++s) v += part[s];
+    } else {
+        v = (float4_t){0.f, 0.f, 0.f, 0.f};
+        for (int s0 = 0; s0 < split_k; s0 += 8) {         // uniform
+            float4_t part[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)                   // past the last split: partial 0 again (a valid address), not added
+                part[u] = *reinterpret_cast<const float4_t*>(src + (int64_t)(s0 + u < split_k ? s0 + u : 0) * MN);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (s0 + u == 0) v = part[0];             // the first term starts the sum (no 0 + x: keeps the sign of zero)
+                else if (s0 + u < split_k) v += part[u];
+            }
+        }
+    }
     typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
     half4_t h = {(half_t)v[0], (half_t)v[1], (half_t)v[2], (half_t)v[3]};
     *reinterpret_cast<half4_t*>(C + i) = h;
@@ -729,7 +754,17 @@ hipError_t launch_linear_grouped(const LinearArgs* args, const LinearPlan* plans
 
 hipError_t launch_splitk_reduce(const float* workspace, void* C_fp16, int64_t MN, int split_k, hipStream_t st) {
     dim3 rgrid((unsigned)((MN / 4 + 255) / 256)), rblock(256);
-    hipLaunchKernelGGL(splitk_reduce_kernel, rgrid, rblock, 0, st, workspace, static_cast<half_t*>(C_fp16), MN, split_k);
+    half_t* C = static_cast<half_t*>(C_fp16);
+    switch (split_k) {
+        case 2: hipLaunchKernelGGL(splitk_reduce_kernel<2>, rgrid, rblock, 0, st, workspace, C, MN, split_k); break;
+        case 3: hipLaunchKernelGGL(splitk_reduce_kernel<3>, rgrid, rblock, 0, st, workspace, C, MN, split_k); break;
+        case 4: hipLaunchKernelGGL(splitk_reduce_kernel<4>, rgrid, rblock, 0, st, workspace, C, MN, split_k); break;
+        case 5: hipLaunchKernelGGL(splitk_reduce_kernel<5>, rgrid, rblock, 0, st, workspace, C, MN, split_k); break;
+        case 6: hipLaunchKernelGGL(splitk_reduce_kernel<6>, rgrid, rblock, 0, st, workspace, C, MN, split_k); break;
+        case 7: hipLaunchKernelGGL(splitk_reduce_kernel<7>, rgrid, rblock, 0, st, workspace, C, MN, split_k); break;
+        case 8: hipLaunchKernelGGL(splitk_reduce_kernel<8>, rgrid, rblock, 0, st, workspace, C, MN, split_k); break;
+        default: hipLaunchKernelGGL(splitk_reduce_kernel<0>, rgrid, rblock, 0, st, workspace, C, MN, split_k); break;
+    }
     return hipGetLastError();
 }
 
